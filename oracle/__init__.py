@@ -1,0 +1,241 @@
+"""CPU oracle for the SAME Gibbs LDA sweep: test infrastructure, not product code.
+
+Thin ctypes access to ``same_lda_oracle.c`` plus :class:`OracleLDA`, which strings
+the C steps together in the order of Algorithm 3 of the paper (zero, draw and
+accumulate, add priors, normalise over words, blend).  Nothing here imports the
+GPU package, and the GPU package never imports this.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from ctypes import POINTER, c_double, c_float, c_int32, c_int64, c_uint32, c_uint64, c_void_p
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "same_lda_oracle.c")
+_LIB = os.path.join(_HERE, "liboracle_same_lda.so")
+
+DOMAIN_TRAIN = 0
+DOMAIN_HELDOUT = 1
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (one rounding per operation: no contraction, no fast-math)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c99", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off",
+               "-fno-fast-math", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        L = ctypes.CDLL(build())
+        u32p, f32p, i32p, i64p = POINTER(c_uint32), POINTER(c_float), POINTER(c_int32), POINTER(c_int64)
+        L.oracle_philox4x32_10.argtypes = [u32p, u32p, u32p]
+        L.oracle_philox4x32_10.restype = None
+        L.oracle_uniform_from_word.argtypes = [c_uint32]
+        L.oracle_uniform_from_word.restype = c_float
+        L.oracle_stream_uniform.argtypes = [c_uint64, c_uint64, c_uint32, c_uint32, c_uint32]
+        L.oracle_stream_uniform.restype = c_float
+        L.oracle_ipow.argtypes = [c_float, c_uint32]
+        L.oracle_ipow.restype = c_float
+        L.oracle_binom_walk.argtypes = [c_uint32, c_float, c_float, c_float]
+        L.oracle_binom_walk.restype = c_uint32
+        L.oracle_binom.argtypes = [c_uint32, c_float, c_uint64, c_uint64, c_uint32, c_uint32]
+        L.oracle_binom.restype = c_uint32
+        L.oracle_draw.argtypes = [c_int32, f32p, c_uint32, c_uint64, c_uint64, c_uint32, u32p, f32p]
+        L.oracle_draw.restype = c_float
+        L.oracle_task_count.argtypes = [c_int64, f32p, c_int32]
+        L.oracle_task_count.restype = c_int64
+        L.oracle_task_base.argtypes = [c_int64, f32p, c_int32, i64p]
+        L.oracle_task_base.restype = None
+        L.oracle_pass.argtypes = [c_int32, c_int32, i32p, i32p, f32p, c_int32, c_int32, c_uint32,
+                                  c_uint64, c_uint32, c_void_p, c_void_p, u32p, c_void_p, c_void_p]
+        L.oracle_pass.restype = None
+        L.oracle_draw_tasks.argtypes = [c_int32, i32p, i32p, f32p, c_int32, c_int32, c_uint32, c_uint64,
+                                        c_uint32, c_void_p, c_void_p, c_int64, i64p, u32p]
+        L.oracle_draw_tasks.restype = None
+        L.oracle_theta_update.argtypes = [c_int32, c_int32, u32p, c_uint32, c_float, f32p]
+        L.oracle_theta_update.restype = None
+        L.oracle_phi_update.argtypes = [c_int32, c_int32, u32p, c_uint32, c_float, c_float, f32p]
+        L.oracle_phi_update.restype = None
+        L.oracle_loglik_eval.argtypes = [c_int32, i32p, i32p, f32p, c_int32, f32p, f32p]
+        L.oracle_loglik_eval.restype = c_double
+        _lib = L
+    return _lib
+
+
+def _p(a: np.ndarray, ty):
+    return a.ctypes.data_as(POINTER(ty))
+
+
+def _vp(a):
+    return None if a is None else a.ctypes.data_as(c_void_p)
+
+
+def pass_word(pass_index: int, domain: int = DOMAIN_TRAIN) -> int:
+    """Fourth counter word of the stream: pass index (28 bits) and stream domain above."""
+    assert 0 <= pass_index < (1 << 28)
+    return (domain << 28) | pass_index
+
+
+# --------------------------------------------------------------------------- #
+# single-function access (used by the pins in tests/)
+def philox(ctr, key) -> np.ndarray:
+    c = np.asarray(ctr, dtype=np.uint32)
+    k = np.asarray(key, dtype=np.uint32)
+    out = np.zeros(4, dtype=np.uint32)
+    lib().oracle_philox4x32_10(_p(c, c_uint32), _p(k, c_uint32), _p(out, c_uint32))
+    return out
+
+
+def uniform_from_word(x: int) -> float:
+    return float(lib().oracle_uniform_from_word(c_uint32(x)))
+
+
+def stream_uniform(seed: int, tau: int, k: int, piece: int, pword: int) -> float:
+    return float(lib().oracle_stream_uniform(seed, tau, k, piece, pword))
+
+
+def ipow(s: float, n: int) -> float:
+    return float(lib().oracle_ipow(c_float(s), n))
+
+
+def binom_walk(n: int, pm0: float, r: float, u: float) -> int:
+    return int(lib().oracle_binom_walk(n, c_float(pm0), c_float(r), c_float(u)))
+
+
+def binom(R: int, q: float, seed: int, tau: int, k: int, pword: int) -> int:
+    return int(lib().oracle_binom(R, c_float(q), seed, tau, k, pword))
+
+
+def draw(w, N: int, seed: int, tau: int, pword: int):
+    """One factored draw from weights w: returns (counts[K], normaliser)."""
+    w = np.ascontiguousarray(w, dtype=np.float32)
+    K = w.shape[0]
+    counts = np.zeros(K, dtype=np.uint32)
+    scratch = np.zeros(K, dtype=np.float32)
+    S = lib().oracle_draw(K, _p(w, c_float), N, seed, tau, pword, _p(counts, c_uint32), _p(scratch, c_float))
+    return counts, float(S)
+
+
+class CSC:
+    """Sparse words x documents count matrix, one column per document."""
+
+    def __init__(self, D, V, colptr, rowidx, val):
+        self.D, self.V = int(D), int(V)
+        self.colptr = np.ascontiguousarray(colptr, dtype=np.int32)
+        self.rowidx = np.ascontiguousarray(rowidx, dtype=np.int32)
+        self.val = np.ascontiguousarray(val, dtype=np.float32)
+        assert self.colptr.shape == (self.D + 1,)
+        self.nnz = int(self.colptr[-1])
+        assert self.rowidx.shape == (self.nnz,) and self.val.shape == (self.nnz,)
+
+    @property
+    def tokens(self) -> float:
+        return float(self.val.astype(np.float64).sum())
+
+    def slice_docs(self, lo: int, hi: int) -> "CSC":
+        a, b = int(self.colptr[lo]), int(self.colptr[hi])
+        return CSC(hi - lo, self.V, self.colptr[lo:hi + 1] - a, self.rowidx[a:b], self.val[a:b])
+
+
+def task_base(X: CSC, G: int) -> np.ndarray:
+    base = np.zeros(X.nnz + 1, dtype=np.int64)
+    lib().oracle_task_base(X.nnz, _p(X.val, c_float), G, _p(base, c_int64))
+    return base
+
+
+def run_pass(X: CSC, K, G, m, seed, pword, theta, phi, want_nwk=True, want_mu=False):
+    """One pass of draws over X.  Returns (ndk, nwk or None, mu or None)."""
+    ndk = np.zeros((X.D, K), dtype=np.uint32)
+    nwk = np.zeros((X.V, K), dtype=np.uint32) if want_nwk else None
+    mu = np.zeros(X.nnz, dtype=np.float32) if want_mu else None
+    lib().oracle_pass(X.D, X.V, _p(X.colptr, c_int32), _p(X.rowidx, c_int32), _p(X.val, c_float),
+                      K, G, m, seed, pword, _vp(theta), _vp(phi), _p(ndk, c_uint32), _vp(nwk), _vp(mu))
+    return ndk, nwk, mu
+
+
+def draw_tasks(X: CSC, K, G, m, seed, pword, theta, phi, task_ids) -> np.ndarray:
+    ids = np.ascontiguousarray(task_ids, dtype=np.int64)
+    out = np.zeros((ids.shape[0], K), dtype=np.uint32)
+    lib().oracle_draw_tasks(X.D, _p(X.colptr, c_int32), _p(X.rowidx, c_int32), _p(X.val, c_float),
+                            K, G, m, seed, pword, _vp(theta), _vp(phi), ids.shape[0],
+                            _p(ids, c_int64), _p(out, c_uint32))
+    return out
+
+
+def theta_update(ndk, m, alpha) -> np.ndarray:
+    D, K = ndk.shape
+    theta = np.empty((D, K), dtype=np.float32)
+    lib().oracle_theta_update(D, K, _p(ndk, c_uint32), m, c_float(alpha), _p(theta, c_float))
+    return theta
+
+
+def phi_update(nwk, m, beta, rho, phi) -> np.ndarray:
+    V, K = nwk.shape
+    out = np.zeros((V, K), dtype=np.float32) if phi is None else np.ascontiguousarray(phi, dtype=np.float32).copy()
+    lib().oracle_phi_update(V, K, _p(nwk, c_uint32), m, c_float(beta), c_float(rho), _p(out, c_float))
+    return out
+
+
+def loglik_eval(X: CSC, theta, phi) -> float:
+    K = theta.shape[1]
+    return float(lib().oracle_loglik_eval(X.D, _p(X.colptr, c_int32), _p(X.rowidx, c_int32),
+                                          _p(X.val, c_float), K, _p(theta, c_float), _p(phi, c_float)))
+
+
+class OracleLDA:
+    """SAME Gibbs LDA state advanced by the oracle, one pass at a time.
+
+    ``t`` counts passes of the training stream: pass 0 is the random
+    initialisation (uniform weights), every sweep or new minibatch takes the
+    next index.  The held-out fold-in of :meth:`loglik` uses its own stream
+    domain and restarts at pass 0 on every call.
+    """
+
+    def __init__(self, X: CSC, K: int, alpha: float, beta: float, seed: int, m0: int, G: int = 8):
+        self.X, self.K, self.G = X, int(K), int(G)
+        self.alpha, self.beta, self.seed = float(np.float32(alpha)), float(np.float32(beta)), int(seed)
+        self.t = 0
+        self.ndk, self.nwk, _ = run_pass(X, self.K, self.G, m0, self.seed, pass_word(self.t), None, None)
+        self.theta = theta_update(self.ndk, m0, self.alpha)
+        self.phi = phi_update(self.nwk, m0, self.beta, 1.0, None)
+        self.t += 1
+
+    def sweep(self, m: int, rho: float = 1.0):
+        self.ndk, self.nwk, _ = run_pass(self.X, self.K, self.G, m, self.seed, pass_word(self.t),
+                                         self.theta, self.phi)
+        self.theta = theta_update(self.ndk, m, self.alpha)
+        self.phi = phi_update(self.nwk, m, self.beta, rho, self.phi)
+        self.t += 1
+
+    def set_batch(self, X: CSC, m_init: int):
+        """New minibatch: phi is kept, theta of the new documents starts from a uniform-weight pass."""
+        assert X.V == self.X.V
+        self.X = X
+        self.ndk, _, _ = run_pass(X, self.K, self.G, m_init, self.seed, pass_word(self.t), None, None,
+                                  want_nwk=False)
+        self.nwk = None
+        self.theta = theta_update(self.ndk, m_init, self.alpha)
+        self.t += 1
+
+    def loglik(self, Xtest: CSC, foldin_sweeps: int, m_eval: int) -> float:
+        p = 0
+        ndk, _, _ = run_pass(Xtest, self.K, self.G, m_eval, self.seed, pass_word(p, DOMAIN_HELDOUT),
+                             None, None, want_nwk=False)
+        theta = theta_update(ndk, m_eval, self.alpha)
+        for _ in range(foldin_sweeps):
+            p += 1
+            ndk, _, _ = run_pass(Xtest, self.K, self.G, m_eval, self.seed, pass_word(p, DOMAIN_HELDOUT),
+                                 theta, self.phi, want_nwk=False)
+            theta = theta_update(ndk, m_eval, self.alpha)
+        return loglik_eval(Xtest, theta, self.phi)

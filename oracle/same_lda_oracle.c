@@ -1,0 +1,348 @@
+/*
+ * CPU oracle for the SAME Gibbs LDA sweep (test infrastructure, not product code).
+ *
+ * A plain, slow, single-file C implementation of what one SAME sweep computes,
+ * written from the paper's text: Section 4 (the m tied copies of a latent
+ * variable form one multinomial count vector), Section 5.1 / Eq. 6-7 (the LDA
+ * update and its count statistics) and Algorithm 3 (zero the accumulators,
+ * normaliser, draw, accumulate, add priors, normalise over words, blend).
+ * It shares no code with the GPU library.  Only tests, the smoke check and the
+ * benchmark's cpu_baseline leg may use it.
+ *
+ * Everything that decides an integer is done in IEEE binary32 with one rounding
+ * per operation (compile with -ffp-contract=off, no fast-math), so that a second
+ * implementation following the same steps obtains the same integers.
+ *
+ * Parts the paper does not fix (build decisions; "parity unpinned" by the paper,
+ * pinned only in distribution): the order of the conditional-binomial chain, the
+ * binomial sampler, the random number generator and its keying, the summation
+ * order, the grouping of a nonzero's tokens into draws, the initialisation and
+ * the held-out fold-in.
+ */
+#include <math.h>
+#include <stddef.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+/* ------------------------------------------------------------------------- */
+/* Philox4x32-10 (Salmon, Moraes, Dror, Shaw: "Parallel random numbers: as easy
+ * as 1, 2, 3", SC'11): ten rounds; each round multiplies counter words 0 and 2
+ * by two fixed constants, mixes the high halves with words 1 and 3 and the key,
+ * and the key is advanced by the Weyl constants between rounds.               */
+void oracle_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4])
+{
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
+    uint32_t k0 = key[0], k1 = key[1];
+    for (int round = 0; round < 10; ++round) {
+        uint64_t prod0 = (uint64_t)0xD2511F53u * (uint64_t)c0;
+        uint64_t prod1 = (uint64_t)0xCD9E8D57u * (uint64_t)c2;
+        uint32_t hi0 = (uint32_t)(prod0 >> 32), lo0 = (uint32_t)prod0;
+        uint32_t hi1 = (uint32_t)(prod1 >> 32), lo1 = (uint32_t)prod1;
+        uint32_t n0 = hi1 ^ c1 ^ k0;
+        uint32_t n2 = hi0 ^ c3 ^ k1;
+        c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+/* A random word becomes a uniform in (0,1): its top 23 bits j give (2j+1)/2^24,
+ * an odd multiple of 2^-24, exactly representable and never 0 or 1.           */
+float oracle_uniform_from_word(uint32_t x)
+{
+    return (float)(2u * (x >> 9) + 1u) * 5.9604644775390625e-8f; /* 2^-24 */
+}
+
+/* Stream layout.  One draw task (see oracle_pass) has a 40-bit id tau.  The
+ * uniform that decides topic k's first binomial piece is word (k mod 4) of the
+ * block with counter (tau_lo, tau_hi, k/4, pass).  Piece j >= 1 of topic k uses
+ * word ((j-1) mod 4) of the block (tau_lo, tau_hi | ((j-1)/4) << 8,
+ * 2^31 | k, pass).  The key is the 64-bit seed.  "pass" carries the pass index
+ * in its low 28 bits and a stream domain (0 training, 1 held-out fold-in) above. */
+static float stream_uniform(uint64_t seed, uint64_t tau, uint32_t k, uint32_t piece, uint32_t pass)
+{
+    uint32_t key[2] = { (uint32_t)seed, (uint32_t)(seed >> 32) };
+    uint32_t ctr[4], out[4];
+    ctr[0] = (uint32_t)tau;
+    ctr[1] = (uint32_t)(tau >> 32) & 0xFFu;
+    ctr[3] = pass;
+    if (piece == 0) {
+        ctr[2] = k >> 2;
+        oracle_philox4x32_10(ctr, key, out);
+        return oracle_uniform_from_word(out[k & 3u]);
+    }
+    ctr[1] |= ((piece - 1u) >> 2) << 8;
+    ctr[2] = 0x80000000u | k;
+    oracle_philox4x32_10(ctr, key, out);
+    return oracle_uniform_from_word(out[(piece - 1u) & 3u]);
+}
+
+float oracle_stream_uniform(uint64_t seed, uint64_t tau, uint32_t k, uint32_t piece, uint32_t pass)
+{
+    return stream_uniform(seed, tau, k, piece, pass);
+}
+
+/* ------------------------------------------------------------------------- */
+/* s^n by binary square-and-multiply, least significant bit first.            */
+float oracle_ipow(float s, uint32_t n)
+{
+    float result = 1.0f, base = s;
+    uint32_t e = n;
+    while (e > 0) {
+        if (e & 1u) result = result * base;
+        e >>= 1;
+        if (e > 0) base = base * base;
+    }
+    return result;
+}
+
+/* Binomial(n, qq) for one piece by inversion: walk the pmf upward from 0,
+ * pm(x) = pm(x-1) * r * (n-x+1) / x with r = qq/(1-qq), until the cdf reaches
+ * u.  The walk also ends when the pmf has fallen below the resolution of the
+ * running cdf (the tail is numerically exhausted).                            */
+uint32_t oracle_binom_walk(uint32_t n, float pm0, float r, float u)
+{
+    uint32_t x = 0;
+    float pm = pm0, cdf = pm0;
+    while (u > cdf && x < n) {
+        x += 1;
+        float inv_x = 1.0f / (float)x;
+        pm = pm * r;
+        pm = pm * (float)(n - x + 1u);
+        pm = pm * inv_x;
+        float next = cdf + pm;
+        if (next == cdf) break;
+        cdf = next;
+    }
+    return x;
+}
+
+/* n ~ Binomial(R, q) for topic k of task tau.  The smaller of q and 1-q is
+ * sampled (the result is complemented for q > 1/2); R is cut into pieces of at
+ * most floor(32/qq) trials so that (1-qq)^piece never underflows; each piece
+ * has its own uniform.                                                        */
+uint32_t oracle_binom(uint32_t R, float q, uint64_t seed, uint64_t tau, uint32_t k, uint32_t pass)
+{
+    if (R == 0 || !(q > 0.0f)) return 0;
+    if (q >= 1.0f) return R;
+    int flip = q > 0.5f;
+    float qq = flip ? 1.0f - q : q;
+    float s = 1.0f - qq;
+    float r = qq / s;
+    float Lf = 32.0f / qq;
+    uint32_t L = (Lf >= (float)R) ? R : (uint32_t)Lf;
+    float pmL = oracle_ipow(s, L);
+    uint32_t rem = R, piece = 0, total = 0;
+    while (rem > 0) {
+        uint32_t n = rem < L ? rem : L;
+        float pm0 = (n == L) ? pmL : oracle_ipow(s, n);
+        float u = stream_uniform(seed, tau, k, piece, pass);
+        total += oracle_binom_walk(n, pm0, r, u);
+        rem -= n;
+        piece += 1;
+    }
+    return flip ? R - total : total;
+}
+
+/* The factored draw (Section 4): the N = m*g copies of a latent topic variable
+ * with conditional weights w[0..K) are one Multinomial(N, w/sum w) count
+ * vector, drawn as a chain of conditional binomials from the last topic down:
+ * n_k ~ Bin(R, w_k / (w_0+...+w_k)), R -= n_k, and topic 0 keeps what is left.
+ * P[k] is the running sum w_0+...+w_k accumulated left to right.  Returns P[K-1]
+ * (the normaliser mu of Algorithm 3).  scratch holds K floats.                */
+float oracle_draw(int32_t K, const float* w, uint32_t N, uint64_t seed, uint64_t tau,
+                  uint32_t pass, uint32_t* counts, float* scratch)
+{
+    float* P = scratch;
+    P[0] = w[0];
+    for (int32_t k = 1; k < K; ++k) P[k] = P[k - 1] + w[k];
+    for (int32_t k = 0; k < K; ++k) counts[k] = 0;
+    uint32_t R = N;
+    for (int32_t k = K - 1; k >= 1 && R > 0; --k) {
+        if (!(w[k] > 0.0f)) continue;
+        float q = w[k] / P[k];
+        uint32_t n = oracle_binom(R, q, seed, tau, (uint32_t)k, pass);
+        counts[k] = n;
+        R -= n;
+    }
+    counts[0] = R;
+    return P[K - 1];
+}
+
+/* ------------------------------------------------------------------------- */
+/* Draw tasks.  A nonzero (d, w, c) stands for c tokens with identical
+ * conditionals; its tokens are drawn in groups of at most G: task j of the
+ * nonzero covers g = min(G, c - j*G) tokens and draws Multinomial(m*g, p).
+ * Task ids number the tasks of all nonzeros consecutively in storage order.   */
+static uint32_t tasks_of(float c, int32_t G)
+{
+    uint32_t ci = (uint32_t)c;
+    return (ci + (uint32_t)G - 1u) / (uint32_t)G;
+}
+
+int64_t oracle_task_count(int64_t nnz, const float* val, int32_t G)
+{
+    int64_t n = 0;
+    for (int64_t i = 0; i < nnz; ++i) n += tasks_of(val[i], G);
+    return n;
+}
+
+/* task_base[i] = id of the first task of nonzero i (task_base has nnz+1 entries). */
+void oracle_task_base(int64_t nnz, const float* val, int32_t G, int64_t* task_base)
+{
+    int64_t n = 0;
+    for (int64_t i = 0; i < nnz; ++i) { task_base[i] = n; n += tasks_of(val[i], G); }
+    task_base[nnz] = n;
+}
+
+static void fill_weights(int32_t K, const float* theta_d, const float* phi_w, float* w)
+{
+    if (theta_d == NULL) { for (int32_t k = 0; k < K; ++k) w[k] = 1.0f; return; }
+    for (int32_t k = 0; k < K; ++k) w[k] = theta_d[k] * phi_w[k];
+}
+
+/* One pass over all nonzeros of a CSC matrix whose columns are documents
+ * (Algorithm 3, the loop over document-word pairs): for every task form the
+ * weights theta[d][k]*phi[w][k] (all ones when theta == NULL: the random
+ * initialisation), draw the count vector and add it to ndk[d][.] and, unless
+ * nwk == NULL, to nwk[w][.].  mu (may be NULL) receives the normaliser of each
+ * nonzero.  theta is [D][K], phi is [V][K] (word-major), counts are u32.      */
+void oracle_pass(int32_t D, int32_t V, const int32_t* colptr, const int32_t* rowidx,
+                 const float* val, int32_t K, int32_t G, uint32_t m, uint64_t seed,
+                 uint32_t pass, const float* theta, const float* phi,
+                 uint32_t* ndk, uint32_t* nwk, float* mu)
+{
+    (void)V;
+    int64_t nnz = colptr[D];
+    int64_t* base = (int64_t*)malloc((size_t)(nnz + 1) * sizeof(int64_t));
+    oracle_task_base(nnz, val, G, base);
+#pragma omp parallel
+    {
+        float* w = (float*)malloc((size_t)K * sizeof(float));
+        float* scratch = (float*)malloc((size_t)K * sizeof(float));
+        uint32_t* cnt = (uint32_t*)malloc((size_t)K * sizeof(uint32_t));
+#pragma omp for schedule(dynamic, 64)
+        for (int32_t d = 0; d < D; ++d) {
+            for (int64_t i = colptr[d]; i < colptr[d + 1]; ++i) {
+                int32_t word = rowidx[i];
+                uint32_t c = (uint32_t)val[i];
+                fill_weights(K, theta ? theta + (size_t)d * K : NULL,
+                             phi ? phi + (size_t)word * K : NULL, w);
+                uint32_t ntask = tasks_of(val[i], G);
+                for (uint32_t j = 0; j < ntask; ++j) {
+                    uint32_t g = c - j * (uint32_t)G;
+                    if (g > (uint32_t)G) g = (uint32_t)G;
+                    float S = oracle_draw(K, w, m * g, seed, (uint64_t)(base[i] + j), pass, cnt, scratch);
+                    if (mu && j == 0) mu[i] = S;
+                    for (int32_t k = 0; k < K; ++k) {
+                        if (cnt[k] == 0) continue;
+                        ndk[(size_t)d * K + k] += cnt[k];   /* document d belongs to this thread */
+                        if (nwk) {
+#pragma omp atomic
+                            nwk[(size_t)word * K + k] += cnt[k];
+                        }
+                    }
+                }
+            }
+        }
+        free(w); free(scratch); free(cnt);
+    }
+    free(base);
+}
+
+/* Count vectors of selected tasks (for sampled parity checks at large sizes).
+ * out is [n][K].  task_ids must be valid ids of this matrix.                  */
+void oracle_draw_tasks(int32_t D, const int32_t* colptr, const int32_t* rowidx, const float* val,
+                       int32_t K, int32_t G, uint32_t m, uint64_t seed, uint32_t pass,
+                       const float* theta, const float* phi,
+                       int64_t n, const int64_t* task_ids, uint32_t* out)
+{
+    int64_t nnz = colptr[D];
+    int64_t* base = (int64_t*)malloc((size_t)(nnz + 1) * sizeof(int64_t));
+    oracle_task_base(nnz, val, G, base);
+    float* w = (float*)malloc((size_t)K * sizeof(float));
+    float* scratch = (float*)malloc((size_t)K * sizeof(float));
+    for (int64_t t = 0; t < n; ++t) {
+        int64_t tau = task_ids[t];
+        int64_t lo = 0, hi = nnz;            /* last nonzero whose base <= tau */
+        while (hi - lo > 1) { int64_t mid = (lo + hi) / 2; if (base[mid] <= tau) lo = mid; else hi = mid; }
+        int64_t i = lo;
+        int32_t dl = 0, dh = D;              /* document holding nonzero i */
+        while (dh - dl > 1) { int32_t mid = (dl + dh) / 2; if (colptr[mid] <= i) dl = mid; else dh = mid; }
+        int32_t d = dl;
+        uint32_t j = (uint32_t)(tau - base[i]);
+        uint32_t c = (uint32_t)val[i];
+        uint32_t g = c - j * (uint32_t)G;
+        if (g > (uint32_t)G) g = (uint32_t)G;
+        fill_weights(K, theta ? theta + (size_t)d * K : NULL,
+                     phi ? phi + (size_t)rowidx[i] * K : NULL, w);
+        oracle_draw(K, w, m * g, seed, (uint64_t)tau, pass, out + (size_t)t * K, scratch);
+    }
+    free(w); free(scratch); free(base);
+}
+
+/* ------------------------------------------------------------------------- */
+/* Parameter update (Eq. 6 and Algorithm 3's last three steps).  Counts hold all
+ * m copies, so they are divided by m; theta keeps its prior and stays
+ * unnormalised (its per-document normaliser cancels in the draw); phi gets its
+ * prior and is normalised over words per topic (the c_k../m + W*beta term of
+ * Eq. 6), then blended into the running model with weight rho.                */
+void oracle_theta_update(int32_t D, int32_t K, const uint32_t* ndk, uint32_t m, float alpha, float* theta)
+{
+    float mf = (float)m;
+    for (size_t e = 0; e < (size_t)D * K; ++e) {
+        float avg = (float)ndk[e] / mf;
+        theta[e] = avg + alpha;
+    }
+}
+
+void oracle_phi_update(int32_t V, int32_t K, const uint32_t* nwk, uint32_t m, float beta, float rho, float* phi)
+{
+    float mf = (float)m;
+    float vbeta = (float)V * beta;
+    float one_minus_rho = 1.0f - rho;
+    for (int32_t k = 0; k < K; ++k) {
+        uint64_t nk = 0;
+        for (int32_t w = 0; w < V; ++w) nk += nwk[(size_t)w * K + k];
+        float avg_k = (float)nk / mf;
+        float den = avg_k + vbeta;
+        for (int32_t w = 0; w < V; ++w) {
+            float avg = (float)nwk[(size_t)w * K + k] / mf;
+            float num = avg + beta;
+            float hat = num / den;
+            if (rho == 1.0f) {
+                phi[(size_t)w * K + k] = hat;
+            } else {
+                float keep = one_minus_rho * phi[(size_t)w * K + k];
+                float add = rho * hat;
+                phi[(size_t)w * K + k] = keep + add;
+            }
+        }
+    }
+}
+
+/* Per-word log-likelihood of a matrix under (theta, phi) (Section 6.1.1):
+ * sum_i c_i * log( sum_k theta_dk phi_wk / sum_k theta_dk ) / sum_i c_i.
+ * phi is already normalised over words.  The inner sum is the fp32 normaliser
+ * of the draw; logs and the outer sum are in double.                          */
+double oracle_loglik_eval(int32_t D, const int32_t* colptr, const int32_t* rowidx, const float* val,
+                          int32_t K, const float* theta, const float* phi)
+{
+    double total = 0.0, tokens = 0.0;
+    for (int32_t d = 0; d < D; ++d) {
+        double tsum = 0.0;
+        for (int32_t k = 0; k < K; ++k) tsum += (double)theta[(size_t)d * K + k];
+        double log_tsum = log(tsum);
+        for (int64_t i = colptr[d]; i < colptr[d + 1]; ++i) {
+            const float* ph = phi + (size_t)rowidx[i] * K;
+            const float* th = theta + (size_t)d * K;
+            float S = th[0] * ph[0];
+            for (int32_t k = 1; k < K; ++k) { float wk = th[k] * ph[k]; S = S + wk; }
+            total += (double)val[i] * (log((double)S) - log_tsum);
+            tokens += (double)val[i];
+        }
+    }
+    return tokens > 0.0 ? total / tokens : 0.0;
+}
