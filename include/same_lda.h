@@ -1,0 +1,142 @@
+/*
+ * same_lda.h - C ABI of the MI355X (gfx950) SAME Gibbs LDA sweep library.
+ *
+ * The library runs the per-nonzero hot path of SAME (State Augmentation for
+ * Marginal Estimation) Gibbs parameter estimation for Latent Dirichlet Allocation
+ * (Zhao, Jiang, Canny, arXiv 1409.5402) on one GPU:
+ *
+ *   for every nonzero (d, w, c) of the sparse words x documents count matrix
+ *     weights   w_k = theta[d][k] * phi[w][k]                (Algorithm 3, normaliser and lambda)
+ *     draw      the m copies of each of the c tokens as ONE multinomial count vector
+ *               totalling m*c (Section 4, "coordinate-factored" multinomial form)
+ *     scatter   the counts into new document-topic and word-topic matrices
+ *   then add the priors, normalise phi over words and blend (Algorithm 3, last steps; Eq. 6).
+ *
+ * Conventions
+ *   - Every function returns SAME_LDA_OK (0) or a negative SAME_LDA_E* code; the text of the
+ *     last failure is available from same_lda_last_error().  No exception crosses the boundary.
+ *   - "host" / "device" on a pointer says where the memory must live.  Device pointers are plain
+ *     HIP device allocations of the current device (for example the data_ptr of a torch tensor).
+ *   - Matrices are dense row-major: theta and n_dk are [D][K], phi and n_wk are [V][K]
+ *     (word-major, so the K values of one word are contiguous).
+ *   - All device state is allocated in same_lda_init / same_lda_set_batch; same_lda_sweep
+ *     allocates nothing (the paper's matrix-caching rule, Section 5.3).
+ *   - The input matrix is borrowed for the duration of the call only: the library keeps its own
+ *     device-side work list and never modifies the caller's arrays.
+ *   - Work is enqueued on the HIP stream given at init; calls are asynchronous unless stated.
+ *   - One handle must not be used from two threads at once.
+ */
+#ifndef SAME_LDA_H
+#define SAME_LDA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SAME_LDA_OK       0
+#define SAME_LDA_EINVAL  (-1)  /* null pointer, bad shape, K < 1, m < 1, alpha <= 0, beta <= 0, bad selector */
+#define SAME_LDA_ECSC    (-2)  /* malformed matrix: column pointers not ascending, word id out of range,
+                                  count not a positive integer, m * count too large                       */
+#define SAME_LDA_ENOMEM  (-3)  /* host or device allocation failed                                         */
+#define SAME_LDA_EHIP    (-4)  /* HIP runtime error (text in same_lda_last_error)                          */
+
+typedef struct same_lda same_lda_t;   /* opaque; owns all device state */
+
+/* Sparse words x documents matrix in compressed-column form: column d is document d
+ * (the D_t of Algorithm 3).  All three arrays live on the host (on_device = 0) or all on the
+ * device (on_device = 1).                                                                     */
+typedef struct {
+    int32_t        D;        /* number of documents (columns), >= 0                           */
+    int32_t        V;        /* vocabulary size (rows), >= 1                                  */
+    int64_t        nnz;      /* number of stored entries, == colptr[D], < 2^31                */
+    const int32_t* colptr;   /* [D+1] ascending, colptr[0] == 0                               */
+    const int32_t* rowidx;   /* [nnz] word id in [0, V)                                       */
+    const float*   val;      /* [nnz] token counts: integer-valued, >= 1, stored as float     */
+    int32_t        on_device;
+} same_lda_csc;
+
+/* Selectors for same_lda_get / same_lda_set. */
+#define SAME_LDA_THETA 0   /* float    [D][K]  theta = n_dk/m + alpha (unnormalised)             */
+#define SAME_LDA_PHI   1   /* float    [V][K]  phi, each topic normalised over words             */
+#define SAME_LDA_NDK   2   /* uint32_t [D][K]  document-topic counts of the last pass            */
+#define SAME_LDA_NWK   3   /* uint32_t [V][K]  word-topic counts of the last pass                */
+#define SAME_LDA_NK    4   /* uint64_t [K]     topic totals of the last pass                     */
+
+/* Create a handle for matrix X and run the random initialisation (Algorithm 2, step 1):
+ * one pass with uniform topic weights and m0 copies per token, followed by the parameter update.
+ *   K                number of topics, 1 <= K <= 4096
+ *   alpha, beta      Dirichlet priors of Eq. 6, > 0
+ *   seed             key of the counter-based random stream
+ *   m0               copies per token of the initial pass, >= 1
+ *   tokens_per_draw  the c tokens of a nonzero are drawn in groups of at most this many
+ *                    (each group is one multinomial of m * group-size copies), >= 1
+ *   hip_stream       hipStream_t to run on (NULL = the default stream)
+ * Synchronises with the stream before returning.  On failure *out is NULL.                     */
+int same_lda_init(same_lda_t** out, const same_lda_csc* X, int32_t K, float alpha, float beta,
+                  uint64_t seed, int32_t m0, int32_t tokens_per_draw, void* hip_stream);
+
+/* One SAME sweep over the resident matrix (Algorithm 3, one iteration): zero the count
+ * matrices, draw and scatter for every nonzero with m_t copies per token, then
+ * theta = n_dk/m_t + alpha, phi_hat = (n_wk/m_t + beta) / (n_k/m_t + V*beta),
+ * phi = (1-rho_t)*phi + rho_t*phi_hat (rho_t = 1 replaces phi).  Asynchronous.
+ *   m_t    >= 1, and m_t * (largest group size) < 2^24
+ *   rho_t  in (0, 1]                                                                           */
+int same_lda_sweep(same_lda_t* h, int32_t m_t, float rho_t);
+
+/* Per-word log-likelihood of held-out documents (Section 6.1.1): theta of the held-out
+ * documents is fitted with phi frozen (a uniform-weight pass, then foldin_sweeps passes with
+ * m_eval copies, on a separate random stream), then
+ * ll = sum_i c_i * log( sum_k theta_dk phi_wk / sum_k theta_dk ) / sum_i c_i.
+ * Allocates temporary device memory, synchronises, writes *ll_per_word (host).                 */
+int same_lda_loglik(same_lda_t* h, const same_lda_csc* Xtest, int32_t foldin_sweeps,
+                    int32_t m_eval, double* ll_per_word);
+
+/* Release the handle and all its device memory (NULL is allowed). */
+void same_lda_free(same_lda_t* h);
+
+/* Replace the resident matrix by a new minibatch with the same vocabulary (Section 5.2):
+ * phi is kept; theta of the new documents is initialised by one uniform-weight pass with
+ * m_init copies per token.  Reallocates per-document state; synchronises.                      */
+int same_lda_set_batch(same_lda_t* h, const same_lda_csc* X, int32_t m_init);
+
+/* Copy a state matrix out of / into the handle.  bytes must equal the matrix size.
+ * same_lda_set accepts SAME_LDA_THETA and SAME_LDA_PHI only.  Both synchronise.                */
+int same_lda_get(same_lda_t* h, int32_t which, void* dst, size_t bytes, int32_t dst_on_device);
+int same_lda_set(same_lda_t* h, int32_t which, const void* src, size_t bytes, int32_t src_on_device);
+
+/* Index of the next pass of the training stream (0 was the initialisation), and a setter so that
+ * a run restored with same_lda_set continues bit-identically.                                   */
+int same_lda_get_pass(const same_lda_t* h, int32_t* pass_index);
+int same_lda_set_pass(same_lda_t* h, int32_t pass_index);
+
+/* Number of draw tasks (groups of tokens) of the resident matrix: task ids are
+ * 0 .. count-1 in storage order, ceil(c / tokens_per_draw) consecutive ids per nonzero.        */
+int same_lda_task_count(const same_lda_t* h, int64_t* count);
+
+/* Test hook: count vectors that the NEXT same_lda_sweep(h, m_t, .) will draw for the listed
+ * tasks, computed by the same device code on the current theta and phi; state is not changed.
+ *   task_ids    host, [n]
+ *   counts_out  host, [n][K] uint32                                                            */
+int same_lda_debug_draw(same_lda_t* h, int32_t m_t, const int64_t* task_ids, int32_t n,
+                        uint32_t* counts_out);
+
+/* Kernel timing.  When enabled, HIP events bracket the draw-and-scatter kernel of every sweep on
+ * the handle's stream.  same_lda_get_timing synchronises, returns the summed duration (ms) and
+ * the number of launches since the last call, and resets both.                                  */
+int same_lda_set_timing(same_lda_t* h, int32_t enabled);
+int same_lda_get_timing(same_lda_t* h, double* draw_ms_total, int64_t* launches);
+
+/* Wait for everything enqueued on the handle's stream. */
+int same_lda_synchronize(same_lda_t* h);
+
+/* Text of the last failure of this handle (of the last failed same_lda_init when h is NULL).
+ * The pointer stays valid until the next failing call.                                          */
+const char* same_lda_last_error(const same_lda_t* h);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SAME_LDA_H */

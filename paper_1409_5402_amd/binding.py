@@ -1,0 +1,200 @@
+"""Thin ctypes binding of libsame_lda.so (argument marshalling only).
+
+Every step of the sweep runs in the HIP library; this module converts Python objects to the
+plain pointers of the C ABI.  PyTorch appears only as the owner of device memory and streams.
+There is no fallback: if the library has not been built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from ctypes import POINTER, Structure, byref, c_char_p, c_double, c_float, c_int32, c_int64, c_size_t, c_uint32, c_uint64, c_void_p
+
+import numpy as np
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libsame_lda.so")
+
+THETA, PHI, NDK, NWK, NK = 0, 1, 2, 3, 4
+_DTYPES = {THETA: np.float32, PHI: np.float32, NDK: np.uint32, NWK: np.uint32, NK: np.uint64}
+
+EXPORTS = ["same_lda_init", "same_lda_sweep", "same_lda_loglik", "same_lda_free", "same_lda_set_batch",
+           "same_lda_get", "same_lda_set", "same_lda_get_pass", "same_lda_set_pass", "same_lda_task_count",
+           "same_lda_debug_draw", "same_lda_set_timing", "same_lda_get_timing", "same_lda_synchronize",
+           "same_lda_last_error"]
+
+
+class SameLdaError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__(f"same_lda error {code}: {text}")
+        self.code = code
+
+
+class _Csc(Structure):
+    _fields_ = [("D", c_int32), ("V", c_int32), ("nnz", c_int64), ("colptr", c_void_p),
+                ("rowidx", c_void_p), ("val", c_void_p), ("on_device", c_int32)]
+
+
+_lib = None
+
+
+def load() -> ctypes.CDLL:
+    """Loads the built library; raises if it is missing (build it with paper_1409_5402_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(f"{LIB_PATH} is missing: run paper_1409_5402_amd.build.build() first")
+        L = ctypes.CDLL(LIB_PATH)
+        L.same_lda_init.argtypes = [POINTER(c_void_p), POINTER(_Csc), c_int32, c_float, c_float, c_uint64,
+                                    c_int32, c_int32, c_void_p]
+        L.same_lda_sweep.argtypes = [c_void_p, c_int32, c_float]
+        L.same_lda_loglik.argtypes = [c_void_p, POINTER(_Csc), c_int32, c_int32, POINTER(c_double)]
+        L.same_lda_free.argtypes = [c_void_p]
+        L.same_lda_free.restype = None
+        L.same_lda_set_batch.argtypes = [c_void_p, POINTER(_Csc), c_int32]
+        L.same_lda_get.argtypes = [c_void_p, c_int32, c_void_p, c_size_t, c_int32]
+        L.same_lda_set.argtypes = [c_void_p, c_int32, c_void_p, c_size_t, c_int32]
+        L.same_lda_get_pass.argtypes = [c_void_p, POINTER(c_int32)]
+        L.same_lda_set_pass.argtypes = [c_void_p, c_int32]
+        L.same_lda_task_count.argtypes = [c_void_p, POINTER(c_int64)]
+        L.same_lda_debug_draw.argtypes = [c_void_p, c_int32, c_void_p, c_int32, c_void_p]
+        L.same_lda_set_timing.argtypes = [c_void_p, c_int32]
+        L.same_lda_get_timing.argtypes = [c_void_p, POINTER(c_double), POINTER(c_int64)]
+        L.same_lda_synchronize.argtypes = [c_void_p]
+        L.same_lda_last_error.argtypes = [c_void_p]
+        L.same_lda_last_error.restype = c_char_p
+        for name in EXPORTS:
+            if name not in ("same_lda_free", "same_lda_last_error"):
+                getattr(L, name).restype = c_int32
+        _lib = L
+    return _lib
+
+
+def _is_torch(x) -> bool:
+    return type(x).__module__.startswith("torch")
+
+
+def _csc(D, V, colptr, rowidx, val):
+    """Builds the C view of a matrix from three numpy arrays (host) or three torch tensors."""
+    keep = []
+    if _is_torch(colptr):
+        import torch
+        dev = colptr.device
+        arrs = []
+        for a, dt in ((colptr, torch.int32), (rowidx, torch.int32), (val, torch.float32)):
+            a = a.to(dtype=dt).contiguous()
+            assert a.device == dev
+            arrs.append(a)
+        keep = arrs
+        ptrs = [a.data_ptr() if a.numel() else None for a in arrs]
+        on_device = 1 if dev.type == "cuda" else 0
+        nnz = int(arrs[1].numel())
+    else:
+        arrs = [np.ascontiguousarray(colptr, np.int32), np.ascontiguousarray(rowidx, np.int32),
+                np.ascontiguousarray(val, np.float32)]
+        keep = arrs
+        ptrs = [a.ctypes.data if a.size else None for a in arrs]
+        on_device = 0
+        nnz = int(arrs[1].size)
+    c = _Csc(int(D), int(V), nnz, ptrs[0], ptrs[1], ptrs[2], on_device)
+    return c, keep
+
+
+class SameLDA:
+    """A SAME Gibbs LDA model resident on the current GPU (one handle of the C library)."""
+
+    def __init__(self, D, V, colptr, rowidx, val, K, alpha, beta, seed, m0, tokens_per_draw=8, stream=None):
+        self._lib = load()
+        self._h = c_void_p()
+        self.V, self.K, self.D = int(V), int(K), int(D)
+        if stream is None:
+            try:
+                import torch
+                stream = torch.cuda.current_stream().cuda_stream if torch.cuda.is_available() else 0
+            except ImportError:
+                stream = 0
+        c, keep = _csc(D, V, colptr, rowidx, val)
+        rc = self._lib.same_lda_init(byref(self._h), byref(c), int(K), float(alpha), float(beta), int(seed),
+                                     int(m0), int(tokens_per_draw), c_void_p(stream or None))
+        del keep
+        if rc != 0:
+            raise SameLdaError(rc, self._lib.same_lda_last_error(None).decode())
+
+    def _check(self, rc):
+        if rc != 0:
+            raise SameLdaError(rc, self._lib.same_lda_last_error(self._h).decode())
+
+    def sweep(self, m, rho=1.0):
+        self._check(self._lib.same_lda_sweep(self._h, int(m), float(rho)))
+
+    def set_batch(self, D, colptr, rowidx, val, m_init):
+        c, keep = _csc(D, self.V, colptr, rowidx, val)
+        self._check(self._lib.same_lda_set_batch(self._h, byref(c), int(m_init)))
+        self.D = int(D)
+        del keep
+
+    def loglik(self, D, colptr, rowidx, val, foldin_sweeps, m_eval) -> float:
+        c, keep = _csc(D, self.V, colptr, rowidx, val)
+        out = c_double()
+        self._check(self._lib.same_lda_loglik(self._h, byref(c), int(foldin_sweeps), int(m_eval), byref(out)))
+        del keep
+        return out.value
+
+    def _shape(self, which):
+        return {THETA: (self.D, self.K), PHI: (self.V, self.K), NDK: (self.D, self.K),
+                NWK: (self.V, self.K), NK: (self.K,)}[which]
+
+    def get(self, which) -> np.ndarray:
+        out = np.empty(self._shape(which), dtype=_DTYPES[which])
+        self._check(self._lib.same_lda_get(self._h, which, out.ctypes.data if out.size else None, out.nbytes, 0))
+        return out
+
+    def set(self, which, arr):
+        a = np.ascontiguousarray(arr, dtype=_DTYPES[which])
+        assert a.shape == self._shape(which)
+        self._check(self._lib.same_lda_set(self._h, which, a.ctypes.data if a.size else None, a.nbytes, 0))
+
+    @property
+    def pass_index(self) -> int:
+        v = c_int32()
+        self._check(self._lib.same_lda_get_pass(self._h, byref(v)))
+        return v.value
+
+    @pass_index.setter
+    def pass_index(self, v):
+        self._check(self._lib.same_lda_set_pass(self._h, int(v)))
+
+    @property
+    def task_count(self) -> int:
+        v = c_int64()
+        self._check(self._lib.same_lda_task_count(self._h, byref(v)))
+        return v.value
+
+    def debug_draw(self, m, task_ids) -> np.ndarray:
+        ids = np.ascontiguousarray(task_ids, np.int64)
+        out = np.zeros((ids.shape[0], self.K), np.uint32)
+        self._check(self._lib.same_lda_debug_draw(self._h, int(m), ids.ctypes.data if ids.size else None,
+                                                  ids.shape[0], out.ctypes.data if out.size else None))
+        return out
+
+    def set_timing(self, enabled: bool):
+        self._check(self._lib.same_lda_set_timing(self._h, 1 if enabled else 0))
+
+    def get_timing(self):
+        ms, n = c_double(), c_int64()
+        self._check(self._lib.same_lda_get_timing(self._h, byref(ms), byref(n)))
+        return ms.value, n.value
+
+    def synchronize(self):
+        self._check(self._lib.same_lda_synchronize(self._h))
+
+    def close(self):
+        if self._h:
+            self._lib.same_lda_free(self._h)
+            self._h = c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

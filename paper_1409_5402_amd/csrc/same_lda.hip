@@ -1,0 +1,530 @@
+// Host side of the SAME LDA library: handle, validation, work-list construction, launches.
+// Exports the C ABI declared in include/same_lda.h.
+#include "../../include/same_lda.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "draw_kernel.h"
+#include "update_kernels.h"
+
+namespace {
+
+thread_local std::string g_init_error;
+
+// Device copy of one sparse matrix plus its draw work list.
+struct Matrix {
+    int32_t D = 0;
+    int64_t nnz = 0, n_tasks = 0;
+    uint32_t max_group = 0;        // largest number of tokens in one task
+    double tokens = 0.0;
+    int32_t*  t_doc = nullptr;     // [n_tasks]
+    int32_t*  t_word = nullptr;    // [n_tasks]
+    uint32_t* t_g = nullptr;       // [n_tasks]
+    int32_t*  nz_doc = nullptr;    // [nnz]
+    int32_t*  rowidx = nullptr;    // [nnz]
+    float*    val = nullptr;       // [nnz]
+    float*    theta = nullptr;     // [D][K]
+    uint32_t* ndk = nullptr;       // [D][K]
+};
+
+}  // namespace
+
+struct same_lda {
+    int32_t V = 0, K = 0, G = 0;
+    float alpha = 0.f, beta = 0.f;
+    uint64_t seed = 0;
+    int32_t pass = 0;              // next pass index of the training stream
+    hipStream_t stream = nullptr;
+    Matrix X;
+    float* phi = nullptr;          // [V][K]
+    uint32_t* nwk = nullptr;       // [V][K]
+    unsigned long long* nk = nullptr;  // [K]
+    bool timing = false;
+    std::vector<std::pair<hipEvent_t, hipEvent_t>> events;   // recorded, not yet read
+    std::vector<std::pair<hipEvent_t, hipEvent_t>> pool;     // free event pairs
+    std::string error;
+};
+
+namespace {
+
+int fail(same_lda* h, int code, const char* fmt, ...)
+{
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    if (h) h->error = buf; else g_init_error = buf;
+    return code;
+}
+
+#define HIP_TRY(h, expr)                                                                         \
+    do {                                                                                         \
+        hipError_t e_ = (expr);                                                                  \
+        if (e_ != hipSuccess)                                                                    \
+            return fail(h, e_ == hipErrorOutOfMemory ? SAME_LDA_ENOMEM : SAME_LDA_EHIP,          \
+                        "%s: %s", #expr, hipGetErrorString(e_));                                 \
+    } while (0)
+
+template <class T>
+int dev_alloc(same_lda* h, T** p, size_t n)
+{
+    *p = nullptr;
+    if (n == 0) return SAME_LDA_OK;
+    HIP_TRY(h, hipMalloc(reinterpret_cast<void**>(p), n * sizeof(T)));
+    return SAME_LDA_OK;
+}
+
+void free_matrix(Matrix& M)
+{
+    hipFree(M.t_doc); hipFree(M.t_word); hipFree(M.t_g); hipFree(M.nz_doc);
+    hipFree(M.rowidx); hipFree(M.val); hipFree(M.theta); hipFree(M.ndk);
+    M = Matrix();
+}
+
+// Validates the matrix, builds the work list on the host and uploads it.
+int build_matrix(same_lda* h, const same_lda_csc* X, int32_t V, int32_t K, int32_t G, Matrix& M, hipStream_t st)
+{
+    if (!X) return fail(h, SAME_LDA_EINVAL, "matrix is null");
+    if (X->D < 0 || X->V != V || X->nnz < 0 || X->nnz >= (int64_t)1 << 31)
+        return fail(h, SAME_LDA_EINVAL, "bad matrix shape D=%d V=%d (expected V=%d) nnz=%lld", X->D, X->V, V,
+                    (long long)X->nnz);
+    if (!X->colptr || (X->nnz > 0 && (!X->rowidx || !X->val)))
+        return fail(h, SAME_LDA_EINVAL, "matrix arrays are null");
+    const int32_t D = X->D;
+    const int64_t nnz = X->nnz;
+    std::vector<int32_t> colptr_h, rowidx_h;
+    std::vector<float> val_h;
+    const int32_t* colptr = X->colptr;
+    const int32_t* rowidx = X->rowidx;
+    const float* val = X->val;
+    try {
+        if (X->on_device) {
+            colptr_h.resize((size_t)D + 1); rowidx_h.resize((size_t)nnz); val_h.resize((size_t)nnz);
+            HIP_TRY(h, hipMemcpy(colptr_h.data(), X->colptr, ((size_t)D + 1) * 4, hipMemcpyDeviceToHost));
+            if (nnz) {
+                HIP_TRY(h, hipMemcpy(rowidx_h.data(), X->rowidx, (size_t)nnz * 4, hipMemcpyDeviceToHost));
+                HIP_TRY(h, hipMemcpy(val_h.data(), X->val, (size_t)nnz * 4, hipMemcpyDeviceToHost));
+            }
+            colptr = colptr_h.data(); rowidx = rowidx_h.data(); val = val_h.data();
+        }
+        if (colptr[0] != 0 || (int64_t)colptr[D] != nnz)
+            return fail(h, SAME_LDA_ECSC, "colptr[0]=%d colptr[D]=%d do not match nnz=%lld", colptr[0], colptr[D],
+                        (long long)nnz);
+        std::vector<int32_t> t_doc, t_word, nz_doc((size_t)nnz);
+        std::vector<uint32_t> t_g;
+        t_doc.reserve((size_t)nnz + 16); t_word.reserve((size_t)nnz + 16); t_g.reserve((size_t)nnz + 16);
+        uint32_t max_group = 0;
+        double tokens = 0.0;
+        for (int32_t d = 0; d < D; ++d) {
+            if (colptr[d + 1] < colptr[d])
+                return fail(h, SAME_LDA_ECSC, "colptr decreases at document %d", d);
+            for (int64_t i = colptr[d]; i < colptr[d + 1]; ++i) {
+                const int32_t w = rowidx[i];
+                const float c = val[i];
+                if (w < 0 || w >= V) return fail(h, SAME_LDA_ECSC, "word id %d out of range at entry %lld", w, (long long)i);
+                if (!(c >= 1.0f) || c >= 16777216.0f || c != std::floor(c))
+                    return fail(h, SAME_LDA_ECSC, "count %g at entry %lld is not an integer in [1, 2^24)", (double)c, (long long)i);
+                nz_doc[(size_t)i] = d;
+                uint32_t left = (uint32_t)c;
+                tokens += (double)left;
+                while (left > 0) {
+                    const uint32_t g = left < (uint32_t)G ? left : (uint32_t)G;
+                    t_doc.push_back(d); t_word.push_back(w); t_g.push_back(g);
+                    if (g > max_group) max_group = g;
+                    left -= g;
+                }
+            }
+        }
+        M.D = D; M.nnz = nnz; M.n_tasks = (int64_t)t_doc.size(); M.max_group = max_group; M.tokens = tokens;
+        int rc;
+        if ((rc = dev_alloc(h, &M.t_doc, t_doc.size()))) return rc;
+        if ((rc = dev_alloc(h, &M.t_word, t_word.size()))) return rc;
+        if ((rc = dev_alloc(h, &M.t_g, t_g.size()))) return rc;
+        if ((rc = dev_alloc(h, &M.nz_doc, (size_t)nnz))) return rc;
+        if ((rc = dev_alloc(h, &M.rowidx, (size_t)nnz))) return rc;
+        if ((rc = dev_alloc(h, &M.val, (size_t)nnz))) return rc;
+        if ((rc = dev_alloc(h, &M.theta, (size_t)D * K))) return rc;
+        if ((rc = dev_alloc(h, &M.ndk, (size_t)D * K))) return rc;
+        if (M.n_tasks) {
+            HIP_TRY(h, hipMemcpyAsync(M.t_doc, t_doc.data(), t_doc.size() * 4, hipMemcpyHostToDevice, st));
+            HIP_TRY(h, hipMemcpyAsync(M.t_word, t_word.data(), t_word.size() * 4, hipMemcpyHostToDevice, st));
+            HIP_TRY(h, hipMemcpyAsync(M.t_g, t_g.data(), t_g.size() * 4, hipMemcpyHostToDevice, st));
+            HIP_TRY(h, hipMemcpyAsync(M.nz_doc, nz_doc.data(), (size_t)nnz * 4, hipMemcpyHostToDevice, st));
+            HIP_TRY(h, hipMemcpyAsync(M.rowidx, rowidx, (size_t)nnz * 4, hipMemcpyHostToDevice, st));
+            HIP_TRY(h, hipMemcpyAsync(M.val, val, (size_t)nnz * 4, hipMemcpyHostToDevice, st));
+        }
+        HIP_TRY(h, hipStreamSynchronize(st));   // the host vectors go out of scope below
+    } catch (const std::bad_alloc&) {
+        return fail(h, SAME_LDA_ENOMEM, "host allocation failed while building the work list");
+    }
+    return SAME_LDA_OK;
+}
+
+int grid_for(size_t n, int threads = 256, int cap = 256 * 32)
+{
+    size_t g = (n + (size_t)threads - 1) / (size_t)threads;
+    if (g < 1) g = 1;
+    if (g > (size_t)cap) g = (size_t)cap;
+    return (int)g;
+}
+
+int check_m(same_lda* h, int32_t m, const Matrix& M)
+{
+    if (m < 1) return fail(h, SAME_LDA_EINVAL, "m must be >= 1 (got %d)", m);
+    if ((uint64_t)m * (uint64_t)(M.max_group ? M.max_group : 1u) >= (1ull << 24))
+        return fail(h, SAME_LDA_ECSC, "m * largest token group = %d * %u must stay below 2^24", m, M.max_group);
+    return SAME_LDA_OK;
+}
+
+// Threads per block of the draw kernel: as many as fit 64 KiB of LDS.
+int draw_threads(int K)
+{
+    int t = 256;
+    while (t > 64 && same::draw_lds_bytes(K, t) > 64u * 1024u) t >>= 1;
+    return t;
+}
+
+template <bool DEBUG>
+int launch_draw(same_lda* h, const same::DrawArgs& a, bool uniform, hipStream_t st)
+{
+    if (a.n <= 0) return SAME_LDA_OK;
+    const int T = draw_threads(a.K);
+    const size_t lds = same::draw_lds_bytes(a.K, T);
+    const int64_t blocks = (a.n + T - 1) / T;
+    if (blocks >= (int64_t)1 << 31) return fail(h, SAME_LDA_EINVAL, "too many draw tasks for one launch");
+    const bool vec = (a.K % same::kBlk) == 0;
+    dim3 grid((unsigned)blocks), block((unsigned)T);
+    if (uniform)      hipLaunchKernelGGL((same::draw_kernel<true, false, DEBUG>), grid, block, lds, st, a);
+    else if (vec)     hipLaunchKernelGGL((same::draw_kernel<false, true, DEBUG>), grid, block, lds, st, a);
+    else              hipLaunchKernelGGL((same::draw_kernel<false, false, DEBUG>), grid, block, lds, st, a);
+    HIP_TRY(h, hipGetLastError());
+    return SAME_LDA_OK;
+}
+
+same::DrawArgs draw_args(const same_lda* h, const Matrix& M, uint32_t m, uint32_t pass_word, bool with_words)
+{
+    same::DrawArgs a;
+    a.n = M.n_tasks; a.t_doc = M.t_doc; a.t_word = M.t_word; a.t_g = M.t_g; a.ids = nullptr;
+    a.theta = M.theta; a.phi = h->phi; a.ndk = M.ndk; a.nwk = with_words ? h->nwk : nullptr;
+    a.K = h->K; a.m = m; a.seed_lo = (uint32_t)h->seed; a.seed_hi = (uint32_t)(h->seed >> 32);
+    a.pass = pass_word;
+    return a;
+}
+
+uint32_t pass_word(int32_t pass_index, uint32_t domain) { return (domain << 28) | ((uint32_t)pass_index & 0x0FFFFFFFu); }
+
+int zero_u32(same_lda* h, uint32_t* p, size_t n, hipStream_t st)
+{
+    if (n == 0) return SAME_LDA_OK;
+    hipLaunchKernelGGL(same::zero_u32_kernel, dim3(grid_for(n)), dim3(256), 0, st, p, n);
+    HIP_TRY(h, hipGetLastError());
+    return SAME_LDA_OK;
+}
+
+int update_theta(same_lda* h, Matrix& M, uint32_t m, hipStream_t st)
+{
+    const size_t n = (size_t)M.D * h->K;
+    if (n == 0) return SAME_LDA_OK;
+    hipLaunchKernelGGL(same::theta_update_kernel, dim3(grid_for(n)), dim3(256), 0, st, M.ndk, M.theta, n,
+                       (float)m, h->alpha);
+    HIP_TRY(h, hipGetLastError());
+    return SAME_LDA_OK;
+}
+
+int update_phi(same_lda* h, uint32_t m, float rho, hipStream_t st)
+{
+    const size_t n = (size_t)h->V * h->K;
+    hipLaunchKernelGGL(same::zero_u64_kernel, dim3(1), dim3(256), 0, st, h->nk, (size_t)h->K);
+    const int rows_per_block = 64;
+    const int blocks = (h->V + rows_per_block - 1) / rows_per_block;
+    hipLaunchKernelGGL(same::topic_totals_kernel, dim3(blocks), dim3(256), 0, st, h->nwk, h->V, h->K, h->nk,
+                       rows_per_block);
+    hipLaunchKernelGGL(same::phi_update_kernel, dim3(grid_for(n)), dim3(256), 0, st, h->nwk, h->nk, h->phi, n,
+                       h->K, (float)m, h->beta, (float)h->V * h->beta, rho);
+    HIP_TRY(h, hipGetLastError());
+    return SAME_LDA_OK;
+}
+
+// One pass of draws on M.  uniform: weights are all ones (initialisation).
+int run_pass(same_lda* h, Matrix& M, uint32_t m, uint32_t pword, bool uniform, bool with_words, bool timed)
+{
+    hipStream_t st = h->stream;
+    int rc;
+    if ((rc = zero_u32(h, M.ndk, (size_t)M.D * h->K, st))) return rc;
+    if (with_words && (rc = zero_u32(h, h->nwk, (size_t)h->V * h->K, st))) return rc;
+    std::pair<hipEvent_t, hipEvent_t> ev{nullptr, nullptr};
+    if (timed) {
+        if (!h->pool.empty()) { ev = h->pool.back(); h->pool.pop_back(); }
+        else {
+            HIP_TRY(h, hipEventCreate(&ev.first));
+            HIP_TRY(h, hipEventCreate(&ev.second));
+        }
+        HIP_TRY(h, hipEventRecord(ev.first, st));
+    }
+    const same::DrawArgs a = draw_args(h, M, m, pword, with_words);
+    if ((rc = launch_draw<false>(h, a, uniform, st))) return rc;
+    if (timed) {
+        HIP_TRY(h, hipEventRecord(ev.second, st));
+        h->events.push_back(ev);
+    }
+    return SAME_LDA_OK;
+}
+
+size_t state_bytes(const same_lda* h, int32_t which)
+{
+    switch (which) {
+        case SAME_LDA_THETA: return (size_t)h->X.D * h->K * sizeof(float);
+        case SAME_LDA_PHI:   return (size_t)h->V * h->K * sizeof(float);
+        case SAME_LDA_NDK:   return (size_t)h->X.D * h->K * sizeof(uint32_t);
+        case SAME_LDA_NWK:   return (size_t)h->V * h->K * sizeof(uint32_t);
+        case SAME_LDA_NK:    return (size_t)h->K * sizeof(uint64_t);
+        default:             return 0;
+    }
+}
+
+void* state_ptr(same_lda* h, int32_t which)
+{
+    switch (which) {
+        case SAME_LDA_THETA: return h->X.theta;
+        case SAME_LDA_PHI:   return h->phi;
+        case SAME_LDA_NDK:   return h->X.ndk;
+        case SAME_LDA_NWK:   return h->nwk;
+        case SAME_LDA_NK:    return h->nk;
+        default:             return nullptr;
+    }
+}
+
+}  // namespace
+
+extern "C" {
+
+int same_lda_init(same_lda_t** out, const same_lda_csc* X, int32_t K, float alpha, float beta, uint64_t seed,
+                  int32_t m0, int32_t tokens_per_draw, void* hip_stream)
+{
+    if (!out) return fail(nullptr, SAME_LDA_EINVAL, "out is null");
+    *out = nullptr;
+    if (!X) return fail(nullptr, SAME_LDA_EINVAL, "matrix is null");
+    if (K < 1 || K > 4096) return fail(nullptr, SAME_LDA_EINVAL, "K must be in [1, 4096] (got %d)", K);
+    if (!(alpha > 0.f) || !(beta > 0.f) || !std::isfinite(alpha) || !std::isfinite(beta))
+        return fail(nullptr, SAME_LDA_EINVAL, "alpha and beta must be positive and finite");
+    if (X->V < 1) return fail(nullptr, SAME_LDA_EINVAL, "V must be >= 1 (got %d)", X->V);
+    if (tokens_per_draw < 1) return fail(nullptr, SAME_LDA_EINVAL, "tokens_per_draw must be >= 1");
+    same_lda* h = new (std::nothrow) same_lda();
+    if (!h) return fail(nullptr, SAME_LDA_ENOMEM, "host allocation failed");
+    h->V = X->V; h->K = K; h->G = tokens_per_draw; h->alpha = alpha; h->beta = beta; h->seed = seed;
+    h->stream = static_cast<hipStream_t>(hip_stream);
+    int rc = build_matrix(h, X, h->V, K, h->G, h->X, h->stream);
+    if (!rc) rc = check_m(h, m0, h->X);
+    if (!rc) rc = dev_alloc(h, &h->phi, (size_t)h->V * K);
+    if (!rc) rc = dev_alloc(h, &h->nwk, (size_t)h->V * K);
+    if (!rc) rc = dev_alloc(h, &h->nk, (size_t)K);
+    if (!rc) rc = run_pass(h, h->X, (uint32_t)m0, pass_word(0, 0), true, true, false);
+    if (!rc) rc = update_theta(h, h->X, (uint32_t)m0, h->stream);
+    if (!rc) rc = update_phi(h, (uint32_t)m0, 1.0f, h->stream);
+    if (!rc) { hipError_t e = hipStreamSynchronize(h->stream); if (e != hipSuccess) rc = fail(h, SAME_LDA_EHIP, "init: %s", hipGetErrorString(e)); }
+    if (rc) { g_init_error = h->error; same_lda_free(h); return rc; }
+    h->pass = 1;
+    *out = h;
+    return SAME_LDA_OK;
+}
+
+int same_lda_sweep(same_lda_t* h, int32_t m_t, float rho_t)
+{
+    if (!h) return SAME_LDA_EINVAL;
+    if (!(rho_t > 0.f) || rho_t > 1.f) return fail(h, SAME_LDA_EINVAL, "rho must be in (0, 1] (got %g)", (double)rho_t);
+    int rc = check_m(h, m_t, h->X);
+    if (!rc) rc = run_pass(h, h->X, (uint32_t)m_t, pass_word(h->pass, 0), false, true, h->timing);
+    if (!rc) rc = update_theta(h, h->X, (uint32_t)m_t, h->stream);
+    if (!rc) rc = update_phi(h, (uint32_t)m_t, rho_t, h->stream);
+    if (!rc) h->pass += 1;
+    return rc;
+}
+
+int same_lda_set_batch(same_lda_t* h, const same_lda_csc* X, int32_t m_init)
+{
+    if (!h) return SAME_LDA_EINVAL;
+    HIP_TRY(h, hipStreamSynchronize(h->stream));
+    Matrix M;
+    int rc = build_matrix(h, X, h->V, h->K, h->G, M, h->stream);
+    if (!rc) rc = check_m(h, m_init, M);
+    if (rc) { free_matrix(M); return rc; }
+    free_matrix(h->X);
+    h->X = M;
+    rc = run_pass(h, h->X, (uint32_t)m_init, pass_word(h->pass, 0), true, false, false);
+    if (!rc) rc = update_theta(h, h->X, (uint32_t)m_init, h->stream);
+    if (!rc) HIP_TRY(h, hipStreamSynchronize(h->stream));
+    if (!rc) h->pass += 1;
+    return rc;
+}
+
+int same_lda_loglik(same_lda_t* h, const same_lda_csc* Xtest, int32_t foldin_sweeps, int32_t m_eval, double* ll_per_word)
+{
+    if (!h) return SAME_LDA_EINVAL;
+    if (!ll_per_word || foldin_sweeps < 0) return fail(h, SAME_LDA_EINVAL, "bad loglik arguments");
+    Matrix M;
+    int rc = build_matrix(h, Xtest, h->V, h->K, h->G, M, h->stream);
+    if (!rc) rc = check_m(h, m_eval, M);
+    double* doc_log = nullptr; double* part = nullptr;
+    const int nblocks = (int)((M.nnz + 255) / 256);
+    if (!rc) rc = dev_alloc(h, &doc_log, (size_t)M.D);
+    if (!rc) rc = dev_alloc(h, &part, (size_t)nblocks);
+    if (!rc) rc = run_pass(h, M, (uint32_t)m_eval, pass_word(0, 1), true, false, false);
+    if (!rc) rc = update_theta(h, M, (uint32_t)m_eval, h->stream);
+    for (int32_t s = 1; !rc && s <= foldin_sweeps; ++s) {
+        rc = run_pass(h, M, (uint32_t)m_eval, pass_word(s, 1), false, false, false);
+        if (!rc) rc = update_theta(h, M, (uint32_t)m_eval, h->stream);
+    }
+    double total = 0.0;
+    if (!rc && M.nnz > 0) {
+        hipLaunchKernelGGL(same::doc_log_total_kernel, dim3((M.D + 255) / 256), dim3(256), 0, h->stream, M.theta,
+                           M.D, h->K, doc_log);
+        hipLaunchKernelGGL(same::loglik_kernel, dim3(nblocks), dim3(256), 0, h->stream, M.nnz, M.nz_doc, M.rowidx,
+                           M.val, M.theta, h->phi, h->K, doc_log, part);
+        std::vector<double> part_h((size_t)nblocks);
+        hipError_t e = hipGetLastError();
+        if (e == hipSuccess) e = hipMemcpyAsync(part_h.data(), part, (size_t)nblocks * 8, hipMemcpyDeviceToHost, h->stream);
+        if (e == hipSuccess) e = hipStreamSynchronize(h->stream);
+        if (e != hipSuccess) rc = fail(h, SAME_LDA_EHIP, "loglik: %s", hipGetErrorString(e));
+        for (double v : part_h) total += v;
+    } else if (!rc) {
+        hipError_t e = hipStreamSynchronize(h->stream);
+        if (e != hipSuccess) rc = fail(h, SAME_LDA_EHIP, "loglik: %s", hipGetErrorString(e));
+    }
+    if (!rc) *ll_per_word = M.tokens > 0.0 ? total / M.tokens : 0.0;
+    hipFree(doc_log); hipFree(part);
+    free_matrix(M);
+    return rc;
+}
+
+void same_lda_free(same_lda_t* h)
+{
+    if (!h) return;
+    hipStreamSynchronize(h->stream);
+    free_matrix(h->X);
+    hipFree(h->phi); hipFree(h->nwk); hipFree(h->nk);
+    for (auto& e : h->events) { hipEventDestroy(e.first); hipEventDestroy(e.second); }
+    for (auto& e : h->pool) { hipEventDestroy(e.first); hipEventDestroy(e.second); }
+    delete h;
+}
+
+int same_lda_get(same_lda_t* h, int32_t which, void* dst, size_t bytes, int32_t dst_on_device)
+{
+    if (!h) return SAME_LDA_EINVAL;
+    const size_t want = state_bytes(h, which);
+    if (!state_ptr(h, which) && want) return fail(h, SAME_LDA_EINVAL, "unknown selector %d", which);
+    if (which < SAME_LDA_THETA || which > SAME_LDA_NK) return fail(h, SAME_LDA_EINVAL, "unknown selector %d", which);
+    if (bytes != want || (!dst && want)) return fail(h, SAME_LDA_EINVAL, "selector %d needs %zu bytes (got %zu)", which, want, bytes);
+    if (want) HIP_TRY(h, hipMemcpyAsync(dst, state_ptr(h, which), want, dst_on_device ? hipMemcpyDeviceToDevice : hipMemcpyDeviceToHost, h->stream));
+    HIP_TRY(h, hipStreamSynchronize(h->stream));
+    return SAME_LDA_OK;
+}
+
+int same_lda_set(same_lda_t* h, int32_t which, const void* src, size_t bytes, int32_t src_on_device)
+{
+    if (!h) return SAME_LDA_EINVAL;
+    if (which != SAME_LDA_THETA && which != SAME_LDA_PHI) return fail(h, SAME_LDA_EINVAL, "only theta and phi can be set");
+    const size_t want = state_bytes(h, which);
+    if (bytes != want || (!src && want)) return fail(h, SAME_LDA_EINVAL, "selector %d needs %zu bytes (got %zu)", which, want, bytes);
+    if (want) HIP_TRY(h, hipMemcpyAsync(state_ptr(h, which), src, want, src_on_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice, h->stream));
+    HIP_TRY(h, hipStreamSynchronize(h->stream));
+    return SAME_LDA_OK;
+}
+
+int same_lda_get_pass(const same_lda_t* h, int32_t* pass_index)
+{
+    if (!h || !pass_index) return SAME_LDA_EINVAL;
+    *pass_index = h->pass;
+    return SAME_LDA_OK;
+}
+
+int same_lda_set_pass(same_lda_t* h, int32_t pass_index)
+{
+    if (!h) return SAME_LDA_EINVAL;
+    if (pass_index < 0 || pass_index >= (1 << 28)) return fail(h, SAME_LDA_EINVAL, "pass index out of range");
+    h->pass = pass_index;
+    return SAME_LDA_OK;
+}
+
+int same_lda_task_count(const same_lda_t* h, int64_t* count)
+{
+    if (!h || !count) return SAME_LDA_EINVAL;
+    *count = h->X.n_tasks;
+    return SAME_LDA_OK;
+}
+
+int same_lda_debug_draw(same_lda_t* h, int32_t m_t, const int64_t* task_ids, int32_t n, uint32_t* counts_out)
+{
+    if (!h) return SAME_LDA_EINVAL;
+    if (n < 0 || (n > 0 && (!task_ids || !counts_out))) return fail(h, SAME_LDA_EINVAL, "bad debug_draw arguments");
+    int rc = check_m(h, m_t, h->X);
+    if (rc || n == 0) return rc;
+    for (int32_t i = 0; i < n; ++i)
+        if (task_ids[i] < 0 || task_ids[i] >= h->X.n_tasks) return fail(h, SAME_LDA_EINVAL, "task id %lld out of range", (long long)task_ids[i]);
+    int64_t* ids_d = nullptr; uint32_t* out_d = nullptr;
+    rc = dev_alloc(h, &ids_d, (size_t)n);
+    if (!rc) rc = dev_alloc(h, &out_d, (size_t)n * h->K);
+    if (!rc) {
+        hipError_t e = hipMemcpyAsync(ids_d, task_ids, (size_t)n * 8, hipMemcpyHostToDevice, h->stream);
+        if (e != hipSuccess) rc = fail(h, SAME_LDA_EHIP, "debug_draw: %s", hipGetErrorString(e));
+    }
+    if (!rc) rc = zero_u32(h, out_d, (size_t)n * h->K, h->stream);
+    if (!rc) {
+        same::DrawArgs a = draw_args(h, h->X, (uint32_t)m_t, pass_word(h->pass, 0), false);
+        a.n = n; a.ids = ids_d; a.ndk = out_d; a.nwk = nullptr;
+        rc = launch_draw<true>(h, a, false, h->stream);
+    }
+    if (!rc) {
+        hipError_t e = hipMemcpyAsync(counts_out, out_d, (size_t)n * h->K * 4, hipMemcpyDeviceToHost, h->stream);
+        if (e == hipSuccess) e = hipStreamSynchronize(h->stream);
+        if (e != hipSuccess) rc = fail(h, SAME_LDA_EHIP, "debug_draw: %s", hipGetErrorString(e));
+    }
+    hipFree(ids_d); hipFree(out_d);
+    return rc;
+}
+
+int same_lda_set_timing(same_lda_t* h, int32_t enabled)
+{
+    if (!h) return SAME_LDA_EINVAL;
+    h->timing = enabled != 0;
+    return SAME_LDA_OK;
+}
+
+int same_lda_get_timing(same_lda_t* h, double* draw_ms_total, int64_t* launches)
+{
+    if (!h || !draw_ms_total || !launches) return SAME_LDA_EINVAL;
+    HIP_TRY(h, hipStreamSynchronize(h->stream));
+    double total = 0.0;
+    for (auto& e : h->events) {
+        float ms = 0.f;
+        HIP_TRY(h, hipEventElapsedTime(&ms, e.first, e.second));
+        total += (double)ms;
+        h->pool.push_back(e);
+    }
+    *draw_ms_total = total;
+    *launches = (int64_t)h->events.size();
+    h->events.clear();
+    return SAME_LDA_OK;
+}
+
+int same_lda_synchronize(same_lda_t* h)
+{
+    if (!h) return SAME_LDA_EINVAL;
+    HIP_TRY(h, hipStreamSynchronize(h->stream));
+    return SAME_LDA_OK;
+}
+
+const char* same_lda_last_error(const same_lda_t* h)
+{
+    return h ? h->error.c_str() : g_init_error.c_str();
+}
+
+}  // extern "C"

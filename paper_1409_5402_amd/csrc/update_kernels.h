@@ -1,0 +1,112 @@
+// Dense kernels around the draw: zeroing, topic totals, the parameter update of Eq. 6 /
+// Algorithm 3 (add priors, normalise phi over words, blend) and the log-likelihood reduction.
+// All are plain coalesced streams over [rows][K] matrices; every arithmetic step is one
+// binary32 operation (no contraction), in the order stated next to it.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace same {
+
+__global__ void zero_u32_kernel(uint32_t* __restrict__ p, size_t n)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = 0u;
+}
+
+__global__ void zero_u64_kernel(unsigned long long* __restrict__ p, size_t n)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = 0ull;
+}
+
+// n_k = sum over words of n_wk[w][k], exact in 64-bit integers (any order gives the same value).
+// Each block sums a slab of rows; thread t owns column (t mod K') of every row group.
+__global__ void topic_totals_kernel(const uint32_t* __restrict__ nwk, int V, int K,
+                                    unsigned long long* __restrict__ nk, int rows_per_block)
+{
+    const int r0 = blockIdx.x * rows_per_block;
+    const int r1 = min(V, r0 + rows_per_block);
+    for (int k = threadIdx.x; k < K; k += blockDim.x) {
+        unsigned long long acc = 0ull;
+        for (int r = r0; r < r1; ++r) acc += nwk[(size_t)r * K + k];
+        if (acc) atomicAdd(nk + k, acc);
+    }
+}
+
+// theta = n_dk / m + alpha   (divide, then add)
+__global__ void theta_update_kernel(const uint32_t* __restrict__ ndk, float* __restrict__ theta,
+                                    size_t n, float mf, float alpha)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+        const float avg = (float)ndk[i] / mf;
+        theta[i] = avg + alpha;
+    }
+}
+
+// phi_hat = (n_wk/m + beta) / (n_k/m + V*beta);  phi = rho == 1 ? phi_hat : (1-rho)*phi + rho*phi_hat
+__global__ void phi_update_kernel(const uint32_t* __restrict__ nwk, const unsigned long long* __restrict__ nk,
+                                  float* __restrict__ phi, size_t n, int K, float mf, float beta,
+                                  float vbeta, float rho)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    const float one_minus_rho = 1.0f - rho;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+        const int k = (int)(i % (size_t)K);
+        const float avg_k = (float)nk[k] / mf;
+        const float den = avg_k + vbeta;
+        const float avg = (float)nwk[i] / mf;
+        const float num = avg + beta;
+        const float hat = num / den;
+        if (rho == 1.0f) {
+            phi[i] = hat;
+        } else {
+            const float keep = one_minus_rho * phi[i];
+            const float add = rho * hat;
+            phi[i] = keep + add;
+        }
+    }
+}
+
+// log of each document's theta total (double, summed left to right)
+__global__ void doc_log_total_kernel(const float* __restrict__ theta, int D, int K, double* __restrict__ out)
+{
+    const int d = blockIdx.x * blockDim.x + threadIdx.x;
+    if (d >= D) return;
+    double s = 0.0;
+    for (int k = 0; k < K; ++k) s += (double)theta[(size_t)d * K + k];
+    out[d] = log(s);
+}
+
+// Per nonzero: c * (log(sum_k theta_dk phi_wk) - log theta total); the inner sum is the
+// binary32 left-to-right running sum of the draw.  Block partial sums (double) go to part[].
+__global__ __launch_bounds__(256) void loglik_kernel(int64_t nnz, const int32_t* __restrict__ nz_doc,
+                                                     const int32_t* __restrict__ rowidx,
+                                                     const float* __restrict__ val,
+                                                     const float* __restrict__ theta,
+                                                     const float* __restrict__ phi, int K,
+                                                     const double* __restrict__ doc_log_total,
+                                                     double* __restrict__ part)
+{
+    __shared__ double red[256];
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    double v = 0.0;
+    if (i < nnz) {
+        const int d = nz_doc[i];
+        const float* th = theta + (size_t)d * K;
+        const float* ph = phi + (size_t)rowidx[i] * K;
+        float S = th[0] * ph[0];
+        for (int k = 1; k < K; ++k) { const float wk = th[k] * ph[k]; S = S + wk; }
+        v = (double)val[i] * (log((double)S) - doc_log_total[d]);
+    }
+    red[threadIdx.x] = v;
+    __syncthreads();
+    for (int s = 128; s > 0; s >>= 1) {
+        if ((int)threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) part[blockIdx.x] = red[0];
+}
+
+}  // namespace same

@@ -1,0 +1,241 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle, element by element.
+
+Integer count matrices must be bit-exact; theta/phi within 1e-5 relative (they are in fact
+expected to be identical, both sides rounding every step once); held-out log-likelihood within
+1e-4 absolute.  Inputs are seeded and synthetic; nothing here feeds GPU results to the oracle.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from helpers import corpus_to_csc, csc_from_dense
+from paper_1409_5402_amd import binding, schedule, synth
+
+pytestmark = pytest.mark.gpu
+
+RTOL = 1e-5          # accumulated fp32 theta / phi
+LL_ATOL = 1e-4       # held-out per-word log-likelihood
+
+
+def make_gpu(X: oracle.CSC, K, alpha, beta, seed, m0, G, on_device=False):
+    if on_device:
+        dev = torch.device("cuda:0")
+        return binding.SameLDA(X.D, X.V, torch.from_numpy(X.colptr).to(dev), torch.from_numpy(X.rowidx).to(dev),
+                               torch.from_numpy(X.val).to(dev), K, alpha, beta, seed, m0, G)
+    return binding.SameLDA(X.D, X.V, X.colptr, X.rowidx, X.val, K, alpha, beta, seed, m0, G)
+
+
+def assert_state_equal(g: binding.SameLDA, o: oracle.OracleLDA, what=""):
+    ndk, nwk = g.get(binding.NDK), g.get(binding.NWK)
+    bad_d = np.flatnonzero((ndk != o.ndk).any(axis=1))
+    assert bad_d.size == 0, f"{what}: n_dk differs in {bad_d.size} documents, first {bad_d[:5]}"
+    if o.nwk is not None:
+        assert np.array_equal(nwk, o.nwk), f"{what}: n_wk differs"
+        assert np.array_equal(g.get(binding.NK), o.nwk.sum(axis=0, dtype=np.uint64)), f"{what}: n_k differs"
+    np.testing.assert_allclose(g.get(binding.THETA), o.theta, rtol=RTOL, atol=0, err_msg=what)
+    np.testing.assert_allclose(g.get(binding.PHI), o.phi, rtol=RTOL, atol=0, err_msg=what)
+
+
+def toy(seed, D, V, density, cmax, empty_doc=True):
+    rng = np.random.default_rng(seed)
+    counts = rng.integers(1, cmax + 1, size=(D, V)) * (rng.uniform(size=(D, V)) < density)
+    if empty_doc and D > 3:
+        counts[2, :] = 0
+        counts[D - 1, :] = 0
+    if V > 5:
+        counts[:, 4] = 0
+    return csc_from_dense(counts)
+
+
+def test_tiny_config_ten_sweeps_bit_exact():
+    """Tiny workload: D=1000, V=2000, K=16, m=10 fixed, 10 sweeps; every sweep compared in full."""
+    p = synth.PRESETS["tiny"]
+    X = corpus_to_csc(synth.preset("tiny"))
+    o = oracle.OracleLDA(X, p["K"], p["alpha"], p["beta"], seed=0, m0=p["m"], G=8)
+    g = make_gpu(X, p["K"], p["alpha"], p["beta"], 0, p["m"], 8)
+    assert g.task_count == int(oracle.task_base(X, 8)[-1])
+    assert_state_equal(g, o, "init")
+    for s in range(p["sweeps"]):
+        o.sweep(p["m"])
+        g.sweep(p["m"])
+        assert_state_equal(g, o, f"sweep {s + 1}")
+    assert g.pass_index == o.t == 11
+    g.close()
+
+
+@pytest.mark.parametrize("K", [1, 2, 3, 5, 16, 17, 40, 64, 100, 256])
+def test_topic_counts_incl_ragged_K(K):
+    """K not a multiple of 4 or 16, K=1, several checkpoint blocks; ragged last thread block; empty docs."""
+    X = toy(seed=K, D=37, V=53, density=0.35, cmax=12)
+    m = 7
+    o = oracle.OracleLDA(X, K, 0.2, 0.01, seed=99, m0=m, G=4)
+    g = make_gpu(X, K, 0.2, 0.01, 99, m, 4)
+    assert_state_equal(g, o, "init")
+    for s in range(3):
+        o.sweep(m); g.sweep(m)
+        assert_state_equal(g, o, f"K={K} sweep {s + 1}")
+    g.close()
+
+
+@pytest.mark.parametrize("G,m", [(1, 1), (1, 30), (2, 100), (8, 100), (1000, 100), (1000, 500), (3, 1000)])
+def test_group_sizes_and_copy_counts(G, m):
+    """tokens_per_draw from 1 (the per-token multinomial of Section 4) to 'whole nonzero'; m from 1 to 1000
+    (large m*c forces several binomial pieces and the complement branch)."""
+    X = toy(seed=5, D=60, V=40, density=0.3, cmax=40)
+    K = 24
+    o = oracle.OracleLDA(X, K, 0.1, 0.01, seed=3, m0=m, G=G)
+    g = make_gpu(X, K, 0.1, 0.01, 3, m, G, on_device=True)
+    assert_state_equal(g, o, "init")
+    for s in range(2):
+        o.sweep(m); g.sweep(m)
+        assert_state_equal(g, o, f"G={G} m={m} sweep {s + 1}")
+    g.close()
+
+
+def test_annealed_medium_shape():
+    """Medium workload shape at reduced document count: K=64, Zipf word skew, m annealed linearly 1..20."""
+    p = synth.PRESETS["medium"]
+    X = corpus_to_csc(synth.preset("medium", scale=0.04))          # 2000 documents, V=20000
+    ms = schedule.linear(10.5, 20)
+    assert ms[0] == 1 and ms[-1] == 20
+    o = oracle.OracleLDA(X, p["K"], p["alpha"], p["beta"], seed=1, m0=ms[0], G=8)
+    g = make_gpu(X, p["K"], p["alpha"], p["beta"], 1, ms[0], 8)
+    assert_state_equal(g, o, "init")
+    for s, m in enumerate(ms[:8]):
+        o.sweep(m); g.sweep(m)
+        assert_state_equal(g, o, f"sweep {s + 1} m={m}")
+    g.close()
+
+
+def test_news_shape_slice_k256_m100():
+    """News workload shape (K=256, m=100, alpha=50/K, Zipf 1.1, log-normal lengths) on a 600-document slice
+    with the full 100k vocabulary: spans many thread blocks, checkpoint blocks and a ragged tail."""
+    p = synth.PRESETS["news"]
+    X = corpus_to_csc(synth.preset("news", scale=0.002))
+    o = oracle.OracleLDA(X, p["K"], p["alpha"], p["beta"], seed=7, m0=p["m"], G=8)
+    g = make_gpu(X, p["K"], p["alpha"], p["beta"], 7, p["m"], 8)
+    assert_state_equal(g, o, "init")
+    for s in range(3):
+        o.sweep(p["m"]); g.sweep(p["m"])
+        assert_state_equal(g, o, f"sweep {s + 1}")
+    g.close()
+
+
+def test_minibatch_blend_and_new_batch():
+    """rho < 1 blending (Algorithm 3, last step) and a second minibatch with phi kept (Section 5.2)."""
+    Xa = toy(seed=11, D=50, V=64, density=0.3, cmax=6)
+    Xb = toy(seed=12, D=33, V=64, density=0.4, cmax=6, empty_doc=False)
+    K = 12
+    o = oracle.OracleLDA(Xa, K, 0.1, 0.01, seed=5, m0=4, G=8)
+    g = make_gpu(Xa, K, 0.1, 0.01, 5, 4, 8)
+    for t, m in enumerate([4, 8, 16]):
+        rho = float(np.float32(schedule.rho(t + 1)))
+        o.sweep(m, rho); g.sweep(m, rho)
+        assert_state_equal(g, o, f"batch a sweep {t}")
+    o.set_batch(Xb, 16); g.set_batch(Xb.D, Xb.colptr, Xb.rowidx, Xb.val, 16)
+    assert np.array_equal(g.get(binding.NDK), o.ndk)
+    np.testing.assert_allclose(g.get(binding.THETA), o.theta, rtol=RTOL)
+    np.testing.assert_allclose(g.get(binding.PHI), o.phi, rtol=RTOL)
+    rho = float(np.float32(schedule.rho(5)))
+    o.sweep(16, rho); g.sweep(16, rho)
+    assert_state_equal(g, o, "batch b sweep")
+    g.close()
+
+
+def test_debug_draw_matches_oracle_tasks_and_next_sweep():
+    X = toy(seed=21, D=40, V=30, density=0.4, cmax=20)
+    K, m, G = 32, 50, 4
+    o = oracle.OracleLDA(X, K, 0.1, 0.01, seed=8, m0=m, G=G)
+    g = make_gpu(X, K, 0.1, 0.01, 8, m, G)
+    o.sweep(m); g.sweep(m)
+    n_tasks = g.task_count
+    ids = np.random.default_rng(0).choice(n_tasks, size=min(n_tasks, 500), replace=False)
+    got = g.debug_draw(m, ids)
+    ref = oracle.draw_tasks(X, K, G, m, 8, oracle.pass_word(o.t), o.theta, o.phi, ids)
+    assert np.array_equal(got, ref)
+    assert np.all(got.sum(axis=1) % m == 0)
+    o.sweep(m); g.sweep(m)                      # the hook must not have changed the state
+    assert_state_equal(g, o, "after debug_draw")
+    g.close()
+
+
+def test_heldout_loglik():
+    c = synth.generate(D=500, V=400, K=6, alpha=0.1, beta=0.05, seed=3, mean_len=80.0)
+    X = corpus_to_csc(c)
+    train, test = X.slice_docs(0, 450), X.slice_docs(450, 500)
+    o = oracle.OracleLDA(train, 6, 0.1, 0.05, seed=4, m0=10, G=8)
+    g = make_gpu(train, 6, 0.1, 0.05, 4, 10, 8)
+    for _ in range(5):
+        o.sweep(10); g.sweep(10)
+    ll_o = o.loglik(test, 3, 10)
+    ll_g = g.loglik(test.D, test.colptr, test.rowidx, test.val, 3, 10)
+    assert abs(ll_g - ll_o) <= LL_ATOL
+    assert_state_equal(g, o, "loglik must not disturb the training state")
+    # K = 1 closed form: ll = sum_w tok_test(w) log phi_w / tokens_test
+    g1 = make_gpu(train, 1, 0.1, 0.05, 4, 10, 8)
+    phi = g1.get(binding.PHI)[:, 0].astype(np.float64)
+    tok_t = np.zeros(X.V); np.add.at(tok_t, test.rowidx, test.val)
+    ref = float((tok_t * np.log(phi)).sum() / tok_t.sum())
+    assert abs(g1.loglik(test.D, test.colptr, test.rowidx, test.val, 2, 10) - ref) <= LL_ATOL
+    g.close(); g1.close()
+
+
+def test_set_state_and_resume_is_bit_identical():
+    """theta, phi and the pass index restore a run exactly (the stream is counter-based)."""
+    X = toy(seed=31, D=30, V=40, density=0.4, cmax=9)
+    K, m = 20, 25
+    g = make_gpu(X, K, 0.1, 0.01, 6, m, 8)
+    g.sweep(m)
+    theta, phi, t = g.get(binding.THETA), g.get(binding.PHI), g.pass_index
+    g.sweep(m)
+    want = g.get(binding.NWK)
+    g2 = make_gpu(X, K, 0.1, 0.01, 6, m, 8)
+    g2.set(binding.THETA, theta); g2.set(binding.PHI, phi); g2.pass_index = t
+    g2.sweep(m)
+    assert np.array_equal(g2.get(binding.NWK), want)
+    g.close(); g2.close()
+
+
+def test_large_topic_totals_on_device():
+    """Topic totals beyond 2^24 (float conversion of 64-bit sums) and phi from oracle-side counts."""
+    X = csc_from_dense(np.array([[60000, 50000, 3], [40000, 1, 70000]]))
+    K, m = 2, 200                                # totals up to 4.4e7 > 2^24
+    o = oracle.OracleLDA(X, K, 0.1, 0.01, seed=2, m0=m, G=100000)
+    g = make_gpu(X, K, 0.1, 0.01, 2, m, 100000)
+    assert_state_equal(g, o, "init")
+    o.sweep(m); g.sweep(m)
+    assert_state_equal(g, o, "sweep")
+    g.close()
+
+
+def test_errors_are_reported_not_crashes():
+    X = toy(seed=1, D=5, V=8, density=0.5, cmax=3, empty_doc=False)
+    with pytest.raises(binding.SameLdaError) as e:
+        binding.SameLDA(X.D, X.V, X.colptr, X.rowidx, X.val, 0, 0.1, 0.01, 1, 1, 8)
+    assert e.value.code == -1
+    bad = X.rowidx.copy(); bad[0] = 99
+    with pytest.raises(binding.SameLdaError) as e:
+        binding.SameLDA(X.D, X.V, X.colptr, bad, X.val, 4, 0.1, 0.01, 1, 1, 8)
+    assert e.value.code == -2
+    badv = X.val.copy(); badv[1] = 1.5
+    with pytest.raises(binding.SameLdaError) as e:
+        binding.SameLDA(X.D, X.V, X.colptr, X.rowidx, badv, 4, 0.1, 0.01, 1, 1, 8)
+    assert e.value.code == -2
+    g = make_gpu(X, 4, 0.1, 0.01, 1, 1, 8)
+    with pytest.raises(binding.SameLdaError):
+        g.sweep(0)
+    with pytest.raises(binding.SameLdaError):
+        g.sweep(1, 0.0)
+    g.sweep(1)
+    g.close()
+
+
+def test_empty_matrix():
+    X = oracle.CSC(3, 10, np.zeros(4, np.int32), np.zeros(0, np.int32), np.zeros(0, np.float32))
+    g = make_gpu(X, 4, 0.1, 0.01, 1, 5, 8)
+    g.sweep(5)
+    assert g.get(binding.NDK).sum() == 0
+    np.testing.assert_allclose(g.get(binding.THETA), 0.1, rtol=1e-6)
+    np.testing.assert_allclose(g.get(binding.PHI), 0.1, rtol=1e-6)       # beta / (V * beta)
+    g.close()
