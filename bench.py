@@ -1,0 +1,139 @@
+#!/usr/bin/env python3
+"""Benchmark of the SAME Gibbs LDA sweep on one MI355X.
+
+A step is one full sweep (zero, draw and scatter over every nonzero, parameter update) of the
+news-shaped workload: D=300,000 documents (the last 10% held out), V=100,000 words, K=256
+topics, m=100 copies per token, synthetic LDA-generated counts resident in HBM.  Prints one
+JSON line: tokens/s per sweep, the HBM-roofline figure of the draw kernel (algorithmic bytes over
+its HIP-event duration) and the CPU oracle's rate on a bounded slice of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def draw_kernel_bytes(nnz: int, D: int, K: int) -> float:
+    """Algorithmic bytes of one draw-and-scatter launch: per nonzero its word id, its count and the
+    K floats of phi_w; per document its column pointer, the K floats of theta_d and the K new counts."""
+    return float(nnz) * (8 + 4 * K) + float(D) * (4 + 8 * K)
+
+
+def cpu_baseline(X_np, K, alpha, beta, m, m0, G, target_s=12.0):
+    """Times one sweep of the oracle (as it stands) on a leading slice of documents sized for ~target_s."""
+    import oracle
+    cores = len(os.sched_getaffinity(0))
+    docs = min(X_np.D, 512)
+    while True:
+        sl = X_np.slice_docs(0, docs)
+        o = oracle.OracleLDA(sl, K, alpha, beta, seed=1, m0=m0, G=G)
+        t0 = time.perf_counter()
+        o.sweep(m)
+        dt = max(time.perf_counter() - t0, 1e-4)
+        if dt >= 0.5 * target_s or docs >= X_np.D:
+            break
+        docs = int(min(X_np.D, max(2 * docs, docs * target_s / dt)))
+    return {"value": sl.tokens / dt, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+            "sample": f"one sweep over the first {docs} documents ({sl.nnz} nonzeros, {int(sl.tokens)} tokens) "
+                      f"of the same corpus, K={K}, m={m}, after the oracle's own initialisation; {dt:.2f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=100,
+                    help="untimed sweeps before timing: all but the last 5 run with m=1 (burn-in), the last 5 with m")
+    ap.add_argument("--workload", default="news")
+    ap.add_argument("--scale", type=float, default=1.0, help="fraction of the workload's documents (1.0 = full size)")
+    ap.add_argument("--tokens-per-draw", type=int, default=8)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-loglik", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import oracle
+    from paper_1409_5402_amd import binding, synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    p = synth.PRESETS[args.workload]
+    K, m, alpha, beta, G = p["K"], p["m"], p["alpha"], p["beta"], args.tokens_per_draw
+
+    t0 = time.perf_counter()
+    corpus = synth.preset(args.workload, device=dev, scale=args.scale)
+    torch.cuda.synchronize()
+    t_gen = time.perf_counter() - t0
+    n_train = corpus.D - corpus.D // 10 if corpus.D >= 10 else corpus.D
+    train = corpus.slice_docs(0, n_train)
+    test = corpus.slice_docs(n_train, corpus.D) if n_train < corpus.D else None
+    st = train.stats()
+
+    t0 = time.perf_counter()
+    m0 = 1      # random initialisation: one topic per token
+    g = binding.SameLDA(train.D, train.V, train.colptr, train.rowidx, train.val, K, alpha, beta,
+                        seed=2, m0=m0, tokens_per_draw=G)
+    t_init = time.perf_counter() - t0
+
+    for s in range(args.warmup):
+        g.sweep(1 if s < args.warmup - 5 else m)
+    g.synchronize()
+    g.set_timing(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        g.sweep(m)
+    g.synchronize()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    draw_ms, launches = g.get_timing()
+    g.set_timing(False)
+    assert launches == args.steps
+
+    ms_per_step = 1e3 * dt / args.steps
+    tokens_per_s = st["tokens"] / (dt / args.steps)
+    bytes_per_launch = draw_kernel_bytes(st["nnz"], st["D"], K)
+    draw_ms_avg = draw_ms / launches
+    achieved = bytes_per_launch / (draw_ms_avg * 1e-3) / 1e9
+
+    out = {
+        "metric": "tokens/sec per SAME sweep (K=256, m=100) + achieved HBM GB/s vs 8 TB/s",
+        "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{args.workload} (LDA-generated, scale {args.scale})", "D": st["D"], "V": st["V"],
+                   "K": K, "m": m, "nnz": st["nnz"], "tokens": st["tokens"], "max_count": st["max_count"],
+                   "tokens_per_draw": G, "draw_tasks": g.task_count, "alpha": alpha, "beta": beta,
+                   "m_init": m0,
+                   "warmup_schedule": f"{max(0, args.warmup - 5)} sweeps at m=1 then {min(5, args.warmup)} at m={m}",
+                   "generate_s": round(t_gen, 2), "init_s": round(t_init, 2)},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "draw_kernel", "kernel_ms": draw_ms_avg, "bytes_per_launch": bytes_per_launch},
+    }
+    if test is not None and not args.no_loglik:
+        out["config"]["heldout_ll_per_word"] = g.loglik(test.D, test.colptr, test.rowidx, test.val, 3, m)
+    g.close()
+
+    if not args.no_cpu_baseline:
+        X_np = oracle.CSC(train.D, train.V, train.colptr.cpu().numpy(), train.rowidx.cpu().numpy(),
+                          train.val.cpu().numpy())
+        out["cpu_baseline"] = cpu_baseline(X_np, K, alpha, beta, m, m0, G)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
