@@ -67,7 +67,7 @@ typedef struct {
 
 /* Create a handle for matrix X and run the random initialisation (Algorithm 2, step 1):
  * one pass with uniform topic weights and m0 copies per token, followed by the parameter update.
- *   K                number of topics, 1 <= K <= 4096
+ *   K                number of topics, 1 <= K <= 2048
  *   alpha, beta      Dirichlet priors of Eq. 6, > 0
  *   seed             key of the counter-based random stream
  *   m0               copies per token of the initial pass, >= 1

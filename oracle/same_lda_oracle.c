@@ -120,9 +120,9 @@ uint32_t oracle_binom_walk(uint32_t n, float pm0, float r, float u)
 }
 
 /* n ~ Binomial(R, q) for topic k of task tau.  The smaller of q and 1-q is
- * sampled (the result is complemented for q > 1/2); R is cut into pieces of at
- * most floor(32/qq) trials so that (1-qq)^piece never underflows; each piece
- * has its own uniform.                                                        */
+ * sampled (the result is complemented for q > 1/2); when R*qq exceeds 32, R is cut
+ * into pieces of floor(32/qq) trials so that (1-qq)^piece never underflows; each
+ * piece has its own uniform.                                                        */
 uint32_t oracle_binom(uint32_t R, float q, uint64_t seed, uint64_t tau, uint32_t k, uint32_t pass)
 {
     if (R == 0 || !(q > 0.0f)) return 0;
@@ -131,8 +131,8 @@ uint32_t oracle_binom(uint32_t R, float q, uint64_t seed, uint64_t tau, uint32_t
     float qq = flip ? 1.0f - q : q;
     float s = 1.0f - qq;
     float r = qq / s;
-    float Lf = 32.0f / qq;
-    uint32_t L = (Lf >= (float)R) ? R : (uint32_t)Lf;
+    int single = ((float)R * qq) <= 32.0f;
+    uint32_t L = single ? R : (uint32_t)(32.0f / qq);
     float pmL = oracle_ipow(s, L);
     uint32_t rem = R, piece = 0, total = 0;
     while (rem > 0) {
@@ -148,26 +148,33 @@ uint32_t oracle_binom(uint32_t R, float q, uint64_t seed, uint64_t tau, uint32_t
 
 /* The factored draw (Section 4): the N = m*g copies of a latent topic variable
  * with conditional weights w[0..K) are one Multinomial(N, w/sum w) count
- * vector, drawn as a chain of conditional binomials from the last topic down:
- * n_k ~ Bin(R, w_k / (w_0+...+w_k)), R -= n_k, and topic 0 keeps what is left.
- * P[k] is the running sum w_0+...+w_k accumulated left to right.  Returns P[K-1]
- * (the normaliser mu of Algorithm 3).  scratch holds K floats.                */
+ * vector, drawn as a chain of conditional binomials.  The heaviest topic h (the
+ * highest index among equal maxima) is never drawn: it keeps what is left.  The
+ * others are visited from the last topic down, n_k ~ Bin(R, w_k / M_k), R -= n_k,
+ * where M_k is the weight not yet decided when k is visited: the topics
+ * 0..k and, if it is not among them, topic h.  P[k] is the running sum
+ * w_0+...+w_k accumulated left to right, so M_k = P[k] for k > h and
+ * M_k = P[k] + w_h for k < h.  Returns P[K-1] (the normaliser mu of Algorithm 3).
+ * scratch holds K floats.                                                      */
 float oracle_draw(int32_t K, const float* w, uint32_t N, uint64_t seed, uint64_t tau,
                   uint32_t pass, uint32_t* counts, float* scratch)
 {
     float* P = scratch;
     P[0] = w[0];
     for (int32_t k = 1; k < K; ++k) P[k] = P[k - 1] + w[k];
+    int32_t h = 0;
+    for (int32_t k = 1; k < K; ++k) if (w[k] >= w[h]) h = k;
     for (int32_t k = 0; k < K; ++k) counts[k] = 0;
     uint32_t R = N;
-    for (int32_t k = K - 1; k >= 1 && R > 0; --k) {
-        if (!(w[k] > 0.0f)) continue;
-        float q = w[k] / P[k];
+    for (int32_t k = K - 1; k >= 0 && R > 0; --k) {
+        if (k == h || !(w[k] > 0.0f)) continue;
+        float M = (k > h) ? P[k] : P[k] + w[h];
+        float q = w[k] / M;
         uint32_t n = oracle_binom(R, q, seed, tau, (uint32_t)k, pass);
         counts[k] = n;
         R -= n;
     }
-    counts[0] = R;
+    counts[h] = R;
     return P[K - 1];
 }
 

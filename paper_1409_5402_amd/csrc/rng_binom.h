@@ -1,4 +1,4 @@
-// Device-side random stream and binomial sampler of the SAME LDA draw (gfx950).
+// Device-side random stream and power helper of the SAME LDA draw (gfx950).
 //
 // Every floating-point step here is a single IEEE binary32 operation with one rounding
 // (the file is compiled with -ffp-contract=off); the integer results therefore depend only
@@ -67,59 +67,6 @@ __device__ __forceinline__ float ipow(float s, uint32_t n)
         if (e > 0) base = base * base;
     }
     return result;
-}
-
-// One binomial piece by inversion: walk the pmf upward from 0 until the cdf reaches u,
-// the piece is exhausted, or the pmf has fallen below the resolution of the running cdf.
-__device__ __forceinline__ uint32_t binom_walk(uint32_t n, float pm0, float r, float u)
-{
-    uint32_t x = 0;
-    float pm = pm0, cdf = pm0;
-    while (u > cdf && x < n) {
-        x += 1;
-        const float inv_x = 1.0f / (float)x;
-        pm = pm * r;
-        pm = pm * (float)(n - x + 1u);
-        pm = pm * inv_x;
-        const float next = cdf + pm;
-        if (next == cdf) break;
-        cdf = next;
-    }
-    return x;
-}
-
-// n ~ Binomial(R, q) for topic k.  The rarer outcome (probability qq <= 1/2) is sampled and the
-// result complemented when q > 1/2; R is cut into pieces of at most floor(32/qq) trials so the
-// starting pmf (1-qq)^piece never underflows.  u0 is the uniform of the first piece; later
-// pieces fetch theirs from the task's piece stream.
-__device__ __forceinline__ uint32_t binom(uint32_t R, float q, float u0, const StreamKey& s, uint32_t k)
-{
-    if (R == 0 || !(q > 0.0f)) return 0;
-    if (q >= 1.0f) return R;
-    const bool flip = q > 0.5f;
-    const float qq = flip ? 1.0f - q : q;
-    const float sc = 1.0f - qq;
-    const float r = qq / sc;
-    const float Lf = 32.0f / qq;
-    const uint32_t L = (Lf >= (float)R) ? R : (uint32_t)Lf;
-    const float pmL = ipow(sc, L);
-    uint32_t rem = R, piece = 0, total = 0;
-    uint32_t xb[4] = {0u, 0u, 0u, 0u};
-    while (rem > 0) {
-        const uint32_t n = rem < L ? rem : L;
-        const float pm0 = (n == L) ? pmL : ipow(sc, n);
-        float u = u0;
-        if (piece > 0) {
-            const uint32_t j = piece - 1u;
-            if ((j & 3u) == 0u) piece_block(s, k, j >> 2, xb);
-            const uint32_t word = (j & 3u) == 0u ? xb[0] : (j & 3u) == 1u ? xb[1] : (j & 3u) == 2u ? xb[2] : xb[3];
-            u = uniform_from_word(word);
-        }
-        total += binom_walk(n, pm0, r, u);
-        rem -= n;
-        piece += 1;
-    }
-    return flip ? R - total : total;
 }
 
 }  // namespace same

@@ -4,6 +4,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -19,6 +20,8 @@ namespace {
 
 thread_local std::string g_init_error;
 
+constexpr int32_t kTileDocs = 16;   // documents per tile of the processing order
+
 // Device copy of one sparse matrix plus its draw work list.
 struct Matrix {
     int32_t D = 0;
@@ -28,6 +31,7 @@ struct Matrix {
     int32_t*  t_doc = nullptr;     // [n_tasks]
     int32_t*  t_word = nullptr;    // [n_tasks]
     uint32_t* t_g = nullptr;       // [n_tasks]
+    int32_t*  order = nullptr;     // [n_tasks] task id processed at each launch position
     int32_t*  nz_doc = nullptr;    // [nnz]
     int32_t*  rowidx = nullptr;    // [nnz]
     float*    val = nullptr;       // [nnz]
@@ -85,7 +89,7 @@ int dev_alloc(same_lda* h, T** p, size_t n)
 
 void free_matrix(Matrix& M)
 {
-    hipFree(M.t_doc); hipFree(M.t_word); hipFree(M.t_g); hipFree(M.nz_doc);
+    hipFree(M.t_doc); hipFree(M.t_word); hipFree(M.t_g); hipFree(M.order); hipFree(M.nz_doc);
     hipFree(M.rowidx); hipFree(M.val); hipFree(M.theta); hipFree(M.ndk);
     M = Matrix();
 }
@@ -144,11 +148,33 @@ int build_matrix(same_lda* h, const same_lda_csc* X, int32_t V, int32_t K, int32
                 }
             }
         }
+        if (t_doc.size() >= ((size_t)1 << 31))
+            return fail(h, SAME_LDA_ECSC, "too many draw tasks (%zu); raise tokens_per_draw", t_doc.size());
+        // Processing order: documents are taken in tiles of kTileDocs; inside a tile the tasks are
+        // sorted by word.  Neighbouring lanes then work on the same or similar words (similar chain
+        // lengths, shared phi rows) while their theta rows stay within one small tile.  The order
+        // does not affect results: tasks are independent and keyed by their id.
+        std::vector<int32_t> order(t_doc.size());
+        {
+            std::vector<uint64_t> keys;
+            size_t begin = 0;
+            while (begin < t_doc.size()) {
+                const int32_t tile = t_doc[begin] / kTileDocs;
+                size_t end = begin;
+                while (end < t_doc.size() && t_doc[end] / kTileDocs == tile) ++end;
+                keys.resize(end - begin);
+                for (size_t i = begin; i < end; ++i) keys[i - begin] = ((uint64_t)(uint32_t)t_word[i] << 32) | (uint64_t)(i - begin);
+                std::sort(keys.begin(), keys.end());
+                for (size_t i = begin; i < end; ++i) order[i] = (int32_t)(begin + (size_t)(keys[i - begin] & 0xFFFFFFFFu));
+                begin = end;
+            }
+        }
         M.D = D; M.nnz = nnz; M.n_tasks = (int64_t)t_doc.size(); M.max_group = max_group; M.tokens = tokens;
         int rc;
         if ((rc = dev_alloc(h, &M.t_doc, t_doc.size()))) return rc;
         if ((rc = dev_alloc(h, &M.t_word, t_word.size()))) return rc;
         if ((rc = dev_alloc(h, &M.t_g, t_g.size()))) return rc;
+        if ((rc = dev_alloc(h, &M.order, order.size()))) return rc;
         if ((rc = dev_alloc(h, &M.nz_doc, (size_t)nnz))) return rc;
         if ((rc = dev_alloc(h, &M.rowidx, (size_t)nnz))) return rc;
         if ((rc = dev_alloc(h, &M.val, (size_t)nnz))) return rc;
@@ -158,6 +184,7 @@ int build_matrix(same_lda* h, const same_lda_csc* X, int32_t V, int32_t K, int32
             HIP_TRY(h, hipMemcpyAsync(M.t_doc, t_doc.data(), t_doc.size() * 4, hipMemcpyHostToDevice, st));
             HIP_TRY(h, hipMemcpyAsync(M.t_word, t_word.data(), t_word.size() * 4, hipMemcpyHostToDevice, st));
             HIP_TRY(h, hipMemcpyAsync(M.t_g, t_g.data(), t_g.size() * 4, hipMemcpyHostToDevice, st));
+            HIP_TRY(h, hipMemcpyAsync(M.order, order.data(), order.size() * 4, hipMemcpyHostToDevice, st));
             HIP_TRY(h, hipMemcpyAsync(M.nz_doc, nz_doc.data(), (size_t)nnz * 4, hipMemcpyHostToDevice, st));
             HIP_TRY(h, hipMemcpyAsync(M.rowidx, rowidx, (size_t)nnz * 4, hipMemcpyHostToDevice, st));
             HIP_TRY(h, hipMemcpyAsync(M.val, val, (size_t)nnz * 4, hipMemcpyHostToDevice, st));
@@ -185,20 +212,12 @@ int check_m(same_lda* h, int32_t m, const Matrix& M)
     return SAME_LDA_OK;
 }
 
-// Threads per block of the draw kernel: as many as fit 64 KiB of LDS.
-int draw_threads(int K)
-{
-    int t = 256;
-    while (t > 64 && same::draw_lds_bytes(K, t) > 64u * 1024u) t >>= 1;
-    return t;
-}
-
 template <bool DEBUG>
 int launch_draw(same_lda* h, const same::DrawArgs& a, bool uniform, hipStream_t st)
 {
     if (a.n <= 0) return SAME_LDA_OK;
-    const int T = draw_threads(a.K);
-    const size_t lds = same::draw_lds_bytes(a.K, T);
+    const int T = same::kWave;
+    const size_t lds = same::draw_lds_bytes(a.K);
     const int64_t blocks = (a.n + T - 1) / T;
     if (blocks >= (int64_t)1 << 31) return fail(h, SAME_LDA_EINVAL, "too many draw tasks for one launch");
     const bool vec = (a.K % same::kBlk) == 0;
@@ -210,13 +229,20 @@ int launch_draw(same_lda* h, const same::DrawArgs& a, bool uniform, hipStream_t 
     return SAME_LDA_OK;
 }
 
+#ifdef SAME_STATS
+unsigned long long* g_stats = nullptr;   // profiling builds only
+#endif
+
 same::DrawArgs draw_args(const same_lda* h, const Matrix& M, uint32_t m, uint32_t pass_word, bool with_words)
 {
     same::DrawArgs a;
-    a.n = M.n_tasks; a.t_doc = M.t_doc; a.t_word = M.t_word; a.t_g = M.t_g; a.ids = nullptr;
+    a.n = M.n_tasks; a.t_doc = M.t_doc; a.t_word = M.t_word; a.t_g = M.t_g; a.order = M.order; a.ids = nullptr;
     a.theta = M.theta; a.phi = h->phi; a.ndk = M.ndk; a.nwk = with_words ? h->nwk : nullptr;
     a.K = h->K; a.m = m; a.seed_lo = (uint32_t)h->seed; a.seed_hi = (uint32_t)(h->seed >> 32);
     a.pass = pass_word;
+#ifdef SAME_STATS
+    a.stats = g_stats;
+#endif
     return a;
 }
 
@@ -313,7 +339,7 @@ int same_lda_init(same_lda_t** out, const same_lda_csc* X, int32_t K, float alph
     if (!out) return fail(nullptr, SAME_LDA_EINVAL, "out is null");
     *out = nullptr;
     if (!X) return fail(nullptr, SAME_LDA_EINVAL, "matrix is null");
-    if (K < 1 || K > 4096) return fail(nullptr, SAME_LDA_EINVAL, "K must be in [1, 4096] (got %d)", K);
+    if (K < 1 || K > 2048) return fail(nullptr, SAME_LDA_EINVAL, "K must be in [1, 2048] (got %d)", K);
     if (!(alpha > 0.f) || !(beta > 0.f) || !std::isfinite(alpha) || !std::isfinite(beta))
         return fail(nullptr, SAME_LDA_EINVAL, "alpha and beta must be positive and finite");
     if (X->V < 1) return fail(nullptr, SAME_LDA_EINVAL, "V must be >= 1 (got %d)", X->V);
@@ -521,6 +547,11 @@ int same_lda_synchronize(same_lda_t* h)
     HIP_TRY(h, hipStreamSynchronize(h->stream));
     return SAME_LDA_OK;
 }
+
+#ifdef SAME_STATS
+// Profiling builds only: device array of 8 event counters filled by the draw kernel.
+void same_lda_stats_buffer(unsigned long long* device_counters) { g_stats = device_counters; }
+#endif
 
 const char* same_lda_last_error(const same_lda_t* h)
 {
