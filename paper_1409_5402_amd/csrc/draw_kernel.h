@@ -4,7 +4,8 @@
 // Mapping: one wave per workgroup, one lane per draw task (a group of tokens of one nonzero).
 // A lane walks the K topics of its task twice.
 //   pass 1  accumulates the running sums P_k = w_0 + ... + w_k left to right
-//           (w_k = theta[d][k] * phi[w][k]) and checkpoints P at every 16th topic in LDS;
+//           (w_k = theta[d][k] * phi[w][k]), checkpoints P at every 16th topic in LDS and finds
+//           the heaviest topic;
 //   pass 2  revisits the 16-topic blocks from the last to the first, rebuilds P_k inside the
 //           block from its checkpoint, generates the topics' uniforms (one Philox block per 4
 //           topics) and tests every topic: a topic whose uniform already proves that its
@@ -13,10 +14,11 @@
 // The heaviest topic of the task is never drawn (it keeps the remainder); for a topic below it the
 // undecided weight is P_k plus the heaviest weight.  The queue is drained by a per-lane state
 // machine that runs the chain n_k ~ Bin(R, w_k / M_k), R -= n_k with the exact division and the
-// exact inversion sampler:
-// every trip of the drain loop lets each lane either fetch its next queued topic (re-testing it
-// against the now exact remaining count) or advance its pmf walk by up to four steps, so lanes
-// with long walks do not hold up lanes with many short ones.
+// exact inversion sampler: every trip of the drain loop lets each lane either fetch its next
+// queued topic (re-testing it against the now exact remaining count) or advance its pmf walk by a
+// few steps, so lanes with long walks do not hold up lanes with many short ones.  A binomial that
+// the sampler cuts into several pieces (independent, one uniform each) is handed to the whole wave,
+// one piece per lane.
 //
 // The drop test is conservative and never changes a result.  For a single-piece binomial with
 // R <= Rb trials and success probability q <= 1/2 the sampler returns 0 iff u <= (1-q)^R
@@ -31,10 +33,16 @@
 
 namespace same {
 
-constexpr int kWave = 64;   // lanes per workgroup (one wave)
-constexpr int kBlk = 16;    // topics per checkpoint block
-constexpr int kQCap = 12;   // queued candidates per lane between drains (drain when > kQCap - 4)
-constexpr int kInvTab = 256;
+#ifndef SAME_QCAP
+#define SAME_QCAP 12
+#endif
+#ifndef SAME_WALK_STEPS
+#define SAME_WALK_STEPS 4
+#endif
+constexpr int kWave = 64;               // lanes per workgroup (one wave)
+constexpr int kBlk = 16;                // topics per checkpoint block
+constexpr int kQCap = SAME_QCAP;        // queued topics per lane between drains (drain when > kQCap - 4)
+constexpr int kWalkSteps = SAME_WALK_STEPS;   // pmf steps per trip of the drain loop
 
 struct DrawArgs {
     int64_t         n;          // tasks in this launch
@@ -42,6 +50,7 @@ struct DrawArgs {
     const int32_t*  t_word;     // [n_tasks] word of the task
     const uint32_t* t_g;        // [n_tasks] tokens in the task's group
     const int32_t*  order;      // [n_tasks] task id handled at each launch position
+    uint32_t*       cost;       // [n_tasks] out: drain trips this task was busy for (null: not recorded)
     const int64_t*  ids;        // debug launches: task ids to draw instead (else null)
     const float*    theta;      // [D][K]   (unused when weights are uniform)
     const float*    phi;        // [V][K]
@@ -68,10 +77,24 @@ __device__ __forceinline__ float weight(const float* __restrict__ th, const floa
     return th[k] * ph[k];
 }
 
+// Sixteen phi values of one block, loaded ahead of their use (K % 16 == 0 only).
+struct PhiBlock { float4 v[kBlk / 4]; };
+
+template <bool UNIFORM, bool VEC>
+__device__ __forceinline__ PhiBlock load_phi(const float* __restrict__ ph, int b)
+{
+    PhiBlock r;
+    if (!UNIFORM && VEC) {
+#pragma unroll
+        for (int v = 0; v < kBlk / 4; ++v) r.v[v] = *reinterpret_cast<const float4*>(ph + b * kBlk + 4 * v);
+    }
+    return r;
+}
+
 // The 16 weights of block b (zero beyond K).
 template <bool UNIFORM, bool VEC>
 __device__ __forceinline__ void block_weights(const float* __restrict__ th, const float* __restrict__ ph,
-                                              int b, int K, float (&wv)[kBlk])
+                                              const PhiBlock& pre, int b, int K, float (&wv)[kBlk])
 {
     const int k0 = b * kBlk;
     if (UNIFORM) {
@@ -79,15 +102,15 @@ __device__ __forceinline__ void block_weights(const float* __restrict__ th, cons
         for (int j = 0; j < kBlk; ++j) wv[j] = (k0 + j < K) ? 1.0f : 0.0f;
         return;
     }
-    if (VEC) {   // K % 16 == 0: four aligned 16-byte loads per operand
+    if (VEC) {
 #pragma unroll
         for (int v = 0; v < kBlk / 4; ++v) {
-            const float4 a = *reinterpret_cast<const float4*>(th + k0 + 4 * v);
-            const float4 c = *reinterpret_cast<const float4*>(ph + k0 + 4 * v);
-            wv[4 * v + 0] = a.x * c.x;
-            wv[4 * v + 1] = a.y * c.y;
-            wv[4 * v + 2] = a.z * c.z;
-            wv[4 * v + 3] = a.w * c.w;
+            const float4 t = *reinterpret_cast<const float4*>(th + k0 + 4 * v);
+            const float4 c = pre.v[v];
+            wv[4 * v + 0] = t.x * c.x;
+            wv[4 * v + 1] = t.y * c.y;
+            wv[4 * v + 2] = t.z * c.z;
+            wv[4 * v + 3] = t.w * c.w;
         }
     } else {
 #pragma unroll
@@ -96,11 +119,21 @@ __device__ __forceinline__ void block_weights(const float* __restrict__ th, cons
 }
 
 // true when Bin(R', q) is certainly 0 for every R' <= Rf (see the header comment)
-__device__ __forceinline__ bool surely_zero(float wk, float Pk, float u, float Rf)
+__device__ __forceinline__ bool surely_zero(float wk, float Mk, float u, float Rf)
 {
-    const float qa = wk * __builtin_amdgcn_rcpf(Pk);
+    const float qa = wk * __builtin_amdgcn_rcpf(Mk);
     const float tt = Rf * (qa * 1.00001f + 1.0e-6f);
     return (qa <= 0.499f) && ((u + tt) <= 0.99999f);
+}
+
+// 1/x for an integer-valued x in [1, 2^24): the hardware reciprocal followed by one Newton step
+// equals the correctly rounded quotient for every such x (checked exhaustively by the library's
+// self-test), at a third of the cost of a full division.
+__device__ __forceinline__ float inv_int(float x)
+{
+    const float y = __builtin_amdgcn_rcpf(x);
+    const float e = __builtin_fmaf(-x, y, 1.0f);
+    return __builtin_fmaf(y, e, y);
 }
 
 template <bool UNIFORM, bool VEC, bool DEBUG>
@@ -110,12 +143,9 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
     const int lane = threadIdx.x;
     const int K = a.K;
     const int nblk = (K + kBlk - 1) / kBlk;
-    float*    inv_tab = reinterpret_cast<float*>(lds);             // [kInvTab]  1/x, correctly rounded
-    float*    chk = inv_tab + kInvTab;                             // [nblk][64]
-    uint32_t* que = lds + kInvTab + (size_t)nblk * kWave;          // [kQCap][4][64]
-
-    for (int i = lane; i < kInvTab; i += kWave) inv_tab[i] = 1.0f / (float)i;
-    __syncthreads();
+    const int qw = K <= 512 ? 3 : 4;                               // words per queue entry
+    float*    chk = reinterpret_cast<float*>(lds);                 // [nblk][64]
+    uint32_t* que = lds + (size_t)nblk * kWave;                    // [kQCap][qw][64]
 
     // lanes past the end take the last task with zero copies: all loads stay valid, nothing is emitted
     const int64_t slot = (int64_t)blockIdx.x * kWave + lane;
@@ -140,67 +170,63 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
     int kstar = 0;
     {
         float P = 0.0f;
+        PhiBlock cur = load_phi<UNIFORM, VEC>(ph, 0);
         for (int b = 0; b < nblk; ++b) {
+            PhiBlock nxt = cur;
+            if (b + 1 < nblk) nxt = load_phi<UNIFORM, VEC>(ph, b + 1);
             chk[b * kWave + lane] = P;
             float wv[kBlk];
-            block_weights<UNIFORM, VEC>(th, ph, b, K, wv);
+            block_weights<UNIFORM, VEC>(th, ph, cur, b, K, wv);
 #pragma unroll
             for (int j = 0; j < kBlk; ++j) {
                 P = P + wv[j];
                 const int k = b * kBlk + j;
                 if ((VEC || k < K) && wv[j] >= wmax) { wmax = wv[j]; kstar = k; }
             }
+            cur = nxt;
         }
     }
 
     uint32_t R = N;
     int cnt = 0;
-#ifdef SAME_STATS
-    uint32_t st_wave_trips = 0, st_lane_trips = 0;
-#endif
+    uint32_t busy = 0;      // drain trips in which this lane still had work: its cost for the next ordering
 
-#ifdef SAME_NO_ATOMICS   // timing experiments only: results are wrong
-    uint32_t sink = 0;
-    auto emit = [&](int k, uint32_t n) { sink += n * (uint32_t)(k + 1); };
-#else
     auto emit = [&](int k, uint32_t n) {
         atomicAdd(out_d + k, n);
         if (out_w) atomicAdd(out_w + k, n);
     };
-#endif
 
     // ---- the conditional-binomial chain over the queued topics (descending k), as a state machine
     auto drain = [&]() {
         int e = 0;
-        int st = 0;                    // 0: fetch the next queued topic, 1: walking a piece, 2: queue exhausted
+        int st = 0;   // 0: fetch the next queued topic, 1: walking a single piece, 2: queue exhausted,
+                      // 3: holds a binomial of several pieces for the whole wave to work on
         // state of the binomial in flight
-        uint32_t bR = 0, rem = 0, L = 0, piece = 0, total = 0, n = 0, xw = 0;
-        float sc = 0.f, r = 0.f, pmL = 0.f, pm = 0.f, cdf = 0.f, u = 0.f;
+        uint32_t bR = 0, L = 0, xw = 0;
+        float sc = 0.f, r = 0.f, pm = 0.f, cdf = 0.f, u = 0.f;
         bool flip = false, stalled = false;
         int kk = 0;
-        uint32_t xb[4] = {0u, 0u, 0u, 0u};
         if (lane == 0) SAME_COUNT(a, 0, 1);                      // drains
         SAME_COUNT(a, 1, cnt);                                     // queued topics
         for (;;) {
             if (lane == 0) SAME_COUNT(a, 2, 1);                  // drain loop trips
-#ifdef SAME_STATS
-            st_wave_trips += 1; if (st != 2) st_lane_trips += 1;
-#endif
+            busy += (st != 2) ? 1u : 0u;
             if (st == 0) {
                 bool found = false;
-                float wq = 0.f, Pq = 1.f;
+                float wq = 0.f, Mq = 1.f;
                 while (e < cnt && R > 0) {
-                    wq = __uint_as_float(que[(e * 4 + 0) * kWave + lane]);
-                    Pq = __uint_as_float(que[(e * 4 + 1) * kWave + lane]);
-                    u = uniform_from_word(que[(e * 4 + 2) * kWave + lane]);
-                    kk = (int)que[(e * 4 + 3) * kWave + lane];
+                    wq = __uint_as_float(que[(e * qw + 0) * kWave + lane]);
+                    Mq = __uint_as_float(que[(e * qw + 1) * kWave + lane]);
+                    const uint32_t xk = que[(e * qw + 2) * kWave + lane];
+                    kk = qw == 3 ? (int)(xk & 511u) : (int)que[(e * qw + 3) * kWave + lane];
+                    u = uniform_from_word(xk);
                     ++e;
-                    if (!surely_zero(wq, Pq, u, (float)R)) { found = true; break; }
+                    if (!surely_zero(wq, Mq, u, (float)R)) { found = true; break; }
                 }
                 if (!found) {
                     st = 2;
                 } else {
-                    const float q = wq / Pq;
+                    const float q = wq / Mq;
                     if (q >= 1.0f) {
                         emit(kk, R);
                         R = 0;
@@ -209,52 +235,94 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
                         const float qq = flip ? 1.0f - q : q;
                         sc = 1.0f - qq;
                         r = qq / sc;
-                        const bool single = ((float)R * qq) <= 32.0f;
-                        L = single ? R : (uint32_t)(32.0f / qq);
-                        pmL = ipow(sc, L);
-                        bR = R; rem = R; piece = 0; total = 0;
-                        n = L;                      // L <= R: the first piece is a full one
-                        xw = 0; pm = pmL; cdf = pmL; stalled = false;
-                        st = 1;
+                        bR = R;
                         SAME_COUNT(a, 3, 1);                       // binomials set up
-                        if (!single) SAME_COUNT(a, 6, 1);          // ... of which in several pieces
+                        if (((float)R * qq) <= 32.0f) {            // one piece of R trials
+                            L = R;
+                            const float pm0 = ipow(sc, R);
+                            xw = 0; pm = pm0; cdf = pm0; stalled = false;
+                            st = 1;
+                        } else {                                   // pieces of L trials: shared by the wave
+                            L = (uint32_t)(32.0f / qq);
+                            st = 3;
+                            SAME_COUNT(a, 6, 1);                   // binomials in several pieces
+                        }
                     }
                 }
             }
             if (!__any(st != 2)) break;
-            if (st == 1) {
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    if (!stalled && u > cdf && xw < n) {
-                        SAME_COUNT(a, 4, 1);                       // walk steps
-                        if (L < bR) SAME_COUNT(a, 7, 1);           // ... of which inside multi-piece binomials
-                        xw += 1;
-                        const float inv_x = xw < (uint32_t)kInvTab ? inv_tab[xw] : 1.0f / (float)xw;
-                        pm = pm * r;
-                        pm = pm * (float)(n - xw + 1u);
-                        pm = pm * inv_x;
-                        const float next = cdf + pm;
-                        if (next == cdf) stalled = true; else cdf = next;
+
+            // Binomials cut into pieces: the pieces are independent (own uniform each), so the 64
+            // lanes take one piece each; the owner lane receives the total.
+            for (uint64_t pend = __ballot(st == 3); pend != 0; pend &= pend - 1) {
+                const int src = __ffsll((unsigned long long)pend) - 1;
+                const uint32_t cR = __shfl(bR, src), cL = __shfl(L, src);
+                const float csc = __shfl(sc, src), cr = __shfl(r, src), cu0 = __shfl(u, src);
+                const uint32_t ck = (uint32_t)__shfl(kk, src);
+                StreamKey ckey = key;
+                ckey.tau_lo = __shfl(key.tau_lo, src);
+                ckey.tau_hi = __shfl(key.tau_hi, src);
+                const uint32_t npieces = (cR + cL - 1u) / cL;
+                const float cpmL = ipow(csc, cL);
+                uint32_t part = 0;
+                for (uint32_t base = 0; base < npieces; base += kWave) {
+                    const uint32_t jp = base + (uint32_t)lane;
+                    if (jp < npieces) {
+                        const uint32_t nj = (jp == npieces - 1u) ? cR - jp * cL : cL;
+                        float pmj = (nj == cL) ? cpmL : ipow(csc, nj);
+                        float uj = cu0;
+                        if (jp > 0) {
+                            uint32_t xb[4];
+                            piece_block(ckey, ck, (jp - 1u) >> 2, xb);
+                            const uint32_t sel = (jp - 1u) & 3u;
+                            uj = uniform_from_word(sel == 0u ? xb[0] : sel == 1u ? xb[1] : sel == 2u ? xb[2] : xb[3]);
+                        }
+                        uint32_t xj = 0;
+                        float cdfj = pmj;
+                        while (uj > cdfj && xj < nj) {
+                            xj += 1;
+                            pmj = pmj * cr;
+                            pmj = pmj * (float)(nj - xj + 1u);
+                            pmj = pmj * inv_int((float)xj);
+                            const float next = cdfj + pmj;
+                            if (next == cdfj) break;
+                            cdfj = next;
+                        }
+                        part += xj;
                     }
                 }
-                if (stalled || !(u > cdf && xw < n)) {          // this piece is finished
-                    total += xw;
-                    rem -= n;
-                    if (rem > 0) {                               // next piece of the same binomial
-                        piece += 1;
-                        n = rem < L ? rem : L;
-                        const float pm0 = (n == L) ? pmL : ipow(sc, n);
-                        const uint32_t j = piece - 1u;
-                        if ((j & 3u) == 0u) piece_block(key, (uint32_t)kk, j >> 2, xb);
-                        const uint32_t word = (j & 3u) == 0u ? xb[0] : (j & 3u) == 1u ? xb[1] : (j & 3u) == 2u ? xb[2] : xb[3];
-                        u = uniform_from_word(word);
-                        xw = 0; pm = pm0; cdf = pm0; stalled = false;
-                    } else {
-                        const uint32_t nk = flip ? bR - total : total;
-                        if (nk > 0) { emit(kk, nk); SAME_COUNT(a, 5, 1); }   // nonzero counts
-                        R -= nk;
-                        st = 0;
-                    }
+#pragma unroll
+                for (int off = kWave / 2; off > 0; off >>= 1) part += __shfl_xor(part, off);
+                if (lane == src) {
+                    const uint32_t nk = flip ? bR - part : part;
+                    if (nk > 0) { emit(kk, nk); SAME_COUNT(a, 5, 1); }
+                    R -= nk;
+                    st = 0;
+                }
+            }
+
+            if (__any(st == 1)) {
+                const bool walking = st == 1;
+#pragma unroll
+                for (int i = 0; i < kWalkSteps; ++i) {
+                    const bool go = walking && !stalled && u > cdf && xw < L;
+                    const uint32_t xn = xw + 1u;
+                    float pmn = pm * r;
+                    pmn = pmn * (float)(L - xn + 1u);
+                    pmn = pmn * inv_int((float)xn);
+                    const float next = cdf + pmn;
+                    const bool still = next == cdf;
+                    if (go) SAME_COUNT(a, 4, 1);                   // walk steps
+                    xw = go ? xn : xw;
+                    pm = go ? pmn : pm;
+                    cdf = (go && !still) ? next : cdf;
+                    stalled = stalled || (go && still);
+                }
+                if (walking && (stalled || !(u > cdf && xw < L))) {   // the piece is finished
+                    const uint32_t nk = flip ? bR - xw : xw;
+                    if (nk > 0) { emit(kk, nk); SAME_COUNT(a, 5, 1); }   // nonzero counts
+                    R -= nk;
+                    st = 0;
                 }
             }
         }
@@ -262,52 +330,57 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
     };
 
     // ---- pass 2: blocks from last to first
-    for (int b = nblk - 1; b >= 0; --b) {
-        if (!__any(R > 0)) break;
-        float wv[kBlk], Pv[kBlk];
-        block_weights<UNIFORM, VEC>(th, ph, b, K, wv);
-        {
-            float P = chk[b * kWave + lane];
+    {
+        PhiBlock cur = load_phi<UNIFORM, VEC>(ph, nblk - 1);
+        for (int b = nblk - 1; b >= 0; --b) {
+            if (!__any(R > 0)) break;
+            PhiBlock nxt = cur;
+            if (b > 0) nxt = load_phi<UNIFORM, VEC>(ph, b - 1);
+            float wv[kBlk], Pv[kBlk];
+            block_weights<UNIFORM, VEC>(th, ph, cur, b, K, wv);
+            cur = nxt;
+            {
+                float P = chk[b * kWave + lane];
 #pragma unroll
-            for (int j = 0; j < kBlk; ++j) { P = P + wv[j]; Pv[j] = P; }
-        }
-        float Rb = (float)R;   // bound on the remaining count until the next drain
-#pragma unroll
-        for (int g = kBlk / 4 - 1; g >= 0; --g) {
-            uint32_t x[4];
-            primary_block(key, (uint32_t)(b * (kBlk / 4) + g), x);
-#pragma unroll
-            for (int j = 3; j >= 0; --j) {
-                const int k = b * kBlk + g * 4 + j;
-                const float wk = wv[g * 4 + j];
-                const float Pk = Pv[g * 4 + j] + (k < kstar ? wmax : 0.0f);   // weight not yet decided at k
-                const bool cand = (k != kstar) && (wk > 0.0f) && !surely_zero(wk, Pk, uniform_from_word(x[j]), Rb);
-                if (cand) {
-                    que[(cnt * 4 + 0) * kWave + lane] = __float_as_uint(wk);
-                    que[(cnt * 4 + 1) * kWave + lane] = __float_as_uint(Pk);
-                    que[(cnt * 4 + 2) * kWave + lane] = x[j];
-                    que[(cnt * 4 + 3) * kWave + lane] = (uint32_t)k;
-                    cnt += 1;
-                }
+                for (int j = 0; j < kBlk; ++j) { P = P + wv[j]; Pv[j] = P; }
             }
-            if (__any(cnt > kQCap - 4)) { drain(); Rb = (float)R; }
+            float Rb = (float)R;   // bound on the remaining count until the next drain
+#pragma unroll
+            for (int g = kBlk / 4 - 1; g >= 0; --g) {
+                uint32_t x[4];
+                primary_block(key, (uint32_t)(b * (kBlk / 4) + g), x);
+#pragma unroll
+                for (int j = 3; j >= 0; --j) {
+                    const int k = b * kBlk + g * 4 + j;
+                    const float wk = wv[g * 4 + j];
+                    const float Mk = Pv[g * 4 + j] + (k < kstar ? wmax : 0.0f);   // weight not yet decided at k
+                    const bool cand = (k != kstar) && (wk > 0.0f) && !surely_zero(wk, Mk, uniform_from_word(x[j]), Rb);
+                    if (cand) {
+                        que[(cnt * qw + 0) * kWave + lane] = __float_as_uint(wk);
+                        que[(cnt * qw + 1) * kWave + lane] = __float_as_uint(Mk);
+                        if (qw == 3) {
+                            que[(cnt * qw + 2) * kWave + lane] = (x[j] & ~511u) | (uint32_t)k;   // the uniform uses the top 23 bits
+                        } else {
+                            que[(cnt * qw + 2) * kWave + lane] = x[j];
+                            que[(cnt * qw + 3) * kWave + lane] = (uint32_t)k;
+                        }
+                        cnt += 1;
+                    }
+                }
+                if (__any(cnt > kQCap - 4)) { drain(); Rb = (float)R; }
+            }
         }
     }
     drain();
     if (R > 0) emit(kstar, R);
-#ifdef SAME_NO_ATOMICS
-    if (sink == 0xFFFFFFFFu) atomicAdd(out_d, sink);
-#endif
-#ifdef SAME_STATS
-    if (lane == 0) SAME_COUNT(a, 8 + (32 - __clz(st_wave_trips)), 1);      // histogram of trips per wave (log2)
-    if (live) SAME_COUNT(a, 24 + (32 - __clz(st_lane_trips)), 1);          // histogram of busy trips per lane
-#endif
+    if (!DEBUG && live && a.cost) a.cost[tau] = busy;
 }
 
 inline size_t draw_lds_bytes(int K)
 {
     const int nblk = (K + kBlk - 1) / kBlk;
-    return 4u * (size_t)(kInvTab + kWave * (nblk + 4 * kQCap));
+    const int qw = K <= 512 ? 3 : 4;
+    return 4u * (size_t)kWave * (size_t)(nblk + qw * kQCap);
 }
 
 }  // namespace same

@@ -56,15 +56,17 @@ __device__ __forceinline__ void piece_block(const StreamKey& s, uint32_t k, uint
     philox4x32_10(s.tau_lo, s.tau_hi | (pb << 8), 0x80000000u | k, s.pass, s.seed_lo, s.seed_hi, out);
 }
 
-// s^n by binary square-and-multiply, least significant bit first.
+// s^n by binary square-and-multiply, least significant bit first.  The loop runs for the longest
+// exponent among the active lanes without per-lane branches; squarings past a lane's last set
+// bit are never multiplied into its result.
 __device__ __forceinline__ float ipow(float s, uint32_t n)
 {
     float result = 1.0f, base = s;
     uint32_t e = n;
-    while (e > 0) {
-        if (e & 1u) result = result * base;
+    while (__any(e > 0)) {
+        result = (e & 1u) ? result * base : result;
+        base = base * base;
         e >>= 1;
-        if (e > 0) base = base * base;
     }
     return result;
 }

@@ -4,7 +4,6 @@
 
 #include <hip/hip_runtime.h>
 
-#include <algorithm>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -32,6 +31,9 @@ struct Matrix {
     int32_t*  t_word = nullptr;    // [n_tasks]
     uint32_t* t_g = nullptr;       // [n_tasks]
     int32_t*  order = nullptr;     // [n_tasks] task id processed at each launch position
+    int32_t*  tile_start = nullptr;// [n_tiles+1] first task id of every document tile
+    uint32_t* cost = nullptr;      // [n_tasks] drain work each task reported in the last pass
+    int32_t   n_tiles = 0;
     int32_t*  nz_doc = nullptr;    // [nnz]
     int32_t*  rowidx = nullptr;    // [nnz]
     float*    val = nullptr;       // [nnz]
@@ -89,7 +91,7 @@ int dev_alloc(same_lda* h, T** p, size_t n)
 
 void free_matrix(Matrix& M)
 {
-    hipFree(M.t_doc); hipFree(M.t_word); hipFree(M.t_g); hipFree(M.order); hipFree(M.nz_doc);
+    hipFree(M.t_doc); hipFree(M.t_word); hipFree(M.t_g); hipFree(M.order); hipFree(M.tile_start); hipFree(M.cost); hipFree(M.nz_doc);
     hipFree(M.rowidx); hipFree(M.val); hipFree(M.theta); hipFree(M.ndk);
     M = Matrix();
 }
@@ -150,31 +152,26 @@ int build_matrix(same_lda* h, const same_lda_csc* X, int32_t V, int32_t K, int32
         }
         if (t_doc.size() >= ((size_t)1 << 31))
             return fail(h, SAME_LDA_ECSC, "too many draw tasks (%zu); raise tokens_per_draw", t_doc.size());
-        // Processing order: documents are taken in tiles of kTileDocs; inside a tile the tasks are
-        // sorted by word.  Neighbouring lanes then work on the same or similar words (similar chain
-        // lengths, shared phi rows) while their theta rows stay within one small tile.  The order
-        // does not affect results: tasks are independent and keyed by their id.
-        std::vector<int32_t> order(t_doc.size());
-        {
-            std::vector<uint64_t> keys;
-            size_t begin = 0;
-            while (begin < t_doc.size()) {
-                const int32_t tile = t_doc[begin] / kTileDocs;
-                size_t end = begin;
-                while (end < t_doc.size() && t_doc[end] / kTileDocs == tile) ++end;
-                keys.resize(end - begin);
-                for (size_t i = begin; i < end; ++i) keys[i - begin] = ((uint64_t)(uint32_t)t_word[i] << 32) | (uint64_t)(i - begin);
-                std::sort(keys.begin(), keys.end());
-                for (size_t i = begin; i < end; ++i) order[i] = (int32_t)(begin + (size_t)(keys[i - begin] & 0xFFFFFFFFu));
-                begin = end;
-            }
+        // Processing order: documents are taken in tiles of kTileDocs (the theta rows a wave touches
+        // stay within one small tile); inside a tile the order starts as storage order and is
+        // re-sorted before every sweep by the cost each task reported in the previous pass, so that
+        // the 64 lanes of a wave run chains of similar length.  The order does not affect results:
+        // tasks are independent and keyed by their id.
+        std::vector<int32_t> order(t_doc.size()), tile_start;
+        for (size_t i = 0; i < t_doc.size(); ++i) {
+            order[i] = (int32_t)i;
+            if (i == 0 || t_doc[i] / kTileDocs != t_doc[i - 1] / kTileDocs) tile_start.push_back((int32_t)i);
         }
+        tile_start.push_back((int32_t)t_doc.size());
+        M.n_tiles = (int32_t)tile_start.size() - 1;
         M.D = D; M.nnz = nnz; M.n_tasks = (int64_t)t_doc.size(); M.max_group = max_group; M.tokens = tokens;
         int rc;
         if ((rc = dev_alloc(h, &M.t_doc, t_doc.size()))) return rc;
         if ((rc = dev_alloc(h, &M.t_word, t_word.size()))) return rc;
         if ((rc = dev_alloc(h, &M.t_g, t_g.size()))) return rc;
         if ((rc = dev_alloc(h, &M.order, order.size()))) return rc;
+        if ((rc = dev_alloc(h, &M.tile_start, tile_start.size()))) return rc;
+        if ((rc = dev_alloc(h, &M.cost, order.size()))) return rc;
         if ((rc = dev_alloc(h, &M.nz_doc, (size_t)nnz))) return rc;
         if ((rc = dev_alloc(h, &M.rowidx, (size_t)nnz))) return rc;
         if ((rc = dev_alloc(h, &M.val, (size_t)nnz))) return rc;
@@ -185,6 +182,8 @@ int build_matrix(same_lda* h, const same_lda_csc* X, int32_t V, int32_t K, int32
             HIP_TRY(h, hipMemcpyAsync(M.t_word, t_word.data(), t_word.size() * 4, hipMemcpyHostToDevice, st));
             HIP_TRY(h, hipMemcpyAsync(M.t_g, t_g.data(), t_g.size() * 4, hipMemcpyHostToDevice, st));
             HIP_TRY(h, hipMemcpyAsync(M.order, order.data(), order.size() * 4, hipMemcpyHostToDevice, st));
+            HIP_TRY(h, hipMemcpyAsync(M.tile_start, tile_start.data(), tile_start.size() * 4, hipMemcpyHostToDevice, st));
+            HIP_TRY(h, hipMemsetAsync(M.cost, 0, order.size() * 4, st));
             HIP_TRY(h, hipMemcpyAsync(M.nz_doc, nz_doc.data(), (size_t)nnz * 4, hipMemcpyHostToDevice, st));
             HIP_TRY(h, hipMemcpyAsync(M.rowidx, rowidx, (size_t)nnz * 4, hipMemcpyHostToDevice, st));
             HIP_TRY(h, hipMemcpyAsync(M.val, val, (size_t)nnz * 4, hipMemcpyHostToDevice, st));
@@ -236,7 +235,7 @@ unsigned long long* g_stats = nullptr;   // profiling builds only
 same::DrawArgs draw_args(const same_lda* h, const Matrix& M, uint32_t m, uint32_t pass_word, bool with_words)
 {
     same::DrawArgs a;
-    a.n = M.n_tasks; a.t_doc = M.t_doc; a.t_word = M.t_word; a.t_g = M.t_g; a.order = M.order; a.ids = nullptr;
+    a.n = M.n_tasks; a.t_doc = M.t_doc; a.t_word = M.t_word; a.t_g = M.t_g; a.order = M.order; a.cost = M.cost; a.ids = nullptr;
     a.theta = M.theta; a.phi = h->phi; a.ndk = M.ndk; a.nwk = with_words ? h->nwk : nullptr;
     a.K = h->K; a.m = m; a.seed_lo = (uint32_t)h->seed; a.seed_hi = (uint32_t)(h->seed >> 32);
     a.pass = pass_word;
@@ -295,6 +294,11 @@ int run_pass(same_lda* h, Matrix& M, uint32_t m, uint32_t pword, bool uniform, b
             HIP_TRY(h, hipEventCreate(&ev.second));
         }
         HIP_TRY(h, hipEventRecord(ev.first, st));
+    }
+    if (!uniform && M.n_tiles > 0) {
+        hipLaunchKernelGGL(same::reorder_kernel, dim3((unsigned)M.n_tiles), dim3(256), 0, st, M.tile_start, M.cost,
+                           M.order);
+        HIP_TRY(h, hipGetLastError());
     }
     const same::DrawArgs a = draw_args(h, M, m, pword, with_words);
     if ((rc = launch_draw<false>(h, a, uniform, st))) return rc;
@@ -505,7 +509,7 @@ int same_lda_debug_draw(same_lda_t* h, int32_t m_t, const int64_t* task_ids, int
     if (!rc) rc = zero_u32(h, out_d, (size_t)n * h->K, h->stream);
     if (!rc) {
         same::DrawArgs a = draw_args(h, h->X, (uint32_t)m_t, pass_word(h->pass, 0), false);
-        a.n = n; a.ids = ids_d; a.ndk = out_d; a.nwk = nullptr;
+        a.n = n; a.ids = ids_d; a.ndk = out_d; a.nwk = nullptr; a.cost = nullptr;
         rc = launch_draw<true>(h, a, false, h->stream);
     }
     if (!rc) {

@@ -20,6 +20,29 @@ __global__ void zero_u64_kernel(unsigned long long* __restrict__ p, size_t n)
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = 0ull;
 }
 
+// Re-sorts the processing order of one document tile by descending cost (counting sort over 256
+// cost buckets; ties land in arbitrary order, which only affects scheduling, never results).
+__global__ __launch_bounds__(256) void reorder_kernel(const int32_t* __restrict__ tile_start,
+                                                      const uint32_t* __restrict__ cost,
+                                                      int32_t* __restrict__ order)
+{
+    __shared__ uint32_t bins[256];
+    const int t0 = tile_start[blockIdx.x], t1 = tile_start[blockIdx.x + 1];
+    bins[threadIdx.x] = 0u;
+    __syncthreads();
+    for (int i = t0 + (int)threadIdx.x; i < t1; i += 256) atomicAdd(&bins[min(cost[i], 255u)], 1u);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t acc = 0u;
+        for (int b = 255; b >= 0; --b) { const uint32_t c = bins[b]; bins[b] = acc; acc += c; }
+    }
+    __syncthreads();
+    for (int i = t0 + (int)threadIdx.x; i < t1; i += 256) {
+        const uint32_t pos = atomicAdd(&bins[min(cost[i], 255u)], 1u);
+        order[t0 + (int)pos] = i;
+    }
+}
+
 // n_k = sum over words of n_wk[w][k], exact in 64-bit integers (any order gives the same value).
 // Each block sums a slab of rows; thread t owns column (t mod K') of every row group.
 __global__ void topic_totals_kernel(const uint32_t* __restrict__ nwk, int V, int K,
