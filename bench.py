@@ -28,6 +28,18 @@ def draw_kernel_bytes(nnz: int, D: int, K: int) -> float:
     return float(nnz) * (8 + 4 * K) + float(D) * (4 + 8 * K)
 
 
+def measured_traffic(workload: str):
+    """HBM bytes per draw-kernel launch from the committed rocprofv3 counter summary (None if absent)."""
+    path = os.path.join(ROOT, "profiles", f"draw_kernel_{workload}_pmc.md")
+    try:
+        for line in open(path):
+            if line.startswith("hbm_bytes_per_launch"):
+                return float(line.split("=")[1].split()[0])
+    except OSError:
+        pass
+    return None
+
+
 def cpu_baseline(X_np, K, alpha, beta, m, m0, G, target_s=12.0):
     """Times one sweep of the oracle (as it stands) on a leading slice of documents sized for ~target_s."""
     import oracle
@@ -51,8 +63,9 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=100,
-                    help="untimed sweeps before timing: all but the last 5 run with m=1 (burn-in), the last 5 with m")
+    ap.add_argument("--warmup", type=int, default=140,
+                    help="untimed sweeps before timing: all but the last 40 run with m=1 (annealing burn-in), "
+                         "the last 40 with the workload's m; the timed sweeps then complete a 50-sweep run at m")
     ap.add_argument("--workload", default="news")
     ap.add_argument("--scale", type=float, default=1.0, help="fraction of the workload's documents (1.0 = full size)")
     ap.add_argument("--tokens-per-draw", type=int, default=8)
@@ -89,7 +102,7 @@ def main():
     t_init = time.perf_counter() - t0
 
     for s in range(args.warmup):
-        g.sweep(1 if s < args.warmup - 5 else m)
+        g.sweep(1 if s < args.warmup - 40 else m)
     g.synchronize()
     g.set_timing(True)
     torch.cuda.synchronize()
@@ -118,10 +131,10 @@ def main():
                    "K": K, "m": m, "nnz": st["nnz"], "tokens": st["tokens"], "max_count": st["max_count"],
                    "tokens_per_draw": G, "draw_tasks": g.task_count, "alpha": alpha, "beta": beta,
                    "m_init": m0,
-                   "warmup_schedule": f"{max(0, args.warmup - 5)} sweeps at m=1 then {min(5, args.warmup)} at m={m}",
+                   "warmup_schedule": f"{max(0, args.warmup - 40)} sweeps at m=1 then {min(40, args.warmup)} at m={m}",
                    "generate_s": round(t_gen, 2), "init_s": round(t_init, 2)},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(args.workload),
                      "kernel": "draw_kernel", "kernel_ms": draw_ms_avg, "bytes_per_launch": bytes_per_launch},
     }
     if test is not None and not args.no_loglik:

@@ -20,7 +20,8 @@ _DTYPES = {THETA: np.float32, PHI: np.float32, NDK: np.uint32, NWK: np.uint32, N
 
 EXPORTS = ["same_lda_init", "same_lda_sweep", "same_lda_loglik", "same_lda_free", "same_lda_set_batch",
            "same_lda_get", "same_lda_set", "same_lda_get_pass", "same_lda_set_pass", "same_lda_task_count",
-           "same_lda_debug_draw", "same_lda_set_timing", "same_lda_get_timing", "same_lda_synchronize",
+           "same_lda_debug_draw", "same_lda_set_timing", "same_lda_get_timing", "same_lda_selftest",
+           "same_lda_synchronize",
            "same_lda_last_error"]
 
 
@@ -60,6 +61,7 @@ def load() -> ctypes.CDLL:
         L.same_lda_debug_draw.argtypes = [c_void_p, c_int32, c_void_p, c_int32, c_void_p]
         L.same_lda_set_timing.argtypes = [c_void_p, c_int32]
         L.same_lda_get_timing.argtypes = [c_void_p, POINTER(c_double), POINTER(c_int64)]
+        L.same_lda_selftest.argtypes = [POINTER(c_int64)]
         L.same_lda_synchronize.argtypes = [c_void_p]
         L.same_lda_last_error.argtypes = [c_void_p]
         L.same_lda_last_error.restype = c_char_p
@@ -98,6 +100,16 @@ def _csc(D, V, colptr, rowidx, val):
         nnz = int(arrs[1].size)
     c = _Csc(int(D), int(V), nnz, ptrs[0], ptrs[1], ptrs[2], on_device)
     return c, keep
+
+
+def selftest() -> int:
+    """Runs the library's device self-test; returns the number of mismatches (0 = pass)."""
+    L = load()
+    n = c_int64()
+    rc = L.same_lda_selftest(byref(n))
+    if rc != 0:
+        raise SameLdaError(rc, L.same_lda_last_error(None).decode())
+    return n.value
 
 
 class SameLDA:
@@ -150,6 +162,15 @@ class SameLDA:
         return out
 
     def set(self, which, arr):
+        """arr: a numpy array (host) or a torch tensor (host or device) of the matrix' shape and dtype."""
+        if _is_torch(arr):
+            import torch
+            t = arr.contiguous()
+            assert tuple(t.shape) == self._shape(which) and t.dtype == torch.float32
+            nbytes = t.numel() * t.element_size()
+            self._check(self._lib.same_lda_set(self._h, which, t.data_ptr() if nbytes else None, nbytes,
+                                               1 if t.device.type == "cuda" else 0))
+            return
         a = np.ascontiguousarray(arr, dtype=_DTYPES[which])
         assert a.shape == self._shape(which)
         self._check(self._lib.same_lda_set(self._h, which, a.ctypes.data if a.size else None, a.nbytes, 0))

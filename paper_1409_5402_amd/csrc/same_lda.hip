@@ -12,7 +12,6 @@
 #include <string>
 #include <vector>
 
-#include "draw_kernel.h"
 #include "update_kernels.h"
 
 namespace {
@@ -542,6 +541,24 @@ int same_lda_get_timing(same_lda_t* h, double* draw_ms_total, int64_t* launches)
     *draw_ms_total = total;
     *launches = (int64_t)h->events.size();
     h->events.clear();
+    return SAME_LDA_OK;
+}
+
+int same_lda_selftest(int64_t* failures)
+{
+    if (!failures) return fail(nullptr, SAME_LDA_EINVAL, "failures is null");
+    unsigned long long* d = nullptr;
+    unsigned long long got = 0;
+    HIP_TRY(nullptr, hipMalloc(reinterpret_cast<void**>(&d), sizeof(unsigned long long)));
+    hipError_t e = hipMemset(d, 0, sizeof(unsigned long long));
+    if (e == hipSuccess) {
+        hipLaunchKernelGGL(same::selftest_kernel, dim3((1u << 24) / 256u), dim3(256), 0, nullptr, d);
+        e = hipGetLastError();
+    }
+    if (e == hipSuccess) e = hipMemcpy(&got, d, sizeof got, hipMemcpyDeviceToHost);
+    hipFree(d);
+    if (e != hipSuccess) return fail(nullptr, SAME_LDA_EHIP, "selftest: %s", hipGetErrorString(e));
+    *failures = (int64_t)got;
     return SAME_LDA_OK;
 }
 

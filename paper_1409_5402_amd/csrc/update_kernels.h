@@ -6,7 +6,30 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "draw_kernel.h"
+
 namespace same {
+
+// Self-test: reciprocal of every integer in [1, 2^24) and the published Philox known answers.
+__global__ void selftest_kernel(unsigned long long* __restrict__ failures)
+{
+    const uint32_t x = blockIdx.x * blockDim.x + threadIdx.x;
+    if (x >= 1u && x < (1u << 24)) {
+        const float fx = (float)x;
+        if (inv_int(fx) != 1.0f / fx) atomicAdd(failures, 1ull);
+    }
+    if (x < 3u) {
+        const uint32_t in[3][6] = {{0u, 0u, 0u, 0u, 0u, 0u},
+                                   {0xffffffffu, 0xffffffffu, 0xffffffffu, 0xffffffffu, 0xffffffffu, 0xffffffffu},
+                                   {0x243f6a88u, 0x85a308d3u, 0x13198a2eu, 0x03707344u, 0xa4093822u, 0x299f31d0u}};
+        const uint32_t want[3][4] = {{0x6627e8d5u, 0xe169c58du, 0xbc57ac4cu, 0x9b00dbd8u},
+                                     {0x408f276du, 0x41c83b0eu, 0xa20bc7c6u, 0x6d5451fdu},
+                                     {0xd16cfe09u, 0x94fdccebu, 0x5001e420u, 0x24126ea1u}};
+        uint32_t out[4];
+        philox4x32_10(in[x][0], in[x][1], in[x][2], in[x][3], in[x][4], in[x][5], out);
+        for (int i = 0; i < 4; ++i) if (out[i] != want[x][i]) atomicAdd(failures, 1ull);
+    }
+}
 
 __global__ void zero_u32_kernel(uint32_t* __restrict__ p, size_t n)
 {

@@ -49,8 +49,8 @@ class Corpus:
                       self.rowidx[a:b].contiguous(), self.val[a:b].contiguous(), dict(self.meta))
 
     def stats(self) -> dict:
-        word_tokens = torch.zeros(self.V, dtype=torch.float64, device=self.val.device)
-        word_tokens.index_add_(0, self.rowidx.long(), self.val.double())
+        word_tokens = torch.zeros(self.V, dtype=torch.float32, device=self.val.device)
+        word_tokens.index_add_(0, self.rowidx.long(), self.val)      # informational (float32 sums)
         return {"D": self.D, "V": self.V, "nnz": self.nnz, "tokens": self.tokens,
                 "max_count": int(self.val.max().item()) if self.nnz else 0,
                 "max_word_tokens": int(word_tokens.max().item()) if self.nnz else 0}
@@ -128,6 +128,29 @@ def generate(D: int, V: int, K: int, alpha: float, beta: float, seed: int,
     meta = {"K_true": K, "alpha_true": alpha, "beta_true": beta, "seed": seed, "length": length,
             "mean_len": mean_len, "sigma": sigma, "zipf_s": zipf_s}
     return Corpus(D, V, colptr.to(torch.int32), rowidx.contiguous(), counts.to(torch.float32), meta)
+
+
+def state(corpus: Corpus, K: int, alpha: float, beta: float, seed: int, zipf_s: float = 0.0):
+    """A seeded, concentrated parameter state shaped like a trained sampler's: theta [D][K] =
+    alpha + document length * Dirichlet(alpha) row, phi [V][K] with every topic a Dirichlet(beta)
+    distribution over words (optionally Zipf-skewed).  Returned as float32 tensors on the corpus' device."""
+    device = corpus.val.device
+    gen = torch.Generator(device=device)
+    gen.manual_seed(int(seed))
+    lens = torch.zeros(corpus.D, dtype=torch.float64, device=device)
+    doc_of = torch.repeat_interleave(torch.arange(corpus.D, device=device), (corpus.colptr[1:] - corpus.colptr[:-1]).long())
+    lens.index_add_(0, doc_of, corpus.val.double())
+    theta = torch.empty(corpus.D, K, dtype=torch.float32, device=device)
+    for lo in range(0, corpus.D, 50_000):
+        hi = min(corpus.D, lo + 50_000)
+        theta[lo:hi] = (alpha + lens[lo:hi, None] * _dirichlet_rows(hi - lo, K, alpha, gen, device)).float()
+    phi_kv = _dirichlet_rows(K, corpus.V, beta, gen, device)
+    if zipf_s > 0.0:
+        rank = torch.arange(1, corpus.V + 1, dtype=torch.float64, device=device)
+        phi_kv = phi_kv * rank.pow(-zipf_s)
+        phi_kv = phi_kv / phi_kv.sum(dim=1, keepdim=True)
+    phi = phi_kv.t().contiguous().float().clamp_min_(1e-30)
+    return theta, phi
 
 
 # Workload presets (shapes of the paper's experiments; K and m are the sampler's settings).
