@@ -68,7 +68,7 @@ def main():
                          "the last 40 with the workload's m; the timed sweeps then complete a 50-sweep run at m")
     ap.add_argument("--workload", default="news")
     ap.add_argument("--scale", type=float, default=1.0, help="fraction of the workload's documents (1.0 = full size)")
-    ap.add_argument("--tokens-per-draw", type=int, default=8)
+    ap.add_argument("--tokens-per-draw", type=int, default=32)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-loglik", action="store_true")
     args = ap.parse_args()

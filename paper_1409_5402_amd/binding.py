@@ -115,7 +115,7 @@ def selftest() -> int:
 class SameLDA:
     """A SAME Gibbs LDA model resident on the current GPU (one handle of the C library)."""
 
-    def __init__(self, D, V, colptr, rowidx, val, K, alpha, beta, seed, m0, tokens_per_draw=8, stream=None):
+    def __init__(self, D, V, colptr, rowidx, val, K, alpha, beta, seed, m0, tokens_per_draw=32, stream=None):
         self._lib = load()
         self._h = c_void_p()
         self.V, self.K, self.D = int(V), int(K), int(D)

@@ -239,3 +239,37 @@ def test_empty_matrix():
     np.testing.assert_allclose(g.get(binding.THETA), 0.1, rtol=1e-6)
     np.testing.assert_allclose(g.get(binding.PHI), 0.1, rtol=1e-6)       # beta / (V * beta)
     g.close()
+
+
+@pytest.mark.parametrize("K", [1024, 2048])
+def test_many_topics_news_shape(K):
+    """K=1024 (the many-topics workload) and the largest supported K: queue entries switch to four
+    words above K=512 and the checkpoint area grows; news-shaped slice, m=100."""
+    X = corpus_to_csc(synth.preset("news_k1024", scale=0.0004))
+    alpha = 50.0 / K
+    o = oracle.OracleLDA(X, K, alpha, 0.01, seed=11, m0=1, G=32)
+    g = make_gpu(X, K, alpha, 0.01, 11, 1, 32, on_device=True)
+    assert_state_equal(g, o, "init")
+    for s, m in enumerate([1, 100, 100]):
+        o.sweep(m); g.sweep(m)
+        assert_state_equal(g, o, f"K={K} sweep {s + 1} m={m}")
+    g.close()
+
+
+def test_streamed_minibatches_abstract_shape():
+    """Abstract-collection shape (V=140k, Poisson 90, Zipf 1.05): three minibatches streamed through
+    same_lda_set_batch with a geometric m schedule and rho_t blending; K reduced to keep the oracle fast."""
+    c = synth.generate(D=900, V=140_000, K=64, alpha=0.1, beta=0.01, seed=4, length="poisson", mean_len=90.0, zipf_s=1.05)
+    X = corpus_to_csc(c)
+    batches = [X.slice_docs(0, 300), X.slice_docs(300, 600), X.slice_docs(600, 900)]
+    ms = schedule.geometric(1, 100, 3)
+    K = 64
+    o = oracle.OracleLDA(batches[0], K, 0.1, 0.01, seed=9, m0=ms[0], G=32)
+    g = make_gpu(batches[0], K, 0.1, 0.01, 9, ms[0], 32)
+    for t, (B, m) in enumerate(zip(batches, ms)):
+        if t > 0:
+            o.set_batch(B, m); g.set_batch(B.D, B.colptr, B.rowidx, B.val, m)
+        rho = float(np.float32(schedule.rho(t)))
+        o.sweep(m, rho); g.sweep(m, rho)
+        assert_state_equal(g, o, f"minibatch {t} m={m} rho={rho}")
+    g.close()
