@@ -24,10 +24,9 @@
 // R <= Rb trials and success probability q <= 1/2 the sampler returns 0 iff u <= (1-q)^R
 // evaluated in binary32 by square-and-multiply; that value is >= 1 - Rb*(q + 2^-22)
 // (Bernoulli's inequality plus at most 2R roundings of relative size 2^-24 and the rounding of
-// 1-q).  The test uses an approximate quotient q~ (hardware reciprocal, relative error
-// < 2^-21) and checks q~ <= 0.499 (so the sampler does not take its complement branch) and
-// u + Rb*(q~*(1+1e-5) + 1e-6) <= 1 - 1e-5, which implies the former (and Rb*q < 1 implies a
-// single piece).
+// 1-q).  The test checks q <= 0.499 (so the sampler does not take its complement branch) and
+// u + Rb*(q*(1+1e-4) + 1e-6) <= 1 - 1e-4, evaluated without a division (see ZeroTest), which
+// implies the former (and Rb*q < 1 implies a single piece).  A topic of zero weight passes it.
 #pragma once
 #include "rng_binom.h"
 
@@ -118,13 +117,21 @@ __device__ __forceinline__ void block_weights(const float* __restrict__ th, cons
     }
 }
 
-// true when Bin(R', q) is certainly 0 for every R' <= Rf (see the header comment)
-__device__ __forceinline__ bool surely_zero(float wk, float Mk, float u, float Rf)
-{
-    const float qa = wk * __builtin_amdgcn_rcpf(Mk);
-    const float tt = Rf * (qa * 1.00001f + 1.0e-6f);
-    return (qa <= 0.499f) && ((u + tt) <= 0.99999f);
-}
+// The drop test without a division: for q = w/M it checks q <= 0.499 and
+// u + Rf*(q*(1+1e-4) + 1e-6) <= 1 - 1e-4, both multiplied through by M > 0
+// (the margins cover the few roundings of this evaluation).  ZeroTest holds the two terms that
+// depend only on the bound Rf; x is the raw random word of the topic (u = (2*(x>>9)+1)/2^24).
+struct ZeroTest {
+    float A, Bp;
+    __device__ __forceinline__ explicit ZeroTest(float Rf)
+        : A(Rf * 1.0001f), Bp((0.9999f - Rf * 1.0e-6f) - 5.9604644775390625e-8f) {}
+    // true when Bin(R', w/M) is certainly 0 for every R' <= Rf (see the header comment)
+    __device__ __forceinline__ bool surely_zero(float wk, float Mk, uint32_t x) const
+    {
+        const float d = __builtin_fmaf((float)(x >> 9), -1.1920928955078125e-7f, Bp);   // (1-1e-4) - Rf*1e-6 - u
+        return (wk <= 0.499f * Mk) && (A * wk <= d * Mk);
+    }
+};
 
 // 1/x for an integer-valued x in [1, 2^24): the hardware reciprocal followed by one Newton step
 // equals the correctly rounded quotient for every such x (checked exhaustively by the library's
@@ -221,7 +228,7 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
                     kk = qw == 3 ? (int)(xk & 511u) : (int)que[(e * qw + 3) * kWave + lane];
                     u = uniform_from_word(xk);
                     ++e;
-                    if (!surely_zero(wq, Mq, u, (float)R)) { found = true; break; }
+                    if (!ZeroTest((float)R).surely_zero(wq, Mq, xk)) { found = true; break; }
                 }
                 if (!found) {
                     st = 2;
@@ -344,7 +351,7 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
 #pragma unroll
                 for (int j = 0; j < kBlk; ++j) { P = P + wv[j]; Pv[j] = P; }
             }
-            float Rb = (float)R;   // bound on the remaining count until the next drain
+            ZeroTest zt((float)R);   // R bounds the remaining count until the next drain
 #pragma unroll
             for (int g = kBlk / 4 - 1; g >= 0; --g) {
                 uint32_t x[4];
@@ -354,7 +361,7 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
                     const int k = b * kBlk + g * 4 + j;
                     const float wk = wv[g * 4 + j];
                     const float Mk = Pv[g * 4 + j] + (k < kstar ? wmax : 0.0f);   // weight not yet decided at k
-                    const bool cand = (k != kstar) && (wk > 0.0f) && !surely_zero(wk, Mk, uniform_from_word(x[j]), Rb);
+                    const bool cand = (k != kstar) && !zt.surely_zero(wk, Mk, x[j]);   // a zero weight passes the test
                     if (cand) {
                         que[(cnt * qw + 0) * kWave + lane] = __float_as_uint(wk);
                         que[(cnt * qw + 1) * kWave + lane] = __float_as_uint(Mk);
@@ -367,7 +374,7 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
                         cnt += 1;
                     }
                 }
-                if (__any(cnt > kQCap - 4)) { drain(); Rb = (float)R; }
+                if (__any(cnt > kQCap - 4)) { drain(); zt = ZeroTest((float)R); }
             }
         }
     }
