@@ -41,7 +41,13 @@ namespace same {
 constexpr int kWave = 64;               // lanes per workgroup (one wave)
 constexpr int kBlk = 16;                // topics per checkpoint block
 constexpr int kQCap = SAME_QCAP;        // queued topics per lane between drains (drain when > kQCap - 4)
-constexpr int kWalkSteps = SAME_WALK_STEPS;   // pmf steps per trip of the drain loop
+constexpr int kPairWords = 16;          // words of a pair-list slot: a count and up to 15 (topic, count) pairs
+constexpr int kPairShift = 11;          // a pair is topic | count << 11 (topics < 2048, counts < 2^21)
+constexpr int kWalkSteps = SAME_WALK_STEPS;   // pmf steps per trip of the chain machine
+#ifndef SAME_POOL_MIN
+#define SAME_POOL_MIN 8
+#endif
+constexpr int kPoolMin = SAME_POOL_MIN;       // waiting multi-piece binomials that trigger a shared pass
 
 struct DrawArgs {
     int64_t         n;          // tasks in this launch
@@ -55,6 +61,8 @@ struct DrawArgs {
     const float*    phi;        // [V][K]
     uint32_t*       ndk;        // [D][K]   (debug launches: [n][K] output rows)
     uint32_t*       nwk;        // [V][K] or null
+    uint32_t*       pairs;      // [n_slots][kPairWords] pair list in word order, or null (update nwk directly)
+    const int32_t*  t_slot;     // [n_tasks] slot of each task in the pair list, -1 for a task without one
     int32_t         K;
     uint32_t        m;
     uint32_t        seed_lo, seed_hi, pass;
@@ -152,7 +160,9 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
     const int nblk = (K + kBlk - 1) / kBlk;
     const int qw = K <= 512 ? 3 : 4;                               // words per queue entry
     float*    chk = reinterpret_cast<float*>(lds);                 // [nblk][64]
-    uint32_t* que = lds + (size_t)nblk * kWave;                    // [kQCap][qw][64]
+    uint32_t* que = lds + (size_t)nblk * kWave;                    // [kQCap][qw][64], a ring per lane
+    uint32_t* acc = que + (size_t)kQCap * qw * kWave;              // [64] piece totals by owner lane
+    acc[lane] = 0u;
 
     // lanes past the end take the last task with zero copies: all loads stay valid, nothing is emitted
     const int64_t slot = (int64_t)blockIdx.x * kWave + lane;
@@ -194,151 +204,175 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
         }
     }
 
-    uint32_t R = N;
-    int cnt = 0;
-    uint32_t busy = 0;      // drain trips in which this lane still had work: its cost for the next ordering
+    // ---- the conditional-binomial chain over the queued topics (descending k), a per-lane state
+    // machine that lives across the whole scan
+    uint32_t R = N;         // copies not yet placed (the heaviest topic keeps what is left at the end)
+    int qh = 0, cnt = 0;    // ring queue: position of the oldest entry, entries queued
+    int st = 0;             // 0: between binomials, 1: walking a single piece,
+                            // 3: holds a binomial of several pieces, waiting for the wave to share it
+    uint32_t bR = 0, L = 0, xw = 0;
+    float sc = 0.f, r = 0.f, pm = 0.f, cdf = 0.f, u = 0.f;
+    bool flip = false, stalled = false;
+    int kk = 0;
+    uint32_t busy = 0;      // trips in which this lane had work: its cost for the next ordering
 
+    // Every placed count goes to the document's row at once.  The word's row is updated either the
+    // same way or, when the launch has a pair list, later by word_reduce_kernel: the task records
+    // (topic, count) in its slot of the list (slots are in word order), so that the scattered
+    // updates of [V][K] become one streaming pass with all updates of a row close together.
+    const int32_t slot_id = (DEBUG || a.pairs == nullptr || out_w == nullptr) ? -1 : a.t_slot[tau];
+    uint32_t* __restrict__ pslot = slot_id < 0 ? nullptr : a.pairs + (size_t)slot_id * kPairWords;
+    uint32_t npairs = 0;
     auto emit = [&](int k, uint32_t n) {
         atomicAdd(out_d + k, n);
-        if (out_w) atomicAdd(out_w + k, n);
+        if (pslot) {
+            if (npairs < (uint32_t)(kPairWords - 1)) pslot[1u + npairs] = (uint32_t)k | (n << kPairShift);
+            else atomicAdd(out_w + k, n);                          // slot full: straight to the row
+            npairs += 1;
+        } else if (out_w) {
+            atomicAdd(out_w + k, n);
+        }
     };
 
-    // ---- the conditional-binomial chain over the queued topics (descending k), as a state machine
-    auto drain = [&]() {
-        int e = 0;
-        int st = 0;   // 0: fetch the next queued topic, 1: walking a single piece, 2: queue exhausted,
-                      // 3: holds a binomial of several pieces for the whole wave to work on
-        // state of the binomial in flight
-        uint32_t bR = 0, L = 0, xw = 0;
-        float sc = 0.f, r = 0.f, pm = 0.f, cdf = 0.f, u = 0.f;
-        bool flip = false, stalled = false;
-        int kk = 0;
-        if (lane == 0) SAME_COUNT(a, 0, 1);                      // drains
-        SAME_COUNT(a, 1, cnt);                                     // queued topics
-        for (;;) {
-            if (lane == 0) SAME_COUNT(a, 2, 1);                  // drain loop trips
-            busy += (st != 2) ? 1u : 0u;
-            if (st == 0) {
-                bool found = false;
-                float wq = 0.f, Mq = 1.f;
-                while (e < cnt && R > 0) {
-                    wq = __uint_as_float(que[(e * qw + 0) * kWave + lane]);
-                    Mq = __uint_as_float(que[(e * qw + 1) * kWave + lane]);
-                    const uint32_t xk = que[(e * qw + 2) * kWave + lane];
-                    kk = qw == 3 ? (int)(xk & 511u) : (int)que[(e * qw + 3) * kWave + lane];
-                    u = uniform_from_word(xk);
-                    ++e;
-                    if (!ZeroTest((float)R).surely_zero(wq, Mq, xk)) { found = true; break; }
-                }
-                if (!found) {
-                    st = 2;
-                } else {
-                    const float q = wq / Mq;
-                    if (q >= 1.0f) {
-                        emit(kk, R);
-                        R = 0;
-                    } else if (q > 0.0f) {
-                        flip = q > 0.5f;
-                        const float qq = flip ? 1.0f - q : q;
-                        sc = 1.0f - qq;
-                        r = qq / sc;
-                        bR = R;
-                        SAME_COUNT(a, 3, 1);                       // binomials set up
-                        if (((float)R * qq) <= 32.0f) {            // one piece of R trials
-                            L = R;
-                            const float pm0 = ipow(sc, R);
-                            xw = 0; pm = pm0; cdf = pm0; stalled = false;
-                            st = 1;
-                        } else {                                   // pieces of L trials: shared by the wave
-                            L = (uint32_t)(32.0f / qq);
-                            st = 3;
-                            SAME_COUNT(a, 6, 1);                   // binomials in several pieces
-                        }
-                    }
-                }
+    // Binomials cut into pieces.  The pieces are independent (own uniform each): those of all the
+    // lanes in state 3 are numbered consecutively and dealt out over the 64 lanes; every owner
+    // receives the total of its pieces through an LDS counter.
+    auto pool = [&](uint64_t pend) {
+        const uint32_t np = (st == 3) ? (bR + L - 1u) / L : 0u;
+        uint32_t total = 0;
+        for (uint64_t p = pend; p != 0; p &= p - 1) total += __shfl(np, __ffsll((unsigned long long)p) - 1);
+        if (lane == 0) { SAME_COUNT(a, 6, 1); SAME_COUNT(a, 7, total); }
+        for (uint32_t base = 0; base < total; base += kWave) {
+            const uint32_t p = base + (uint32_t)lane;
+            int owner = lane;
+            uint32_t first = 0, off = 0;
+            for (uint64_t q = pend; q != 0; q &= q - 1) {        // the last owner whose first piece is <= p
+                const int src = __ffsll((unsigned long long)q) - 1;
+                if (p >= off) { owner = src; first = off; }
+                off += __shfl(np, src);
             }
-            if (!__any(st != 2)) break;
-
-            // Binomials cut into pieces: the pieces are independent (own uniform each), so the 64
-            // lanes take one piece each; the owner lane receives the total.
-            for (uint64_t pend = __ballot(st == 3); pend != 0; pend &= pend - 1) {
-                const int src = __ffsll((unsigned long long)pend) - 1;
-                const uint32_t cR = __shfl(bR, src), cL = __shfl(L, src);
-                const float csc = __shfl(sc, src), cr = __shfl(r, src), cu0 = __shfl(u, src);
-                const uint32_t ck = (uint32_t)__shfl(kk, src);
-                StreamKey ckey = key;
-                ckey.tau_lo = __shfl(key.tau_lo, src);
-                ckey.tau_hi = __shfl(key.tau_hi, src);
-                const uint32_t npieces = (cR + cL - 1u) / cL;
-                const float cpmL = ipow(csc, cL);
-                uint32_t part = 0;
-                for (uint32_t base = 0; base < npieces; base += kWave) {
-                    const uint32_t jp = base + (uint32_t)lane;
-                    if (jp < npieces) {
-                        const uint32_t nj = (jp == npieces - 1u) ? cR - jp * cL : cL;
-                        float pmj = (nj == cL) ? cpmL : ipow(csc, nj);
-                        float uj = cu0;
-                        if (jp > 0) {
-                            uint32_t xb[4];
-                            piece_block(ckey, ck, (jp - 1u) >> 2, xb);
-                            const uint32_t sel = (jp - 1u) & 3u;
-                            uj = uniform_from_word(sel == 0u ? xb[0] : sel == 1u ? xb[1] : sel == 2u ? xb[2] : xb[3]);
-                        }
-                        uint32_t xj = 0;
-                        float cdfj = pmj;
-                        while (uj > cdfj && xj < nj) {
-                            xj += 1;
-                            pmj = pmj * cr;
-                            pmj = pmj * (float)(nj - xj + 1u);
-                            pmj = pmj * inv_int((float)xj);
-                            const float next = cdfj + pmj;
-                            if (next == cdfj) break;
-                            cdfj = next;
-                        }
-                        part += xj;
-                    }
+            const uint32_t oR = __shfl(bR, owner), oL = __shfl(L, owner), onp = __shfl(np, owner);
+            const float osc = __shfl(sc, owner), orr = __shfl(r, owner), ou = __shfl(u, owner);
+            const uint32_t ok = (uint32_t)__shfl(kk, owner);
+            StreamKey okey = key;
+            okey.tau_lo = __shfl(key.tau_lo, owner);
+            okey.tau_hi = __shfl(key.tau_hi, owner);
+            if (p < total) {
+                const uint32_t jp = p - first;
+                const uint32_t nj = (jp == onp - 1u) ? oR - jp * oL : oL;
+                float pmj = ipow(osc, nj);
+                float uj = ou;
+                if (jp > 0) {
+                    uint32_t xb[4];
+                    piece_block(okey, ok, (jp - 1u) >> 2, xb);
+                    const uint32_t sel = (jp - 1u) & 3u;
+                    uj = uniform_from_word(sel == 0u ? xb[0] : sel == 1u ? xb[1] : sel == 2u ? xb[2] : xb[3]);
                 }
-#pragma unroll
-                for (int off = kWave / 2; off > 0; off >>= 1) part += __shfl_xor(part, off);
-                if (lane == src) {
-                    const uint32_t nk = flip ? bR - part : part;
-                    if (nk > 0) { emit(kk, nk); SAME_COUNT(a, 5, 1); }
-                    R -= nk;
-                    st = 0;
+                uint32_t xj = 0;
+                float cdfj = pmj;
+                while (uj > cdfj && xj < nj) {
+                    xj += 1;
+                    pmj = pmj * orr;
+                    pmj = pmj * (float)(nj - xj + 1u);
+                    pmj = pmj * inv_int((float)xj);
+                    const float next = cdfj + pmj;
+                    if (next == cdfj) break;
+                    cdfj = next;
                 }
+                if (xj > 0) atomicAdd(acc + owner, xj);
             }
+        }
+        __syncthreads();
+        if (st == 3) {
+            const uint32_t part = acc[lane];
+            acc[lane] = 0u;
+            const uint32_t nk = flip ? bR - part : part;
+            if (nk > 0) { emit(kk, nk); SAME_COUNT(a, 5, 1); }
+            R -= nk;
+            st = 0;
+        }
+        __syncthreads();
+    };
 
-            if (__any(st == 1)) {
-                const bool walking = st == 1;
-#pragma unroll
-                for (int i = 0; i < kWalkSteps; ++i) {
-                    const bool go = walking && !stalled && u > cdf && xw < L;
-                    const uint32_t xn = xw + 1u;
-                    float pmn = pm * r;
-                    pmn = pmn * (float)(L - xn + 1u);
-                    pmn = pmn * inv_int((float)xn);
-                    const float next = cdf + pmn;
-                    const bool still = next == cdf;
-                    if (go) SAME_COUNT(a, 4, 1);                   // walk steps
-                    xw = go ? xn : xw;
-                    pm = go ? pmn : pm;
-                    cdf = (go && !still) ? next : cdf;
-                    stalled = stalled || (go && still);
-                }
-                if (walking && (stalled || !(u > cdf && xw < L))) {   // the piece is finished
-                    const uint32_t nk = flip ? bR - xw : xw;
-                    if (nk > 0) { emit(kk, nk); SAME_COUNT(a, 5, 1); }   // nonzero counts
-                    R -= nk;
-                    st = 0;
+    // One trip of the machine for the whole wave: lanes in state 0 take their next queued topic
+    // (re-tested against the now exact remaining count), shared binomials are worked off when enough
+    // of them wait or nothing else is in flight, walking lanes advance by kWalkSteps pmf steps.
+    auto trip = [&]() {
+        if (lane == 0) SAME_COUNT(a, 2, 1);
+        busy += (st != 0 || (cnt > 0 && R > 0)) ? 1u : 0u;
+        if (st == 0) {
+            bool found = false;
+            float wq = 0.f, Mq = 1.f;
+            while (cnt > 0 && R > 0) {
+                wq = __uint_as_float(que[(qh * qw + 0) * kWave + lane]);
+                Mq = __uint_as_float(que[(qh * qw + 1) * kWave + lane]);
+                const uint32_t xk = que[(qh * qw + 2) * kWave + lane];
+                kk = qw == 3 ? (int)(xk & 511u) : (int)que[(qh * qw + 3) * kWave + lane];
+                u = uniform_from_word(xk);
+                qh = (qh + 1 == kQCap) ? 0 : qh + 1;
+                --cnt;
+                if (!ZeroTest((float)R).surely_zero(wq, Mq, xk)) { found = true; break; }
+            }
+            if (R == 0) cnt = 0;                                   // nothing left to place: the rest is void
+            if (found) {
+                const float q = wq / Mq;
+                if (q >= 1.0f) {
+                    emit(kk, R);
+                    R = 0;
+                    cnt = 0;
+                } else if (q > 0.0f) {
+                    flip = q > 0.5f;
+                    const float qq = flip ? 1.0f - q : q;
+                    sc = 1.0f - qq;
+                    r = qq / sc;
+                    bR = R;
+                    SAME_COUNT(a, 3, 1);                           // binomials set up
+                    if (((float)R * qq) <= 32.0f) {                // one piece of R trials
+                        L = R;
+                        const float pm0 = ipow(sc, R);
+                        xw = 0; pm = pm0; cdf = pm0; stalled = false;
+                        st = 1;
+                    } else {                                       // pieces of L trials: shared by the wave
+                        L = (uint32_t)(32.0f / qq);
+                        st = 3;
+                    }
                 }
             }
         }
-        cnt = 0;
+        {
+            const uint64_t pend = __ballot(st == 3);
+            if (pend != 0 && (__popcll((unsigned long long)pend) >= kPoolMin || !__any(st == 1))) pool(pend);
+        }
+        if (__any(st == 1)) {
+            const bool walking = st == 1;
+#pragma unroll
+            for (int i = 0; i < kWalkSteps; ++i) {
+                const bool go = walking && !stalled && u > cdf && xw < L;
+                const uint32_t xn = xw + 1u;
+                float pmn = pm * r;
+                pmn = pmn * (float)(L - xn + 1u);
+                pmn = pmn * inv_int((float)xn);
+                const float next = cdf + pmn;
+                const bool still = next == cdf;
+                if (go) SAME_COUNT(a, 4, 1);                       // walk steps
+                xw = go ? xn : xw;
+                pm = go ? pmn : pm;
+                cdf = (go && !still) ? next : cdf;
+                stalled = stalled || (go && still);
+            }
+            if (walking && (stalled || !(u > cdf && xw < L))) {   // the piece is finished
+                const uint32_t nk = flip ? bR - xw : xw;
+                if (nk > 0) { emit(kk, nk); SAME_COUNT(a, 5, 1); }   // nonzero counts
+                R -= nk;
+                st = 0;
+            }
+        }
     };
 
     // ---- pass 2: blocks from last to first
     {
         PhiBlock cur = load_phi<UNIFORM, VEC>(ph, nblk - 1);
+        ZeroTest zt((float)R);      // R bounds the remaining count from here on
         for (int b = nblk - 1; b >= 0; --b) {
             if (!__any(R > 0)) break;
             PhiBlock nxt = cur;
@@ -351,7 +385,6 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
 #pragma unroll
                 for (int j = 0; j < kBlk; ++j) { P = P + wv[j]; Pv[j] = P; }
             }
-            ZeroTest zt((float)R);   // R bounds the remaining count until the next drain
 #pragma unroll
             for (int g = kBlk / 4 - 1; g >= 0; --g) {
                 uint32_t x[4];
@@ -363,31 +396,80 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
                     const float Mk = Pv[g * 4 + j] + (k < kstar ? wmax : 0.0f);   // weight not yet decided at k
                     const bool cand = (k != kstar) && !zt.surely_zero(wk, Mk, x[j]);   // a zero weight passes the test
                     if (cand) {
-                        que[(cnt * qw + 0) * kWave + lane] = __float_as_uint(wk);
-                        que[(cnt * qw + 1) * kWave + lane] = __float_as_uint(Mk);
+                        int e = qh + cnt;
+                        e = e >= kQCap ? e - kQCap : e;
+                        que[(e * qw + 0) * kWave + lane] = __float_as_uint(wk);
+                        que[(e * qw + 1) * kWave + lane] = __float_as_uint(Mk);
                         if (qw == 3) {
-                            que[(cnt * qw + 2) * kWave + lane] = (x[j] & ~511u) | (uint32_t)k;   // the uniform uses the top 23 bits
+                            que[(e * qw + 2) * kWave + lane] = (x[j] & ~511u) | (uint32_t)k;   // the uniform uses the top 23 bits
                         } else {
-                            que[(cnt * qw + 2) * kWave + lane] = x[j];
-                            que[(cnt * qw + 3) * kWave + lane] = (uint32_t)k;
+                            que[(e * qw + 2) * kWave + lane] = x[j];
+                            que[(e * qw + 3) * kWave + lane] = (uint32_t)k;
                         }
                         cnt += 1;
+                        SAME_COUNT(a, 1, 1);                       // queued topics
                     }
                 }
-                if (__any(cnt > kQCap - 4)) { drain(); zt = ZeroTest((float)R); }
+                // trips are run only while some lane could not take the next four topics
+                if (__any(cnt > kQCap - 4)) {
+                    do { trip(); } while (__any(cnt > kQCap - 4));
+                    zt = ZeroTest((float)R);
+                }
             }
         }
     }
-    drain();
+    while (__any(st != 0 || (cnt > 0 && R > 0))) trip();
     if (R > 0) emit(kstar, R);
+    if (pslot && live) pslot[0] = npairs < (uint32_t)(kPairWords - 1) ? npairs : (uint32_t)(kPairWords - 1);
     if (!DEBUG && live && a.cost) a.cost[tau] = busy;
 }
+
+// Adds the recorded pairs to the word rows.  Slots are in word order and exist only for words with
+// at least kSlotMinTasks tasks: a workgroup takes kReduceChunk consecutive slots, sums the pairs of
+// the first `rows` words it meets in an LDS table and sends the rest straight to [V][K]; the table is
+// then added to the rows it stands for.  Threads start at different pairs of their slots: tasks of
+// one word have their large counts at the same topics, and aligned walks would meet at one address.
+constexpr int kReduceChunk = 2048;
+constexpr int kSlotMinTasks = 32;
+
+__global__ __launch_bounds__(256) void word_reduce_kernel(const uint32_t* __restrict__ pairs,
+                                                          const int32_t* __restrict__ slot_word, int64_t n, int K,
+                                                          int rows, uint32_t* __restrict__ nwk)
+{
+    extern __shared__ uint32_t tab[];                              // [rows][K]
+    const int64_t s0 = (int64_t)blockIdx.x * kReduceChunk;
+    const int64_t s1 = s0 + kReduceChunk < n ? s0 + kReduceChunk : n;
+    const int32_t w0 = slot_word[s0];
+    for (int i = threadIdx.x; i < rows * K; i += blockDim.x) tab[i] = 0u;
+    __syncthreads();
+    for (int64_t s = s0 + threadIdx.x; s < s1; s += blockDim.x) {
+        const uint32_t* __restrict__ src = pairs + (size_t)s * kPairWords;
+        const int32_t w = slot_word[s];
+        const bool in_tab = w - w0 < rows;
+        uint32_t* dst = in_tab ? tab + (size_t)(w - w0) * K : nwk + (size_t)w * K;
+        const uint32_t cnt = src[0];
+        uint32_t idx = (threadIdx.x * cnt) >> 8;                   // start somewhere in [0, cnt)
+        for (uint32_t i = 0; i < cnt; ++i) {
+            const uint32_t p = src[1u + idx];
+            idx = idx + 1u == cnt ? 0u : idx + 1u;
+            atomicAdd(dst + (p & ((1u << kPairShift) - 1u)), p >> kPairShift);
+        }
+    }
+    __syncthreads();
+    uint32_t* base = nwk + (size_t)w0 * K;                         // row w0 + r, topic k is at base[r*K + k]
+    for (int i = threadIdx.x; i < rows * K; i += blockDim.x) {
+        const uint32_t v = tab[i];
+        if (v != 0u) atomicAdd(base + i, v);                       // only rows of real words hold counts
+    }
+}
+
+inline int reduce_rows(int K) { const int r = 16384 / K; return r < 1 ? 1 : (r > 64 ? 64 : r); }
 
 inline size_t draw_lds_bytes(int K)
 {
     const int nblk = (K + kBlk - 1) / kBlk;
     const int qw = K <= 512 ? 3 : 4;
-    return 4u * (size_t)kWave * (size_t)(nblk + qw * kQCap);
+    return 4u * (size_t)kWave * (size_t)(nblk + qw * kQCap + 1);
 }
 
 }  // namespace same

@@ -38,6 +38,11 @@ struct Matrix {
     float*    val = nullptr;       // [nnz]
     float*    theta = nullptr;     // [D][K]
     uint32_t* ndk = nullptr;       // [D][K]
+    // pair list of the word-count update (training matrices only; absent if it did not fit)
+    uint32_t* pairs = nullptr;     // [n_tasks][kPairWords]
+    int64_t   n_slots = 0;         // tasks of frequent words, each with a slot
+    int32_t*  t_slot = nullptr;    // [n_tasks] slot of each task (rank in (word, task id) order), -1 if none
+    int32_t*  slot_word = nullptr; // [n_slots] word of each slot
 };
 
 }  // namespace
@@ -92,11 +97,13 @@ void free_matrix(Matrix& M)
 {
     hipFree(M.t_doc); hipFree(M.t_word); hipFree(M.t_g); hipFree(M.order); hipFree(M.tile_start); hipFree(M.cost); hipFree(M.nz_doc);
     hipFree(M.rowidx); hipFree(M.val); hipFree(M.theta); hipFree(M.ndk);
+    hipFree(M.pairs); hipFree(M.t_slot); hipFree(M.slot_word);
     M = Matrix();
 }
 
 // Validates the matrix, builds the work list on the host and uploads it.
-int build_matrix(same_lda* h, const same_lda_csc* X, int32_t V, int32_t K, int32_t G, Matrix& M, hipStream_t st)
+int build_matrix(same_lda* h, const same_lda_csc* X, int32_t V, int32_t K, int32_t G, Matrix& M, hipStream_t st,
+                 bool with_pairs)
 {
     if (!X) return fail(h, SAME_LDA_EINVAL, "matrix is null");
     if (X->D < 0 || X->V != V || X->nnz < 0 || X->nnz >= (int64_t)1 << 31)
@@ -187,6 +194,38 @@ int build_matrix(same_lda* h, const same_lda_csc* X, int32_t V, int32_t K, int32
             HIP_TRY(h, hipMemcpyAsync(M.rowidx, rowidx, (size_t)nnz * 4, hipMemcpyHostToDevice, st));
             HIP_TRY(h, hipMemcpyAsync(M.val, val, (size_t)nnz * 4, hipMemcpyHostToDevice, st));
         }
+        // Pair list: slots in (word, task id) order for the tasks of frequent words.  Optional: without
+        // it the draw kernel updates the word rows directly.
+        if (with_pairs && M.n_tasks > 0) {
+            std::vector<int32_t> cursor((size_t)V + 1, 0), t_slot(t_word.size());
+            for (int32_t w : t_word) cursor[(size_t)w + 1] += 1;
+            int64_t n_slots = 0;
+            for (int32_t w = 0; w < V; ++w) {                      // cursor[w+1] = tasks of w -> first slot of w, or -1
+                const int32_t c = cursor[(size_t)w + 1];
+                cursor[(size_t)w] = c >= same::kSlotMinTasks ? (int32_t)n_slots : -1;
+                if (c >= same::kSlotMinTasks) n_slots += c;
+            }
+            std::vector<int32_t> slot_word((size_t)n_slots);
+            for (size_t i = 0; i < t_word.size(); ++i) {
+                int32_t& cur = cursor[(size_t)t_word[i]];
+                t_slot[i] = cur;
+                if (cur >= 0) { slot_word[(size_t)cur] = t_word[i]; cur += 1; }
+            }
+            const size_t n = t_word.size();
+            if (n_slots > 0 &&
+                hipMalloc(reinterpret_cast<void**>(&M.pairs), (size_t)n_slots * same::kPairWords * sizeof(uint32_t)) == hipSuccess &&
+                hipMalloc(reinterpret_cast<void**>(&M.t_slot), n * 4) == hipSuccess &&
+                hipMalloc(reinterpret_cast<void**>(&M.slot_word), (size_t)n_slots * 4) == hipSuccess) {
+                M.n_slots = n_slots;
+                HIP_TRY(h, hipMemcpyAsync(M.t_slot, t_slot.data(), n * 4, hipMemcpyHostToDevice, st));
+                HIP_TRY(h, hipMemcpyAsync(M.slot_word, slot_word.data(), (size_t)n_slots * 4, hipMemcpyHostToDevice, st));
+                HIP_TRY(h, hipStreamSynchronize(st));
+            } else {
+                (void)hipGetLastError();
+                hipFree(M.pairs); hipFree(M.t_slot); hipFree(M.slot_word);
+                M.pairs = nullptr; M.t_slot = nullptr; M.slot_word = nullptr; M.n_slots = 0;
+            }
+        }
         HIP_TRY(h, hipStreamSynchronize(st));   // the host vectors go out of scope below
     } catch (const std::bad_alloc&) {
         return fail(h, SAME_LDA_ENOMEM, "host allocation failed while building the work list");
@@ -236,6 +275,10 @@ same::DrawArgs draw_args(const same_lda* h, const Matrix& M, uint32_t m, uint32_
     same::DrawArgs a;
     a.n = M.n_tasks; a.t_doc = M.t_doc; a.t_word = M.t_word; a.t_g = M.t_g; a.order = M.order; a.cost = M.cost; a.ids = nullptr;
     a.theta = M.theta; a.phi = h->phi; a.ndk = M.ndk; a.nwk = with_words ? h->nwk : nullptr;
+    // a pair holds a count below 2^(32 - kPairShift): m * largest group must fit
+    const bool pairs_fit = (uint64_t)m * (uint64_t)(M.max_group ? M.max_group : 1u) < (1ull << (32 - same::kPairShift));
+    a.pairs = (with_words && M.pairs && pairs_fit) ? M.pairs : nullptr;
+    a.t_slot = M.t_slot;
     a.K = h->K; a.m = m; a.seed_lo = (uint32_t)h->seed; a.seed_hi = (uint32_t)(h->seed >> 32);
     a.pass = pass_word;
 #ifdef SAME_STATS
@@ -285,6 +328,12 @@ int run_pass(same_lda* h, Matrix& M, uint32_t m, uint32_t pword, bool uniform, b
     int rc;
     if ((rc = zero_u32(h, M.ndk, (size_t)M.D * h->K, st))) return rc;
     if (with_words && (rc = zero_u32(h, h->nwk, (size_t)h->V * h->K, st))) return rc;
+    if (!uniform && M.n_tiles > 0) {
+        hipLaunchKernelGGL(same::reorder_kernel, dim3((unsigned)M.n_tiles), dim3(256), 0, st, M.tile_start, M.cost,
+                           M.order);
+        HIP_TRY(h, hipGetLastError());
+    }
+    // the events bracket the draw kernel alone
     std::pair<hipEvent_t, hipEvent_t> ev{nullptr, nullptr};
     if (timed) {
         if (!h->pool.empty()) { ev = h->pool.back(); h->pool.pop_back(); }
@@ -294,16 +343,19 @@ int run_pass(same_lda* h, Matrix& M, uint32_t m, uint32_t pword, bool uniform, b
         }
         HIP_TRY(h, hipEventRecord(ev.first, st));
     }
-    if (!uniform && M.n_tiles > 0) {
-        hipLaunchKernelGGL(same::reorder_kernel, dim3((unsigned)M.n_tiles), dim3(256), 0, st, M.tile_start, M.cost,
-                           M.order);
-        HIP_TRY(h, hipGetLastError());
-    }
     const same::DrawArgs a = draw_args(h, M, m, pword, with_words);
     if ((rc = launch_draw<false>(h, a, uniform, st))) return rc;
     if (timed) {
         HIP_TRY(h, hipEventRecord(ev.second, st));
         h->events.push_back(ev);
+    }
+    if (a.pairs && a.n > 0) {
+        const int rows = same::reduce_rows(h->K);
+        const int64_t blocks = (M.n_slots + same::kReduceChunk - 1) / same::kReduceChunk;
+        hipLaunchKernelGGL(same::word_reduce_kernel, dim3((unsigned)blocks), dim3(256),
+                           (size_t)rows * h->K * sizeof(uint32_t), st, a.pairs, M.slot_word, M.n_slots, h->K, rows,
+                           h->nwk);
+        HIP_TRY(h, hipGetLastError());
     }
     return SAME_LDA_OK;
 }
@@ -351,7 +403,7 @@ int same_lda_init(same_lda_t** out, const same_lda_csc* X, int32_t K, float alph
     if (!h) return fail(nullptr, SAME_LDA_ENOMEM, "host allocation failed");
     h->V = X->V; h->K = K; h->G = tokens_per_draw; h->alpha = alpha; h->beta = beta; h->seed = seed;
     h->stream = static_cast<hipStream_t>(hip_stream);
-    int rc = build_matrix(h, X, h->V, K, h->G, h->X, h->stream);
+    int rc = build_matrix(h, X, h->V, K, h->G, h->X, h->stream, true);
     if (!rc) rc = check_m(h, m0, h->X);
     if (!rc) rc = dev_alloc(h, &h->phi, (size_t)h->V * K);
     if (!rc) rc = dev_alloc(h, &h->nwk, (size_t)h->V * K);
@@ -383,7 +435,7 @@ int same_lda_set_batch(same_lda_t* h, const same_lda_csc* X, int32_t m_init)
     if (!h) return SAME_LDA_EINVAL;
     HIP_TRY(h, hipStreamSynchronize(h->stream));
     Matrix M;
-    int rc = build_matrix(h, X, h->V, h->K, h->G, M, h->stream);
+    int rc = build_matrix(h, X, h->V, h->K, h->G, M, h->stream, true);
     if (!rc) rc = check_m(h, m_init, M);
     if (rc) { free_matrix(M); return rc; }
     free_matrix(h->X);
@@ -400,7 +452,7 @@ int same_lda_loglik(same_lda_t* h, const same_lda_csc* Xtest, int32_t foldin_swe
     if (!h) return SAME_LDA_EINVAL;
     if (!ll_per_word || foldin_sweeps < 0) return fail(h, SAME_LDA_EINVAL, "bad loglik arguments");
     Matrix M;
-    int rc = build_matrix(h, Xtest, h->V, h->K, h->G, M, h->stream);
+    int rc = build_matrix(h, Xtest, h->V, h->K, h->G, M, h->stream, false);
     if (!rc) rc = check_m(h, m_eval, M);
     double* doc_log = nullptr; double* part = nullptr;
     const int nblocks = (int)((M.nnz + 255) / 256);
