@@ -84,16 +84,19 @@ __device__ __forceinline__ float weight(const float* __restrict__ th, const floa
     return th[k] * ph[k];
 }
 
-// Sixteen phi values of one block, loaded ahead of their use (K % 16 == 0 only).
-struct PhiBlock { float4 v[kBlk / 4]; };
+// The sixteen theta and phi values of one block, loaded ahead of their use (K % 16 == 0 only).
+struct PhiBlock { float4 v[kBlk / 4]; float4 t[kBlk / 4]; };
 
 template <bool UNIFORM, bool VEC>
-__device__ __forceinline__ PhiBlock load_phi(const float* __restrict__ ph, int b)
+__device__ __forceinline__ PhiBlock load_phi(const float* __restrict__ th, const float* __restrict__ ph, int b)
 {
     PhiBlock r;
     if (!UNIFORM && VEC) {
 #pragma unroll
-        for (int v = 0; v < kBlk / 4; ++v) r.v[v] = *reinterpret_cast<const float4*>(ph + b * kBlk + 4 * v);
+        for (int v = 0; v < kBlk / 4; ++v) {
+            r.v[v] = *reinterpret_cast<const float4*>(ph + b * kBlk + 4 * v);
+            r.t[v] = *reinterpret_cast<const float4*>(th + b * kBlk + 4 * v);
+        }
     }
     return r;
 }
@@ -112,7 +115,7 @@ __device__ __forceinline__ void block_weights(const float* __restrict__ th, cons
     if (VEC) {
 #pragma unroll
         for (int v = 0; v < kBlk / 4; ++v) {
-            const float4 t = *reinterpret_cast<const float4*>(th + k0 + 4 * v);
+            const float4 t = pre.t[v];
             const float4 c = pre.v[v];
             wv[4 * v + 0] = t.x * c.x;
             wv[4 * v + 1] = t.y * c.y;
@@ -187,10 +190,10 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
     int kstar = 0;
     {
         float P = 0.0f;
-        PhiBlock cur = load_phi<UNIFORM, VEC>(ph, 0);
+        PhiBlock cur = load_phi<UNIFORM, VEC>(th, ph, 0);
         for (int b = 0; b < nblk; ++b) {
             PhiBlock nxt = cur;
-            if (b + 1 < nblk) nxt = load_phi<UNIFORM, VEC>(ph, b + 1);
+            if (b + 1 < nblk) nxt = load_phi<UNIFORM, VEC>(th, ph, b + 1);
             chk[b * kWave + lane] = P;
             float wv[kBlk];
             block_weights<UNIFORM, VEC>(th, ph, cur, b, K, wv);
@@ -371,12 +374,12 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
 
     // ---- pass 2: blocks from last to first
     {
-        PhiBlock cur = load_phi<UNIFORM, VEC>(ph, nblk - 1);
+        PhiBlock cur = load_phi<UNIFORM, VEC>(th, ph, nblk - 1);
         ZeroTest zt((float)R);      // R bounds the remaining count from here on
         for (int b = nblk - 1; b >= 0; --b) {
             if (!__any(R > 0)) break;
             PhiBlock nxt = cur;
-            if (b > 0) nxt = load_phi<UNIFORM, VEC>(ph, b - 1);
+            if (b > 0) nxt = load_phi<UNIFORM, VEC>(th, ph, b - 1);
             float wv[kBlk], Pv[kBlk];
             block_weights<UNIFORM, VEC>(th, ph, cur, b, K, wv);
             cur = nxt;
