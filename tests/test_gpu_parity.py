@@ -93,6 +93,23 @@ def test_group_sizes_and_copy_counts(G, m):
     g.close()
 
 
+def test_word_counts_through_the_pair_list():
+    """Twelve words, each in nearly every document with counts up to 30: every task has a slot in the word-ordered
+    pair list, a word's slots run over several chunks of the reduce kernel and a chunk holds several words; the
+    uniform start (many nonzero topics per task) fills slots beyond their 15 pairs."""
+    rng = np.random.default_rng(11)
+    counts = rng.integers(1, 31, size=(700, 12)) * (rng.uniform(size=(700, 12)) < 0.9)
+    X = csc_from_dense(counts)
+    K, m = 48, 40
+    o = oracle.OracleLDA(X, K, 0.5, 0.05, seed=21, m0=m, G=4)
+    g = make_gpu(X, K, 0.5, 0.05, 21, m, 4, on_device=True)
+    assert_state_equal(g, o, "init")
+    for s in range(3):
+        o.sweep(m); g.sweep(m)
+        assert_state_equal(g, o, f"sweep {s + 1}")
+    g.close()
+
+
 def test_annealed_medium_shape():
     """Medium workload shape at reduced document count: K=64, Zipf word skew, m annealed linearly 1..20."""
     p = synth.PRESETS["medium"]
