@@ -67,6 +67,24 @@ def lib() -> ctypes.CDLL:
         L.oracle_theta_update.restype = None
         L.oracle_phi_update.argtypes = [c_int32, c_int32, u32p, c_uint32, c_float, c_float, f32p]
         L.oracle_phi_update.restype = None
+        L.oracle_expneg.argtypes = [c_float]
+        L.oracle_expneg.restype = c_float
+        L.oracle_poisson_walk.argtypes = [c_float, c_float, c_float]
+        L.oracle_poisson_walk.restype = c_uint32
+        L.oracle_poisson.argtypes = [c_float, c_uint64, c_uint64, c_uint32, c_uint32]
+        L.oracle_poisson.restype = c_uint32
+        L.oracle_draw_poisson.argtypes = [c_int32, f32p, c_float, c_uint64, c_uint64, c_uint32, u32p]
+        L.oracle_draw_poisson.restype = c_float
+        L.oracle_pass_poisson.argtypes = [c_int32, c_int32, i32p, i32p, f32p, c_int32, c_int32, c_float,
+                                          c_uint64, c_uint32, c_void_p, c_void_p, u32p, c_void_p]
+        L.oracle_pass_poisson.restype = None
+        L.oracle_draw_tasks_poisson.argtypes = [c_int32, i32p, i32p, f32p, c_int32, c_int32, c_float, c_uint64,
+                                                c_uint32, c_void_p, c_void_p, c_int64, i64p, u32p]
+        L.oracle_draw_tasks_poisson.restype = None
+        L.oracle_theta_update_real.argtypes = [c_int32, c_int32, u32p, c_float, c_float, f32p]
+        L.oracle_theta_update_real.restype = None
+        L.oracle_phi_update_real.argtypes = [c_int32, c_int32, u32p, c_float, c_float, c_float, f32p]
+        L.oracle_phi_update_real.restype = None
         L.oracle_loglik_eval.argtypes = [c_int32, i32p, i32p, f32p, c_int32, f32p, f32p]
         L.oracle_loglik_eval.restype = c_double
         _lib = L
@@ -187,6 +205,59 @@ def phi_update(nwk, m, beta, rho, phi) -> np.ndarray:
     return out
 
 
+# --------------------------------------------------------------------------- #
+# Poisson form of the factored draw (the number of copies m is a positive real)
+def expneg(y: float) -> float:
+    return float(lib().oracle_expneg(c_float(y)))
+
+
+def poisson_walk(rate: float, pm0: float, u: float) -> int:
+    return int(lib().oracle_poisson_walk(c_float(rate), c_float(pm0), c_float(u)))
+
+
+def poisson(lam: float, seed: int, tau: int, k: int, pword: int) -> int:
+    return int(lib().oracle_poisson(c_float(lam), seed, tau, k, pword))
+
+
+def draw_poisson(w, Nf: float, seed: int, tau: int, pword: int):
+    """Independent Poisson counts of one task; returns (counts uint32[K], mu)."""
+    w = np.ascontiguousarray(w, dtype=np.float32)
+    counts = np.zeros(w.shape[0], dtype=np.uint32)
+    mu = lib().oracle_draw_poisson(w.shape[0], _p(w, c_float), c_float(Nf), seed, tau, pword, _p(counts, c_uint32))
+    return counts, float(mu)
+
+
+def run_pass_poisson(X: CSC, K, G, m: float, seed, pword, theta, phi, want_nwk=True):
+    ndk = np.zeros((X.D, K), dtype=np.uint32)
+    nwk = np.zeros((X.V, K), dtype=np.uint32) if want_nwk else None
+    lib().oracle_pass_poisson(X.D, X.V, _p(X.colptr, c_int32), _p(X.rowidx, c_int32), _p(X.val, c_float),
+                              K, G, c_float(m), seed, pword, _vp(theta), _vp(phi), _p(ndk, c_uint32), _vp(nwk))
+    return ndk, nwk
+
+
+def draw_tasks_poisson(X: CSC, K, G, m: float, seed, pword, theta, phi, task_ids) -> np.ndarray:
+    ids = np.ascontiguousarray(task_ids, dtype=np.int64)
+    out = np.zeros((ids.shape[0], K), dtype=np.uint32)
+    lib().oracle_draw_tasks_poisson(X.D, _p(X.colptr, c_int32), _p(X.rowidx, c_int32), _p(X.val, c_float),
+                                    K, G, c_float(m), seed, pword, _vp(theta), _vp(phi), ids.shape[0],
+                                    _p(ids, c_int64), _p(out, c_uint32))
+    return out
+
+
+def theta_update_real(ndk, m: float, alpha) -> np.ndarray:
+    D, K = ndk.shape
+    theta = np.empty((D, K), dtype=np.float32)
+    lib().oracle_theta_update_real(D, K, _p(ndk, c_uint32), c_float(m), c_float(alpha), _p(theta, c_float))
+    return theta
+
+
+def phi_update_real(nwk, m: float, beta, rho, phi) -> np.ndarray:
+    V, K = nwk.shape
+    out = np.zeros((V, K), dtype=np.float32) if phi is None else np.ascontiguousarray(phi, dtype=np.float32).copy()
+    lib().oracle_phi_update_real(V, K, _p(nwk, c_uint32), c_float(m), c_float(beta), c_float(rho), _p(out, c_float))
+    return out
+
+
 def loglik_eval(X: CSC, theta, phi) -> float:
     K = theta.shape[1]
     return float(lib().oracle_loglik_eval(X.D, _p(X.colptr, c_int32), _p(X.rowidx, c_int32),
@@ -216,6 +287,15 @@ class OracleLDA:
                                          self.theta, self.phi)
         self.theta = theta_update(self.ndk, m, self.alpha)
         self.phi = phi_update(self.nwk, m, self.beta, rho, self.phi)
+        self.t += 1
+
+    def sweep_poisson(self, m: float, rho: float = 1.0):
+        """One sweep in the Poisson form (Algorithm 3 as printed): m may be any positive real."""
+        m = float(np.float32(m))
+        self.ndk, self.nwk = run_pass_poisson(self.X, self.K, self.G, m, self.seed, pass_word(self.t),
+                                              self.theta, self.phi)
+        self.theta = theta_update_real(self.ndk, m, self.alpha)
+        self.phi = phi_update_real(self.nwk, m, self.beta, rho, self.phi)
         self.t += 1
 
     def set_batch(self, X: CSC, m_init: int):

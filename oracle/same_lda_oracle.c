@@ -179,6 +179,100 @@ float oracle_draw(int32_t K, const float* w, uint32_t N, uint64_t seed, uint64_t
 }
 
 /* ------------------------------------------------------------------------- */
+/* Poisson form of the factored draw (Section 4, second part; Algorithm 3, the
+ * sampling line): the count of topic k among the copies of a latent variable is
+ * an independent Poisson variable with rate (number of copies) * P(topic k).
+ * The number of copies may be any positive real.
+ *
+ * exp(-y) for 0 <= y <= 32 from + - * only, so that a second implementation
+ * obtains the same bits: t = y*log2(e), n = trunc(t), f = t-n in [0,1),
+ * g = f - 1/2, 2^-(g+1/2) by the degree-7 Taylor polynomial of
+ * 2^-1/2 * exp(-g ln 2) in Horner form (every product and sum rounded once),
+ * scaled by 2^-n.  Relative error below 2e-6, below 2e-7 for y <= 2 (tests).                          */
+float oracle_expneg(float y)
+{
+    static const float c[8] = {
+        0.7071067811865476f,       /* 2^-1/2                      */
+        -0.4901290717342736f,      /* 2^-1/2 * (-ln2)             */
+        0.16986579209153746f,      /* 2^-1/2 * (ln2)^2 / 2        */
+        -0.039247331620610344f,    /* 2^-1/2 * (-ln2)^3 / 6       */
+        0.006801044314331813f,     /* 2^-1/2 * (ln2)^4 / 24       */
+        -0.0009428249382684684f,   /* 2^-1/2 * (-ln2)^5 / 120     */
+        0.00010891940795373223f,   /* 2^-1/2 * (ln2)^6 / 720      */
+        -1.0785311504483996e-05f   /* 2^-1/2 * (-ln2)^7 / 5040    */
+    };
+    float t = y * 1.4426950408889634f;
+    int n = (int)t;
+    float f = t - (float)n;
+    float g = f - 0.5f;
+    float p = c[7];
+    for (int i = 6; i >= 0; --i) {
+        p = p * g;
+        p = p + c[i];
+    }
+    return ldexpf(p, -n);
+}
+
+/* Poisson(rate) for one piece by inversion: walk the pmf upward from 0,
+ * pm(x) = pm(x-1) * rate / x, until the cdf reaches u or the pmf has fallen
+ * below the resolution of the running cdf.                                   */
+uint32_t oracle_poisson_walk(float rate, float pm0, float u)
+{
+    uint32_t x = 0;
+    float pm = pm0, cdf = pm0;
+    while (u > cdf) {
+        x += 1;
+        float inv_x = 1.0f / (float)x;
+        pm = pm * rate;
+        pm = pm * inv_x;
+        float next = cdf + pm;
+        if (next == cdf) break;
+        cdf = next;
+    }
+    return x;
+}
+
+/* z ~ Poisson(lambda) for topic k of task tau.  A rate above 32 is cut into
+ * J = trunc(lambda/32) + 1 equal pieces (a sum of independent Poisson variables
+ * is Poisson with the summed rate), so that exp(-rate) never underflows; each
+ * piece has its own uniform (same stream layout as the binomial pieces).      */
+uint32_t oracle_poisson(float lambda, uint64_t seed, uint64_t tau, uint32_t k, uint32_t pass)
+{
+    if (!(lambda > 0.0f)) return 0;
+    uint32_t J = 1;
+    float rate = lambda;
+    if (lambda > 32.0f) {
+        J = (uint32_t)(lambda / 32.0f) + 1u;
+        rate = lambda / (float)J;
+    }
+    float pm0 = oracle_expneg(rate);
+    uint32_t total = 0;
+    for (uint32_t piece = 0; piece < J; ++piece) {
+        float u = stream_uniform(seed, tau, k, piece, pass);
+        total += oracle_poisson_walk(rate, pm0, u);
+    }
+    return total;
+}
+
+/* All topics of one task: with Nf copies (a positive real) and weights w,
+ * counts[k] ~ Poisson(Nf * w_k / mu), mu = w_0 + ... + w_{K-1} accumulated left
+ * to right (the same normaliser as in oracle_draw).  Returns mu.              */
+float oracle_draw_poisson(int32_t K, const float* w, float Nf, uint64_t seed, uint64_t tau,
+                          uint32_t pass, uint32_t* counts)
+{
+    float mu = w[0];
+    for (int32_t k = 1; k < K; ++k) mu = mu + w[k];
+    for (int32_t k = 0; k < K; ++k) {
+        counts[k] = 0;
+        if (!(w[k] > 0.0f)) continue;
+        float scaled = Nf * w[k];
+        float lambda = scaled / mu;
+        counts[k] = oracle_poisson(lambda, seed, tau, (uint32_t)k, pass);
+    }
+    return mu;
+}
+
+/* ------------------------------------------------------------------------- */
 /* Draw tasks.  A nonzero (d, w, c) stands for c tokens with identical
  * conditionals; its tokens are drawn in groups of at most G: task j of the
  * nonzero covers g = min(G, c - j*G) tokens and draws Multinomial(m*g, p).
@@ -290,24 +384,92 @@ void oracle_draw_tasks(int32_t D, const int32_t* colptr, const int32_t* rowidx, 
     free(w); free(scratch); free(base);
 }
 
+/* The same pass in the Poisson form: m is a positive real, a task of g tokens
+ * has Nf = m*g copies (one rounded product).                                  */
+void oracle_pass_poisson(int32_t D, int32_t V, const int32_t* colptr, const int32_t* rowidx,
+                         const float* val, int32_t K, int32_t G, float m, uint64_t seed,
+                         uint32_t pass, const float* theta, const float* phi,
+                         uint32_t* ndk, uint32_t* nwk)
+{
+    (void)V;
+    int64_t nnz = colptr[D];
+    int64_t* base = (int64_t*)malloc((size_t)(nnz + 1) * sizeof(int64_t));
+    oracle_task_base(nnz, val, G, base);
+#pragma omp parallel
+    {
+        float* w = (float*)malloc((size_t)K * sizeof(float));
+        uint32_t* cnt = (uint32_t*)malloc((size_t)K * sizeof(uint32_t));
+#pragma omp for schedule(dynamic, 64)
+        for (int32_t d = 0; d < D; ++d) {
+            for (int64_t i = colptr[d]; i < colptr[d + 1]; ++i) {
+                int32_t word = rowidx[i];
+                uint32_t c = (uint32_t)val[i];
+                fill_weights(K, theta + (size_t)d * K, phi + (size_t)word * K, w);
+                uint32_t ntask = tasks_of(val[i], G);
+                for (uint32_t j = 0; j < ntask; ++j) {
+                    uint32_t g = c - j * (uint32_t)G;
+                    if (g > (uint32_t)G) g = (uint32_t)G;
+                    float Nf = m * (float)g;
+                    oracle_draw_poisson(K, w, Nf, seed, (uint64_t)(base[i] + j), pass, cnt);
+                    for (int32_t k = 0; k < K; ++k) {
+                        if (cnt[k] == 0) continue;
+                        ndk[(size_t)d * K + k] += cnt[k];   /* document d belongs to this thread */
+                        if (nwk) {
+#pragma omp atomic
+                            nwk[(size_t)word * K + k] += cnt[k];
+                        }
+                    }
+                }
+            }
+        }
+        free(w); free(cnt);
+    }
+    free(base);
+}
+
+void oracle_draw_tasks_poisson(int32_t D, const int32_t* colptr, const int32_t* rowidx, const float* val,
+                               int32_t K, int32_t G, float m, uint64_t seed, uint32_t pass,
+                               const float* theta, const float* phi,
+                               int64_t n, const int64_t* task_ids, uint32_t* out)
+{
+    int64_t nnz = colptr[D];
+    int64_t* base = (int64_t*)malloc((size_t)(nnz + 1) * sizeof(int64_t));
+    oracle_task_base(nnz, val, G, base);
+    float* w = (float*)malloc((size_t)K * sizeof(float));
+    for (int64_t t = 0; t < n; ++t) {
+        int64_t tau = task_ids[t];
+        int64_t lo = 0, hi = nnz;            /* last nonzero whose base <= tau */
+        while (hi - lo > 1) { int64_t mid = (lo + hi) / 2; if (base[mid] <= tau) lo = mid; else hi = mid; }
+        int64_t i = lo;
+        int32_t dl = 0, dh = D;              /* document holding nonzero i */
+        while (dh - dl > 1) { int32_t mid = (dl + dh) / 2; if (colptr[mid] <= i) dl = mid; else dh = mid; }
+        int32_t d = dl;
+        uint32_t j = (uint32_t)(tau - base[i]);
+        uint32_t c = (uint32_t)val[i];
+        uint32_t g = c - j * (uint32_t)G;
+        if (g > (uint32_t)G) g = (uint32_t)G;
+        fill_weights(K, theta + (size_t)d * K, phi + (size_t)rowidx[i] * K, w);
+        oracle_draw_poisson(K, w, m * (float)g, seed, (uint64_t)tau, pass, out + (size_t)t * K);
+    }
+    free(w); free(base);
+}
+
 /* ------------------------------------------------------------------------- */
 /* Parameter update (Eq. 6 and Algorithm 3's last three steps).  Counts hold all
  * m copies, so they are divided by m; theta keeps its prior and stays
  * unnormalised (its per-document normaliser cancels in the draw); phi gets its
  * prior and is normalised over words per topic (the c_k../m + W*beta term of
  * Eq. 6), then blended into the running model with weight rho.                */
-void oracle_theta_update(int32_t D, int32_t K, const uint32_t* ndk, uint32_t m, float alpha, float* theta)
+void oracle_theta_update_real(int32_t D, int32_t K, const uint32_t* ndk, float mf, float alpha, float* theta)
 {
-    float mf = (float)m;
     for (size_t e = 0; e < (size_t)D * K; ++e) {
         float avg = (float)ndk[e] / mf;
         theta[e] = avg + alpha;
     }
 }
 
-void oracle_phi_update(int32_t V, int32_t K, const uint32_t* nwk, uint32_t m, float beta, float rho, float* phi)
+void oracle_phi_update_real(int32_t V, int32_t K, const uint32_t* nwk, float mf, float beta, float rho, float* phi)
 {
-    float mf = (float)m;
     float vbeta = (float)V * beta;
     float one_minus_rho = 1.0f - rho;
     for (int32_t k = 0; k < K; ++k) {
@@ -328,6 +490,17 @@ void oracle_phi_update(int32_t V, int32_t K, const uint32_t* nwk, uint32_t m, fl
             }
         }
     }
+}
+
+/* The multinomial form counts exactly m copies per token: m is an integer there. */
+void oracle_theta_update(int32_t D, int32_t K, const uint32_t* ndk, uint32_t m, float alpha, float* theta)
+{
+    oracle_theta_update_real(D, K, ndk, (float)m, alpha, theta);
+}
+
+void oracle_phi_update(int32_t V, int32_t K, const uint32_t* nwk, uint32_t m, float beta, float rho, float* phi)
+{
+    oracle_phi_update_real(V, K, nwk, (float)m, beta, rho, phi);
 }
 
 /* Per-word log-likelihood of a matrix under (theta, phi) (Section 6.1.1):

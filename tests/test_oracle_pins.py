@@ -376,3 +376,128 @@ def test_learning_sanity_on_generated_corpus():
     tok_t = np.zeros(X.V); np.add.at(tok_t, test.rowidx, test.val)
     ll_uni = float((tok_t * np.log(uni)).sum() / tok_t.sum())
     assert ll1 > ll0 + 0.05 and ll1 > ll_uni + 0.05
+
+
+# --------------------------------------------------------------------------- #
+# Poisson form of the factored draw (Section 4, second part: with a randomised order the count of
+# topic v among the copies is an independent Poisson(m P(Z = v)) variable; Algorithm 3's sampling line)
+def test_expneg_against_library_exp():
+    ys = np.concatenate([np.logspace(-9, 0, 500), np.linspace(0.0, 32.0, 40001)]).astype(np.float32)
+    got = np.array([oracle.expneg(float(y)) for y in ys], dtype=np.float64)
+    ref = np.exp(-ys.astype(np.float64))
+    rel = np.abs(got - ref) / ref
+    assert rel.max() < 2e-6
+    assert rel[ys <= 2.0].max() < 2e-7
+    assert oracle.expneg(0.0) == 1.0
+
+
+def test_poisson_walk_matches_library_quantile():
+    """Inversion must return the Poisson quantile of u (scipy) away from cdf thresholds."""
+    rng = np.random.default_rng(5)
+    checked = 0
+    for _ in range(300):
+        lam = float(np.float32(rng.uniform(0.001, 32.0) if rng.uniform() < 0.7 else rng.uniform(0.001, 1.0)))
+        pm0 = oracle.expneg(lam)
+        cdf = stats.poisson.cdf(np.arange(200), lam)
+        for u in rng.uniform(0.001, 0.999, size=8):
+            u = float(np.float32(u))
+            if np.min(np.abs(cdf - u)) < 1e-4:
+                continue
+            assert oracle.poisson_walk(lam, pm0, u) == int(stats.poisson.ppf(u, lam))
+            checked += 1
+    assert checked > 1500
+
+
+@pytest.mark.parametrize("lam", [0.02, 0.7, 4.0, 31.5, 32.5, 70.0, 400.0, 3000.0])
+def test_poisson_distribution_incl_pieces(lam):
+    """Poisson(lambda) frequencies against scipy's pmf; rates above 32 are sums of several pieces."""
+    n_draws = 40000
+    xs = np.array([oracle.poisson(lam, 13, tau, 9, PW(3)) for tau in range(n_draws)])
+    lf = float(np.float32(lam))
+    assert abs(xs.mean() - lf) < 5 * math.sqrt(lf / n_draws)
+    assert abs(xs.var() - lf) < 6 * lf * math.sqrt(2.0 / n_draws) + 6 * math.sqrt(lf / n_draws)
+    hi = int(stats.poisson.ppf(1 - 1e-9, lf)) + 2
+    pmf = stats.poisson.pmf(np.arange(hi), lf)
+    order = np.arange(hi)
+    keep = pmf * n_draws >= 10
+    obs = np.array([np.sum(xs == v) for v in order[keep]] + [np.sum(~np.isin(xs, order[keep]))], float)
+    exp = np.array(list(pmf[keep] * n_draws) + [max(n_draws * (1 - pmf[keep].sum()), 1e-9)])
+    if exp[-1] < 5:
+        obs[-2] += obs[-1]; exp[-2] += exp[-1]; obs, exp = obs[:-1], exp[:-1]
+    assert stats.chisquare(obs, exp * obs.sum() / exp.sum()).pvalue > 1e-4
+
+
+def test_poisson_degenerate_cases():
+    assert oracle.poisson(0.0, 1, 1, 1, PW(1)) == 0
+    c, mu = oracle.draw_poisson([0.0, 2.0, 0.0, 1.0], 50.0, 1, 1, PW(1))
+    assert c[0] == 0 and c[2] == 0 and mu == 3.0
+
+
+def test_poisson_draw_rates_totals_and_independence():
+    """Counts of a task: topic k has mean and variance Nf p_k, the total is Poisson(Nf) (not fixed, unlike the
+    multinomial form), and topics are uncorrelated (the multinomial form would give -Nf p_j p_k)."""
+    w = np.array([0.5, 0.1, 0.25, 0.0, 0.15], dtype=np.float32)
+    p = w.astype(np.float64) / w.astype(np.float64).sum()
+    Nf, n_draws = 37.5, 30000
+    cs = np.array([oracle.draw_poisson(w, Nf, 17, tau, PW(4))[0] for tau in range(n_draws)], dtype=np.float64)
+    for k in range(5):
+        lam = Nf * p[k]
+        assert abs(cs[:, k].mean() - lam) < 5 * math.sqrt(lam / n_draws) + 1e-12
+        if lam > 0:
+            assert abs(cs[:, k].var() - lam) < 6 * lam * math.sqrt(2.0 / n_draws) + 6 * math.sqrt(lam / n_draws)
+    tot = cs.sum(axis=1)
+    assert abs(tot.mean() - Nf) < 5 * math.sqrt(Nf / n_draws)
+    assert abs(tot.var() - Nf) < 0.1 * Nf                       # a multinomial total would have variance 0
+    cov = np.cov(cs[:, 0], cs[:, 2])[0, 1]
+    assert abs(cov) < 6 * math.sqrt(Nf * p[0] * Nf * p[2] / n_draws)    # multinomial: -Nf p0 p2 = -4.7
+
+
+def test_poisson_small_rates_approach_the_binomial_marginal():
+    """For a topic of small probability the multinomial form's count Bin(N, p) and the Poisson form's
+    Poisson(N p) nearly agree: their means over many tasks must match closely."""
+    w = np.array([0.97, 0.01, 0.02], dtype=np.float32)
+    n_draws = 20000
+    a = np.array([oracle.draw(w, 60, 23, tau, PW(5))[0] for tau in range(n_draws)], dtype=np.float64)
+    b = np.array([oracle.draw_poisson(w, 60.0, 23, tau, PW(5))[0] for tau in range(n_draws)], dtype=np.float64)
+    for k in (1, 2):
+        lam = 60.0 * float(w[k]) / float(w.astype(np.float64).sum())
+        assert abs(a[:, k].mean() - lam) < 5 * math.sqrt(lam / n_draws)
+        assert abs(b[:, k].mean() - lam) < 5 * math.sqrt(lam / n_draws)
+
+
+@pytest.mark.parametrize("m", [0.4, 1.0, 2.5, 30.0])
+def test_poisson_pass_expected_totals_for_real_m(m):
+    """A pass in the Poisson form on a toy matrix: document and word totals have mean m * tokens (any real m),
+    both count matrices hold the same copies, and per-task counts sum back to the pass."""
+    rng = np.random.default_rng(3)
+    counts = rng.integers(1, 9, size=(40, 30)) * (rng.uniform(size=(40, 30)) < 0.4)
+    X = csc_from_dense(counts)
+    K, G = 6, 3
+    theta = rng.uniform(0.1, 2.0, size=(X.D, K)).astype(np.float32)
+    phi = rng.uniform(0.01, 1.0, size=(X.V, K)).astype(np.float32)
+    ndk, nwk = oracle.run_pass_poisson(X, K, G, m, 29, PW(6), theta, phi)
+    assert ndk.sum() == nwk.sum()
+    tokens = counts.sum()
+    assert abs(float(ndk.sum()) - m * tokens) < 5 * math.sqrt(m * tokens)
+    doc_tok = counts.sum(axis=1).astype(np.float64)
+    z = (ndk.sum(axis=1) - m * doc_tok) / np.sqrt(np.maximum(m * doc_tok, 1e-9))
+    assert np.abs(z[doc_tok > 0]).max() < 5.5
+    assert np.all(ndk[doc_tok == 0] == 0)
+    n_tasks = int(oracle.task_base(X, G)[-1])
+    per_task = oracle.draw_tasks_poisson(X, K, G, m, 29, PW(6), theta, phi, np.arange(n_tasks))
+    assert per_task.sum() == ndk.sum()
+    assert np.array_equal(per_task.sum(axis=0, dtype=np.uint64), ndk.sum(axis=0, dtype=np.uint64))
+
+
+def test_poisson_sweep_update_uses_real_m():
+    """theta = n_dk / m + alpha and the word-normalised phi with a real m: closed form for K = 1."""
+    counts = np.array([[3, 0, 2], [0, 5, 1]])
+    X = csc_from_dense(counts)
+    o = oracle.OracleLDA(X, 1, 0.5, 0.1, seed=4, m0=2, G=8)
+    o.sweep_poisson(2.5)
+    m = np.float32(2.5)
+    np.testing.assert_array_equal(o.theta[:, 0], (o.ndk[:, 0].astype(np.float32) / m + np.float32(0.5)))
+    nk = np.float32(o.nwk[:, 0].sum())
+    np.testing.assert_allclose(o.phi[:, 0], (o.nwk[:, 0].astype(np.float32) / m + np.float32(0.1))
+                               / (nk / m + np.float32(3) * np.float32(0.1)), rtol=1e-6)
+    assert abs(o.phi[:, 0].sum() - 1.0) < 1e-5
