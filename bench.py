@@ -28,9 +28,10 @@ def draw_kernel_bytes(nnz: int, D: int, K: int) -> float:
     return float(nnz) * (8 + 4 * K) + float(D) * (4 + 8 * K)
 
 
-def measured_traffic(workload: str):
+def measured_traffic(workload: str, form: str = "multinomial"):
     """HBM bytes per draw-kernel launch from the committed rocprofv3 counter summary (None if absent)."""
-    path = os.path.join(ROOT, "profiles", f"draw_kernel_{workload}_pmc.md")
+    tag = "" if form == "multinomial" else f"_{form}"
+    path = os.path.join(ROOT, "profiles", f"draw_kernel{tag}_{workload}_pmc.md")
     try:
         for line in open(path):
             if line.startswith("hbm_bytes_per_launch"):
@@ -40,7 +41,7 @@ def measured_traffic(workload: str):
     return None
 
 
-def cpu_baseline(X_np, K, alpha, beta, m, m0, G, target_s=12.0):
+def cpu_baseline(X_np, K, alpha, beta, m, m0, G, target_s=12.0, poisson=False):
     """Times one sweep of the oracle (as it stands) on a leading slice of documents sized for ~target_s."""
     import oracle
     cores = len(os.sched_getaffinity(0))
@@ -49,7 +50,7 @@ def cpu_baseline(X_np, K, alpha, beta, m, m0, G, target_s=12.0):
         sl = X_np.slice_docs(0, docs)
         o = oracle.OracleLDA(sl, K, alpha, beta, seed=1, m0=m0, G=G)
         t0 = time.perf_counter()
-        o.sweep(m)
+        o.sweep_poisson(float(m)) if poisson else o.sweep(m)
         dt = max(time.perf_counter() - t0, 1e-4)
         if dt >= 0.5 * target_s or docs >= X_np.D:
             break
@@ -69,6 +70,9 @@ def main():
     ap.add_argument("--workload", default="news")
     ap.add_argument("--scale", type=float, default=1.0, help="fraction of the workload's documents (1.0 = full size)")
     ap.add_argument("--tokens-per-draw", type=int, default=32)
+    ap.add_argument("--form", choices=["multinomial", "poisson"], default="multinomial",
+                    help="form of the factored draw: the exact-total multinomial (the headline path) or the "
+                         "independent Poisson counts of Algorithm 3 as printed")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-loglik", action="store_true")
     args = ap.parse_args()
@@ -101,14 +105,16 @@ def main():
                         seed=2, m0=m0, tokens_per_draw=G)
     t_init = time.perf_counter() - t0
 
+    poisson = args.form == "poisson"
+    sweep = (lambda mm: g.sweep_poisson(float(mm))) if poisson else (lambda mm: g.sweep(mm))
     for s in range(args.warmup):
-        g.sweep(1 if s < args.warmup - 40 else m)
+        sweep(1 if s < args.warmup - 40 else m)
     g.synchronize()
     g.set_timing(True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        g.sweep(m)
+        sweep(m)
     g.synchronize()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
@@ -123,18 +129,19 @@ def main():
     achieved = bytes_per_launch / (draw_ms_avg * 1e-3) / 1e9
 
     out = {
-        "metric": "tokens/sec per SAME sweep (K=256, m=100) + achieved HBM GB/s vs 8 TB/s",
+        "metric": ("tokens/sec per SAME sweep (K=256, m=100) + achieved HBM GB/s vs 8 TB/s" if not poisson else
+                   "tokens/sec per SAME sweep in the Poisson form (K=256, m=100) + achieved HBM GB/s vs 8 TB/s"),
         "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{args.workload} (LDA-generated, scale {args.scale})", "D": st["D"], "V": st["V"],
                    "K": K, "m": m, "nnz": st["nnz"], "tokens": st["tokens"], "max_count": st["max_count"],
-                   "tokens_per_draw": G, "draw_tasks": g.task_count, "alpha": alpha, "beta": beta,
+                   "form": args.form, "tokens_per_draw": G, "draw_tasks": g.task_count, "alpha": alpha, "beta": beta,
                    "m_init": m0,
                    "warmup_schedule": f"{max(0, args.warmup - 40)} sweeps at m=1 then {min(40, args.warmup)} at m={m}",
                    "generate_s": round(t_gen, 2), "init_s": round(t_init, 2)},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(args.workload),
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(args.workload, args.form),
                      "kernel": "draw_kernel", "kernel_ms": draw_ms_avg, "bytes_per_launch": bytes_per_launch},
     }
     if test is not None and not args.no_loglik:
@@ -144,7 +151,7 @@ def main():
     if not args.no_cpu_baseline:
         X_np = oracle.CSC(train.D, train.V, train.colptr.cpu().numpy(), train.rowidx.cpu().numpy(),
                           train.val.cpu().numpy())
-        out["cpu_baseline"] = cpu_baseline(X_np, K, alpha, beta, m, m0, G)
+        out["cpu_baseline"] = cpu_baseline(X_np, K, alpha, beta, m, m0, G, poisson=poisson)
     print(json.dumps(out))
 
 

@@ -86,6 +86,16 @@ int same_lda_init(same_lda_t** out, const same_lda_csc* X, int32_t K, float alph
  *   rho_t  in (0, 1]                                                                           */
 int same_lda_sweep(same_lda_t* h, int32_t m_t, float rho_t);
 
+/* The same sweep in the Poisson form of the factored draw (Section 4, second part; the sampling
+ * line of Algorithm 3 as printed): the count of topic k for a group of g tokens is an independent
+ * Poisson variable with rate m_t * g * w_k / mu, so the copies of a token no longer total exactly
+ * m_t * c, and m_t may be any positive real (the real-valued schedules of Section 6.1.3 apply as
+ * they are).  The update divides by the same real m_t.  Takes the next pass index of the training
+ * stream like same_lda_sweep; the two forms may alternate on one handle.  Asynchronous.
+ *   m_t    > 0, and m_t * (largest group size) < 2^22
+ *   rho_t  in (0, 1]                                                                           */
+int same_lda_sweep_poisson(same_lda_t* h, float m_t, float rho_t);
+
 /* Per-word log-likelihood of held-out documents (Section 6.1.1): theta of the held-out
  * documents is fitted with phi frozen (a uniform-weight pass, then foldin_sweeps passes with
  * m_eval copies, on a separate random stream), then
@@ -122,6 +132,9 @@ int same_lda_task_count(const same_lda_t* h, int64_t* count);
  *   counts_out  host, [n][K] uint32                                                            */
 int same_lda_debug_draw(same_lda_t* h, int32_t m_t, const int64_t* task_ids, int32_t n,
                         uint32_t* counts_out);
+/* The same hook for the NEXT same_lda_sweep_poisson(h, m_t, .).                                  */
+int same_lda_debug_draw_poisson(same_lda_t* h, float m_t, const int64_t* task_ids, int32_t n,
+                                uint32_t* counts_out);
 
 /* Kernel timing.  When enabled, HIP events bracket the draw-and-scatter kernel of every sweep on
  * the handle's stream.  same_lda_get_timing synchronises, returns the summed duration (ms) and

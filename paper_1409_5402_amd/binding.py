@@ -18,7 +18,8 @@ LIB_PATH = os.path.join(HERE, "libsame_lda.so")
 THETA, PHI, NDK, NWK, NK = 0, 1, 2, 3, 4
 _DTYPES = {THETA: np.float32, PHI: np.float32, NDK: np.uint32, NWK: np.uint32, NK: np.uint64}
 
-EXPORTS = ["same_lda_init", "same_lda_sweep", "same_lda_loglik", "same_lda_free", "same_lda_set_batch",
+EXPORTS = ["same_lda_init", "same_lda_sweep", "same_lda_sweep_poisson", "same_lda_loglik", "same_lda_free",
+           "same_lda_set_batch", "same_lda_debug_draw_poisson",
            "same_lda_get", "same_lda_set", "same_lda_get_pass", "same_lda_set_pass", "same_lda_task_count",
            "same_lda_debug_draw", "same_lda_set_timing", "same_lda_get_timing", "same_lda_selftest",
            "same_lda_synchronize",
@@ -49,6 +50,8 @@ def load() -> ctypes.CDLL:
         L.same_lda_init.argtypes = [POINTER(c_void_p), POINTER(_Csc), c_int32, c_float, c_float, c_uint64,
                                     c_int32, c_int32, c_void_p]
         L.same_lda_sweep.argtypes = [c_void_p, c_int32, c_float]
+        L.same_lda_sweep_poisson.argtypes = [c_void_p, c_float, c_float]
+        L.same_lda_debug_draw_poisson.argtypes = [c_void_p, c_float, c_void_p, c_int32, c_void_p]
         L.same_lda_loglik.argtypes = [c_void_p, POINTER(_Csc), c_int32, c_int32, POINTER(c_double)]
         L.same_lda_free.argtypes = [c_void_p]
         L.same_lda_free.restype = None
@@ -139,6 +142,9 @@ class SameLDA:
     def sweep(self, m, rho=1.0):
         self._check(self._lib.same_lda_sweep(self._h, int(m), float(rho)))
 
+    def sweep_poisson(self, m, rho=1.0):
+        self._check(self._lib.same_lda_sweep_poisson(self._h, float(m), float(rho)))
+
     def set_batch(self, D, colptr, rowidx, val, m_init):
         c, keep = _csc(D, self.V, colptr, rowidx, val)
         self._check(self._lib.same_lda_set_batch(self._h, byref(c), int(m_init)))
@@ -196,6 +202,13 @@ class SameLDA:
         out = np.zeros((ids.shape[0], self.K), np.uint32)
         self._check(self._lib.same_lda_debug_draw(self._h, int(m), ids.ctypes.data if ids.size else None,
                                                   ids.shape[0], out.ctypes.data if out.size else None))
+        return out
+
+    def debug_draw_poisson(self, m, task_ids) -> np.ndarray:
+        ids = np.ascontiguousarray(task_ids, np.int64)
+        out = np.zeros((ids.shape[0], self.K), np.uint32)
+        self._check(self._lib.same_lda_debug_draw_poisson(self._h, float(m), ids.ctypes.data if ids.size else None,
+                                                          ids.shape[0], out.ctypes.data if out.size else None))
         return out
 
     def set_timing(self, enabled: bool):

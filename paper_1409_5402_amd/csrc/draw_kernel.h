@@ -64,7 +64,8 @@ struct DrawArgs {
     uint32_t*       pairs;      // [n_slots][kPairWords] pair list in word order, or null (update nwk directly)
     const int32_t*  t_slot;     // [n_tasks] slot of each task in the pair list, -1 for a task without one
     int32_t         K;
-    uint32_t        m;
+    uint32_t        m;          // copies per token (multinomial form)
+    float           mf;         // copies per token (Poisson form: any positive real)
     uint32_t        seed_lo, seed_hi, pass;
 #ifdef SAME_STATS
     unsigned long long* stats;  // profiling builds only: event counters
@@ -154,7 +155,12 @@ __device__ __forceinline__ float inv_int(float x)
     return __builtin_fmaf(y, e, y);
 }
 
-template <bool UNIFORM, bool VEC, bool DEBUG>
+// POISSON selects the second form of Section 4 (the one Algorithm 3 prints): topic k of a task
+// with Nf = mf * g copies gets an independent Poisson(Nf * w_k / mu) count, mu = P_{K-1}.  The scan
+// is the same (drop test with the bound Nf and M_k = mu for every topic, the heaviest included);
+// the machine then has no remaining count to carry: a queued topic starts its draw at once, a rate
+// above 32 is cut into equal pieces that wait for the wave like the binomial pieces do.
+template <bool UNIFORM, bool VEC, bool DEBUG, bool POISSON>
 __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
 {
     extern __shared__ uint32_t lds[];
@@ -174,7 +180,8 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
     const int64_t tau = DEBUG ? a.ids[row] : (int64_t)a.order[row];
     const int32_t d = a.t_doc[tau];
     const int32_t w = a.t_word[tau];
-    const uint32_t N = live ? a.m * a.t_g[tau] : 0u;
+    const uint32_t N = POISSON ? (live ? 1u : 0u) : (live ? a.m * a.t_g[tau] : 0u);
+    const float Nf = POISSON ? (live ? a.mf * (float)a.t_g[tau] : 0.0f) : (float)N;
     const float* __restrict__ th = UNIFORM ? nullptr : a.theta + (size_t)d * K;
     const float* __restrict__ ph = UNIFORM ? nullptr : a.phi + (size_t)w * K;
     uint32_t* __restrict__ out_d = DEBUG ? a.ndk + (size_t)row * K : a.ndk + (size_t)d * K;
@@ -188,6 +195,7 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
     // ---- pass 1: running sum, checkpoint before every block; heaviest topic (highest index among ties)
     float wmax = -1.0f;
     int kstar = 0;
+    float mu = 0.0f;
     {
         float P = 0.0f;
         PhiBlock cur = load_phi<UNIFORM, VEC>(th, ph, 0);
@@ -205,6 +213,7 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
             }
             cur = nxt;
         }
+        mu = P;
     }
 
     // ---- the conditional-binomial chain over the queued topics (descending k), a per-lane state
@@ -241,7 +250,7 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
     // lanes in state 3 are numbered consecutively and dealt out over the 64 lanes; every owner
     // receives the total of its pieces through an LDS counter.
     auto pool = [&](uint64_t pend) {
-        const uint32_t np = (st == 3) ? (bR + L - 1u) / L : 0u;
+        const uint32_t np = (st == 3) ? (POISSON ? bR : (bR + L - 1u) / L) : 0u;   // Poisson: bR holds the piece count
         uint32_t total = 0;
         for (uint64_t p = pend; p != 0; p &= p - 1) total += __shfl(np, __ffsll((unsigned long long)p) - 1);
         if (lane == 0) { SAME_COUNT(a, 6, 1); SAME_COUNT(a, 7, total); }
@@ -255,15 +264,15 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
                 off += __shfl(np, src);
             }
             const uint32_t oR = __shfl(bR, owner), oL = __shfl(L, owner), onp = __shfl(np, owner);
-            const float osc = __shfl(sc, owner), orr = __shfl(r, owner), ou = __shfl(u, owner);
+            const float osc = __shfl(POISSON ? pm : sc, owner), orr = __shfl(r, owner), ou = __shfl(u, owner);
             const uint32_t ok = (uint32_t)__shfl(kk, owner);
             StreamKey okey = key;
             okey.tau_lo = __shfl(key.tau_lo, owner);
             okey.tau_hi = __shfl(key.tau_hi, owner);
             if (p < total) {
                 const uint32_t jp = p - first;
-                const uint32_t nj = (jp == onp - 1u) ? oR - jp * oL : oL;
-                float pmj = ipow(osc, nj);
+                const uint32_t nj = POISSON ? 0xFFFFFFFFu : ((jp == onp - 1u) ? oR - jp * oL : oL);
+                float pmj = POISSON ? osc : ipow(osc, nj);          // Poisson: the owner's exp(-rate)
                 float uj = ou;
                 if (jp > 0) {
                     uint32_t xb[4];
@@ -276,7 +285,7 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
                 while (uj > cdfj && xj < nj) {
                     xj += 1;
                     pmj = pmj * orr;
-                    pmj = pmj * (float)(nj - xj + 1u);
+                    if (!POISSON) pmj = pmj * (float)(nj - xj + 1u);
                     pmj = pmj * inv_int((float)xj);
                     const float next = cdfj + pmj;
                     if (next == cdfj) break;
@@ -289,9 +298,9 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
         if (st == 3) {
             const uint32_t part = acc[lane];
             acc[lane] = 0u;
-            const uint32_t nk = flip ? bR - part : part;
+            const uint32_t nk = (!POISSON && flip) ? bR - part : part;
             if (nk > 0) { emit(kk, nk); SAME_COUNT(a, 5, 1); }
-            R -= nk;
+            if (!POISSON) R -= nk;
             st = 0;
         }
         __syncthreads();
@@ -314,10 +323,27 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
                 u = uniform_from_word(xk);
                 qh = (qh + 1 == kQCap) ? 0 : qh + 1;
                 --cnt;
-                if (!ZeroTest((float)R).surely_zero(wq, Mq, xk)) { found = true; break; }
+                if (POISSON || !ZeroTest((float)R).surely_zero(wq, Mq, xk)) { found = true; break; }
             }
             if (R == 0) cnt = 0;                                   // nothing left to place: the rest is void
-            if (found) {
+            if (found && POISSON) {
+                const float scaled = Nf * wq;
+                const float lam = scaled / Mq;
+                if (lam > 0.0f) {
+                    L = 0xFFFFFFFFu;                               // the walk has no upper end
+                    if (lam <= 32.0f) {                            // one piece
+                        r = lam;
+                        const float pm0 = expneg(lam);
+                        xw = 0; pm = pm0; cdf = pm0; stalled = false;
+                        st = 1;
+                    } else {                                       // equal pieces: shared by the wave
+                        bR = (uint32_t)(lam / 32.0f) + 1u;
+                        r = lam / (float)bR;
+                        pm = expneg(r);
+                        st = 3;
+                    }
+                }
+            } else if (found) {
                 const float q = wq / Mq;
                 if (q >= 1.0f) {
                     emit(kk, R);
@@ -353,7 +379,7 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
                 const bool go = walking && !stalled && u > cdf && xw < L;
                 const uint32_t xn = xw + 1u;
                 float pmn = pm * r;
-                pmn = pmn * (float)(L - xn + 1u);
+                if (!POISSON) pmn = pmn * (float)(L - xn + 1u);
                 pmn = pmn * inv_int((float)xn);
                 const float next = cdf + pmn;
                 const bool still = next == cdf;
@@ -364,9 +390,9 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
                 stalled = stalled || (go && still);
             }
             if (walking && (stalled || !(u > cdf && xw < L))) {   // the piece is finished
-                const uint32_t nk = flip ? bR - xw : xw;
+                const uint32_t nk = (!POISSON && flip) ? bR - xw : xw;
                 if (nk > 0) { emit(kk, nk); SAME_COUNT(a, 5, 1); }   // nonzero counts
-                R -= nk;
+                if (!POISSON) R -= nk;
                 st = 0;
             }
         }
@@ -375,7 +401,7 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
     // ---- pass 2: blocks from last to first
     {
         PhiBlock cur = load_phi<UNIFORM, VEC>(th, ph, nblk - 1);
-        ZeroTest zt((float)R);      // R bounds the remaining count from here on
+        ZeroTest zt(POISSON ? Nf : (float)R);   // R bounds the remaining count from here on
         for (int b = nblk - 1; b >= 0; --b) {
             if (!__any(R > 0)) break;
             PhiBlock nxt = cur;
@@ -396,8 +422,8 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
                 for (int j = 3; j >= 0; --j) {
                     const int k = b * kBlk + g * 4 + j;
                     const float wk = wv[g * 4 + j];
-                    const float Mk = Pv[g * 4 + j] + (k < kstar ? wmax : 0.0f);   // weight not yet decided at k
-                    const bool cand = (k != kstar) && !zt.surely_zero(wk, Mk, x[j]);   // a zero weight passes the test
+                    const float Mk = POISSON ? mu : Pv[g * 4 + j] + (k < kstar ? wmax : 0.0f);   // weight not yet decided at k
+                    const bool cand = (POISSON || k != kstar) && (VEC || k < K) && !zt.surely_zero(wk, Mk, x[j]);   // a zero weight passes the test
                     if (cand) {
                         int e = qh + cnt;
                         e = e >= kQCap ? e - kQCap : e;
@@ -416,13 +442,13 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
                 // trips are run only while some lane could not take the next four topics
                 if (__any(cnt > kQCap - 4)) {
                     do { trip(); } while (__any(cnt > kQCap - 4));
-                    zt = ZeroTest((float)R);
+                    if (!POISSON) zt = ZeroTest((float)R);
                 }
             }
         }
     }
     while (__any(st != 0 || (cnt > 0 && R > 0))) trip();
-    if (R > 0) emit(kstar, R);
+    if (!POISSON && R > 0) emit(kstar, R);
     if (pslot && live) pslot[0] = npairs < (uint32_t)(kPairWords - 1) ? npairs : (uint32_t)(kPairWords - 1);
     if (!DEBUG && live && a.cost) a.cost[tau] = busy;
 }

@@ -71,4 +71,24 @@ __device__ __forceinline__ float ipow(float s, uint32_t n)
     return result;
 }
 
+// exp(-y) for 0 <= y <= 32 from + - * only (Poisson form of the draw): t = y*log2(e), n = trunc(t),
+// f = t-n in [0,1), g = f - 1/2, 2^-(g+1/2) by the degree-7 Taylor polynomial of
+// 2^-1/2 * exp(-g ln 2) in Horner form, every product and sum rounded once, scaled by 2^-n.
+__device__ __forceinline__ float expneg(float y)
+{
+    const float t = y * 1.4426950408889634f;
+    const int n = (int)t;
+    const float f = t - (float)n;
+    const float g = f - 0.5f;
+    float p = -1.0785311504483996e-05f;
+    p = p * g; p = p + 0.00010891940795373223f;
+    p = p * g; p = p + -0.0009428249382684684f;
+    p = p * g; p = p + 0.006801044314331813f;
+    p = p * g; p = p + -0.039247331620610344f;
+    p = p * g; p = p + 0.16986579209153746f;
+    p = p * g; p = p + -0.4901290717342736f;
+    p = p * g; p = p + 0.7071067811865476f;
+    return ldexpf(p, -n);
+}
+
 }  // namespace same

@@ -241,6 +241,23 @@ int grid_for(size_t n, int threads = 256, int cap = 256 * 32)
     return (int)g;
 }
 
+// Copies per token of one pass: an integer (multinomial form) or a positive real (Poisson form).
+struct Copies {
+    uint32_t m = 1;
+    float mf = 1.0f;
+    bool poisson = false;
+    static Copies whole(uint32_t m) { Copies c; c.m = m; c.mf = (float)m; return c; }
+    static Copies real(float mf) { Copies c; c.m = 0; c.mf = mf; c.poisson = true; return c; }
+};
+
+int check_mf(same_lda* h, float m, const Matrix& M)
+{
+    if (!(m > 0.0f) || !std::isfinite(m)) return fail(h, SAME_LDA_EINVAL, "m must be a positive number (got %g)", (double)m);
+    if ((double)m * (double)(M.max_group ? M.max_group : 1u) >= 4194304.0)
+        return fail(h, SAME_LDA_ECSC, "m * largest token group = %g * %u must stay below 2^22", (double)m, M.max_group);
+    return SAME_LDA_OK;
+}
+
 int check_m(same_lda* h, int32_t m, const Matrix& M)
 {
     if (m < 1) return fail(h, SAME_LDA_EINVAL, "m must be >= 1 (got %d)", m);
@@ -250,7 +267,7 @@ int check_m(same_lda* h, int32_t m, const Matrix& M)
 }
 
 template <bool DEBUG>
-int launch_draw(same_lda* h, const same::DrawArgs& a, bool uniform, hipStream_t st)
+int launch_draw(same_lda* h, const same::DrawArgs& a, bool uniform, bool poisson, hipStream_t st)
 {
     if (a.n <= 0) return SAME_LDA_OK;
     const int T = same::kWave;
@@ -259,9 +276,11 @@ int launch_draw(same_lda* h, const same::DrawArgs& a, bool uniform, hipStream_t 
     if (blocks >= (int64_t)1 << 31) return fail(h, SAME_LDA_EINVAL, "too many draw tasks for one launch");
     const bool vec = (a.K % same::kBlk) == 0;
     dim3 grid((unsigned)blocks), block((unsigned)T);
-    if (uniform)      hipLaunchKernelGGL((same::draw_kernel<true, false, DEBUG>), grid, block, lds, st, a);
-    else if (vec)     hipLaunchKernelGGL((same::draw_kernel<false, true, DEBUG>), grid, block, lds, st, a);
-    else              hipLaunchKernelGGL((same::draw_kernel<false, false, DEBUG>), grid, block, lds, st, a);
+    if (uniform)      hipLaunchKernelGGL((same::draw_kernel<true, false, DEBUG, false>), grid, block, lds, st, a);
+    else if (poisson && vec) hipLaunchKernelGGL((same::draw_kernel<false, true, DEBUG, true>), grid, block, lds, st, a);
+    else if (poisson) hipLaunchKernelGGL((same::draw_kernel<false, false, DEBUG, true>), grid, block, lds, st, a);
+    else if (vec)     hipLaunchKernelGGL((same::draw_kernel<false, true, DEBUG, false>), grid, block, lds, st, a);
+    else              hipLaunchKernelGGL((same::draw_kernel<false, false, DEBUG, false>), grid, block, lds, st, a);
     HIP_TRY(h, hipGetLastError());
     return SAME_LDA_OK;
 }
@@ -270,16 +289,18 @@ int launch_draw(same_lda* h, const same::DrawArgs& a, bool uniform, hipStream_t 
 unsigned long long* g_stats = nullptr;   // profiling builds only
 #endif
 
-same::DrawArgs draw_args(const same_lda* h, const Matrix& M, uint32_t m, uint32_t pass_word, bool with_words)
+same::DrawArgs draw_args(const same_lda* h, const Matrix& M, Copies c, uint32_t pass_word, bool with_words)
 {
     same::DrawArgs a;
     a.n = M.n_tasks; a.t_doc = M.t_doc; a.t_word = M.t_word; a.t_g = M.t_g; a.order = M.order; a.cost = M.cost; a.ids = nullptr;
     a.theta = M.theta; a.phi = h->phi; a.ndk = M.ndk; a.nwk = with_words ? h->nwk : nullptr;
     // a pair holds a count below 2^(32 - kPairShift): m * largest group must fit
-    const bool pairs_fit = (uint64_t)m * (uint64_t)(M.max_group ? M.max_group : 1u) < (1ull << (32 - same::kPairShift));
+    // (a Poisson count may exceed its rate: four times the rate plus 128 is beyond any count the walk can return)
+    const double most = (double)c.mf * (double)(M.max_group ? M.max_group : 1u);
+    const bool pairs_fit = (c.poisson ? 4.0 * most + 128.0 : most) < (double)(1ull << (32 - same::kPairShift));
     a.pairs = (with_words && M.pairs && pairs_fit) ? M.pairs : nullptr;
     a.t_slot = M.t_slot;
-    a.K = h->K; a.m = m; a.seed_lo = (uint32_t)h->seed; a.seed_hi = (uint32_t)(h->seed >> 32);
+    a.K = h->K; a.m = c.m; a.mf = c.mf; a.seed_lo = (uint32_t)h->seed; a.seed_hi = (uint32_t)(h->seed >> 32);
     a.pass = pass_word;
 #ifdef SAME_STATS
     a.stats = g_stats;
@@ -297,17 +318,17 @@ int zero_u32(same_lda* h, uint32_t* p, size_t n, hipStream_t st)
     return SAME_LDA_OK;
 }
 
-int update_theta(same_lda* h, Matrix& M, uint32_t m, hipStream_t st)
+int update_theta(same_lda* h, Matrix& M, float m, hipStream_t st)
 {
     const size_t n = (size_t)M.D * h->K;
     if (n == 0) return SAME_LDA_OK;
     hipLaunchKernelGGL(same::theta_update_kernel, dim3(grid_for(n)), dim3(256), 0, st, M.ndk, M.theta, n,
-                       (float)m, h->alpha);
+                       m, h->alpha);
     HIP_TRY(h, hipGetLastError());
     return SAME_LDA_OK;
 }
 
-int update_phi(same_lda* h, uint32_t m, float rho, hipStream_t st)
+int update_phi(same_lda* h, float m, float rho, hipStream_t st)
 {
     const size_t n = (size_t)h->V * h->K;
     hipLaunchKernelGGL(same::zero_u64_kernel, dim3(1), dim3(256), 0, st, h->nk, (size_t)h->K);
@@ -316,13 +337,13 @@ int update_phi(same_lda* h, uint32_t m, float rho, hipStream_t st)
     hipLaunchKernelGGL(same::topic_totals_kernel, dim3(blocks), dim3(256), 0, st, h->nwk, h->V, h->K, h->nk,
                        rows_per_block);
     hipLaunchKernelGGL(same::phi_update_kernel, dim3(grid_for(n)), dim3(256), 0, st, h->nwk, h->nk, h->phi, n,
-                       h->K, (float)m, h->beta, (float)h->V * h->beta, rho);
+                       h->K, m, h->beta, (float)h->V * h->beta, rho);
     HIP_TRY(h, hipGetLastError());
     return SAME_LDA_OK;
 }
 
 // One pass of draws on M.  uniform: weights are all ones (initialisation).
-int run_pass(same_lda* h, Matrix& M, uint32_t m, uint32_t pword, bool uniform, bool with_words, bool timed)
+int run_pass(same_lda* h, Matrix& M, Copies c, uint32_t pword, bool uniform, bool with_words, bool timed)
 {
     hipStream_t st = h->stream;
     int rc;
@@ -343,8 +364,8 @@ int run_pass(same_lda* h, Matrix& M, uint32_t m, uint32_t pword, bool uniform, b
         }
         HIP_TRY(h, hipEventRecord(ev.first, st));
     }
-    const same::DrawArgs a = draw_args(h, M, m, pword, with_words);
-    if ((rc = launch_draw<false>(h, a, uniform, st))) return rc;
+    const same::DrawArgs a = draw_args(h, M, c, pword, with_words);
+    if ((rc = launch_draw<false>(h, a, uniform, c.poisson, st))) return rc;
     if (timed) {
         HIP_TRY(h, hipEventRecord(ev.second, st));
         h->events.push_back(ev);
@@ -408,9 +429,9 @@ int same_lda_init(same_lda_t** out, const same_lda_csc* X, int32_t K, float alph
     if (!rc) rc = dev_alloc(h, &h->phi, (size_t)h->V * K);
     if (!rc) rc = dev_alloc(h, &h->nwk, (size_t)h->V * K);
     if (!rc) rc = dev_alloc(h, &h->nk, (size_t)K);
-    if (!rc) rc = run_pass(h, h->X, (uint32_t)m0, pass_word(0, 0), true, true, false);
-    if (!rc) rc = update_theta(h, h->X, (uint32_t)m0, h->stream);
-    if (!rc) rc = update_phi(h, (uint32_t)m0, 1.0f, h->stream);
+    if (!rc) rc = run_pass(h, h->X, Copies::whole((uint32_t)m0), pass_word(0, 0), true, true, false);
+    if (!rc) rc = update_theta(h, h->X, (float)m0, h->stream);
+    if (!rc) rc = update_phi(h, (float)m0, 1.0f, h->stream);
     if (!rc) { hipError_t e = hipStreamSynchronize(h->stream); if (e != hipSuccess) rc = fail(h, SAME_LDA_EHIP, "init: %s", hipGetErrorString(e)); }
     if (rc) { g_init_error = h->error; same_lda_free(h); return rc; }
     h->pass = 1;
@@ -423,9 +444,21 @@ int same_lda_sweep(same_lda_t* h, int32_t m_t, float rho_t)
     if (!h) return SAME_LDA_EINVAL;
     if (!(rho_t > 0.f) || rho_t > 1.f) return fail(h, SAME_LDA_EINVAL, "rho must be in (0, 1] (got %g)", (double)rho_t);
     int rc = check_m(h, m_t, h->X);
-    if (!rc) rc = run_pass(h, h->X, (uint32_t)m_t, pass_word(h->pass, 0), false, true, h->timing);
-    if (!rc) rc = update_theta(h, h->X, (uint32_t)m_t, h->stream);
-    if (!rc) rc = update_phi(h, (uint32_t)m_t, rho_t, h->stream);
+    if (!rc) rc = run_pass(h, h->X, Copies::whole((uint32_t)m_t), pass_word(h->pass, 0), false, true, h->timing);
+    if (!rc) rc = update_theta(h, h->X, (float)m_t, h->stream);
+    if (!rc) rc = update_phi(h, (float)m_t, rho_t, h->stream);
+    if (!rc) h->pass += 1;
+    return rc;
+}
+
+int same_lda_sweep_poisson(same_lda_t* h, float m_t, float rho_t)
+{
+    if (!h) return SAME_LDA_EINVAL;
+    if (!(rho_t > 0.f) || rho_t > 1.f) return fail(h, SAME_LDA_EINVAL, "rho must be in (0, 1] (got %g)", (double)rho_t);
+    int rc = check_mf(h, m_t, h->X);
+    if (!rc) rc = run_pass(h, h->X, Copies::real(m_t), pass_word(h->pass, 0), false, true, h->timing);
+    if (!rc) rc = update_theta(h, h->X, m_t, h->stream);
+    if (!rc) rc = update_phi(h, m_t, rho_t, h->stream);
     if (!rc) h->pass += 1;
     return rc;
 }
@@ -440,8 +473,8 @@ int same_lda_set_batch(same_lda_t* h, const same_lda_csc* X, int32_t m_init)
     if (rc) { free_matrix(M); return rc; }
     free_matrix(h->X);
     h->X = M;
-    rc = run_pass(h, h->X, (uint32_t)m_init, pass_word(h->pass, 0), true, false, false);
-    if (!rc) rc = update_theta(h, h->X, (uint32_t)m_init, h->stream);
+    rc = run_pass(h, h->X, Copies::whole((uint32_t)m_init), pass_word(h->pass, 0), true, false, false);
+    if (!rc) rc = update_theta(h, h->X, (float)m_init, h->stream);
     if (!rc) HIP_TRY(h, hipStreamSynchronize(h->stream));
     if (!rc) h->pass += 1;
     return rc;
@@ -458,11 +491,11 @@ int same_lda_loglik(same_lda_t* h, const same_lda_csc* Xtest, int32_t foldin_swe
     const int nblocks = (int)((M.nnz + 255) / 256);
     if (!rc) rc = dev_alloc(h, &doc_log, (size_t)M.D);
     if (!rc) rc = dev_alloc(h, &part, (size_t)nblocks);
-    if (!rc) rc = run_pass(h, M, (uint32_t)m_eval, pass_word(0, 1), true, false, false);
-    if (!rc) rc = update_theta(h, M, (uint32_t)m_eval, h->stream);
+    if (!rc) rc = run_pass(h, M, Copies::whole((uint32_t)m_eval), pass_word(0, 1), true, false, false);
+    if (!rc) rc = update_theta(h, M, (float)m_eval, h->stream);
     for (int32_t s = 1; !rc && s <= foldin_sweeps; ++s) {
-        rc = run_pass(h, M, (uint32_t)m_eval, pass_word(s, 1), false, false, false);
-        if (!rc) rc = update_theta(h, M, (uint32_t)m_eval, h->stream);
+        rc = run_pass(h, M, Copies::whole((uint32_t)m_eval), pass_word(s, 1), false, false, false);
+        if (!rc) rc = update_theta(h, M, (float)m_eval, h->stream);
     }
     double total = 0.0;
     if (!rc && M.nnz > 0) {
@@ -542,11 +575,11 @@ int same_lda_task_count(const same_lda_t* h, int64_t* count)
     return SAME_LDA_OK;
 }
 
-int same_lda_debug_draw(same_lda_t* h, int32_t m_t, const int64_t* task_ids, int32_t n, uint32_t* counts_out)
+namespace {
+int debug_draw(same_lda_t* h, Copies c, const int64_t* task_ids, int32_t n, uint32_t* counts_out)
 {
-    if (!h) return SAME_LDA_EINVAL;
     if (n < 0 || (n > 0 && (!task_ids || !counts_out))) return fail(h, SAME_LDA_EINVAL, "bad debug_draw arguments");
-    int rc = check_m(h, m_t, h->X);
+    int rc = c.poisson ? check_mf(h, c.mf, h->X) : check_m(h, (int32_t)c.m, h->X);
     if (rc || n == 0) return rc;
     for (int32_t i = 0; i < n; ++i)
         if (task_ids[i] < 0 || task_ids[i] >= h->X.n_tasks) return fail(h, SAME_LDA_EINVAL, "task id %lld out of range", (long long)task_ids[i]);
@@ -559,9 +592,9 @@ int same_lda_debug_draw(same_lda_t* h, int32_t m_t, const int64_t* task_ids, int
     }
     if (!rc) rc = zero_u32(h, out_d, (size_t)n * h->K, h->stream);
     if (!rc) {
-        same::DrawArgs a = draw_args(h, h->X, (uint32_t)m_t, pass_word(h->pass, 0), false);
+        same::DrawArgs a = draw_args(h, h->X, c, pass_word(h->pass, 0), false);
         a.n = n; a.ids = ids_d; a.ndk = out_d; a.nwk = nullptr; a.cost = nullptr;
-        rc = launch_draw<true>(h, a, false, h->stream);
+        rc = launch_draw<true>(h, a, false, c.poisson, h->stream);
     }
     if (!rc) {
         hipError_t e = hipMemcpyAsync(counts_out, out_d, (size_t)n * h->K * 4, hipMemcpyDeviceToHost, h->stream);
@@ -570,6 +603,20 @@ int same_lda_debug_draw(same_lda_t* h, int32_t m_t, const int64_t* task_ids, int
     }
     hipFree(ids_d); hipFree(out_d);
     return rc;
+}
+}  // namespace
+
+int same_lda_debug_draw(same_lda_t* h, int32_t m_t, const int64_t* task_ids, int32_t n, uint32_t* counts_out)
+{
+    if (!h) return SAME_LDA_EINVAL;
+    if (m_t < 1) return fail(h, SAME_LDA_EINVAL, "m must be >= 1 (got %d)", m_t);
+    return debug_draw(h, Copies::whole((uint32_t)m_t), task_ids, n, counts_out);
+}
+
+int same_lda_debug_draw_poisson(same_lda_t* h, float m_t, const int64_t* task_ids, int32_t n, uint32_t* counts_out)
+{
+    if (!h) return SAME_LDA_EINVAL;
+    return debug_draw(h, Copies::real(m_t), task_ids, n, counts_out);
 }
 
 int same_lda_set_timing(same_lda_t* h, int32_t enabled)

@@ -290,3 +290,66 @@ def test_streamed_minibatches_abstract_shape():
         o.sweep(m, rho); g.sweep(m, rho)
         assert_state_equal(g, o, f"minibatch {t} m={m} rho={rho}")
     g.close()
+
+
+# --------------------------------------------------------------------------- #
+# Poisson form of the factored draw (Section 4, second part; Algorithm 3's sampling line)
+@pytest.mark.parametrize("K,G,ms", [(16, 8, [10.0, 0.5, 3.25]), (24, 1, [1.0, 30.0]), (40, 3, [100.0, 2.5]),
+                                    (5, 1000, [400.0, 0.1])])
+def test_poisson_sweeps_bit_exact(K, G, ms):
+    """Sweeps in the Poisson form with integer and non-integer m (below 1 too); large m * c gives rates far
+    above 32 (pieces shared by the wave); K=40 and K=5 take the ragged path."""
+    X = toy(seed=8, D=70, V=50, density=0.3, cmax=40)
+    o = oracle.OracleLDA(X, K, 0.1, 0.01, seed=5, m0=3, G=G)
+    g = make_gpu(X, K, 0.1, 0.01, 5, 3, G, on_device=True)
+    assert_state_equal(g, o, "init")
+    for s, m in enumerate(ms):
+        o.sweep_poisson(m); g.sweep_poisson(m)
+        assert_state_equal(g, o, f"K={K} G={G} poisson sweep {s + 1} m={m}")
+    g.close()
+
+
+def test_poisson_news_shape_slice_and_mixed_forms():
+    """News workload shape (K=256) on a 600-document slice: Poisson sweeps at m=100 (frequent words go through
+    the pair list), alternating with the multinomial form and a blend, on one handle and one stream of passes."""
+    p = synth.PRESETS["news"]
+    X = corpus_to_csc(synth.preset("news", scale=0.002))
+    o = oracle.OracleLDA(X, p["K"], p["alpha"], p["beta"], seed=9, m0=1, G=32)
+    g = make_gpu(X, p["K"], p["alpha"], p["beta"], 9, 1, 32)
+    assert_state_equal(g, o, "init")
+    o.sweep_poisson(100.0); g.sweep_poisson(100.0)
+    assert_state_equal(g, o, "poisson m=100")
+    o.sweep(20); g.sweep(20)
+    assert_state_equal(g, o, "multinomial m=20")
+    o.sweep_poisson(37.5, 0.6); g.sweep_poisson(37.5, 0.6)
+    assert_state_equal(g, o, "poisson m=37.5 rho=0.6")
+    assert g.pass_index == o.t == 4
+    # the copies of a token no longer total exactly m * c
+    ntok = np.bincount(np.repeat(np.arange(X.D), np.diff(X.colptr)), weights=X.val, minlength=X.D)
+    assert np.any(g.get(binding.NDK).sum(axis=1) != 37.5 * ntok)
+    g.close()
+
+
+def test_poisson_debug_draw_matches_oracle_tasks():
+    X = toy(seed=12, D=50, V=30, density=0.4, cmax=25)
+    K, G, m = 32, 4, 12.5
+    o = oracle.OracleLDA(X, K, 0.2, 0.05, seed=31, m0=5, G=G)
+    g = make_gpu(X, K, 0.2, 0.05, 31, 5, G)
+    ids = np.arange(0, g.task_count, 3)
+    want = oracle.draw_tasks_poisson(X, K, G, m, 31, oracle.pass_word(o.t), o.theta, o.phi, ids)
+    got = g.debug_draw_poisson(m, ids)
+    assert np.array_equal(got, want)
+    o.sweep_poisson(m); g.sweep_poisson(m)
+    assert_state_equal(g, o, "sweep after the hook")
+    g.close()
+
+
+def test_poisson_rejects_bad_m():
+    X = toy(seed=1, D=10, V=10, density=0.5, cmax=3)
+    g = make_gpu(X, 4, 0.1, 0.01, 1, 2, 8)
+    for bad in (0.0, -1.0, float("nan"), float("inf"), 1e9):
+        with pytest.raises(binding.SameLdaError):
+            g.sweep_poisson(bad)
+    g.sweep_poisson(0.25)
+    g.synchronize()
+    g.close()
