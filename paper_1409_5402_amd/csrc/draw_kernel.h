@@ -131,17 +131,20 @@ __device__ __forceinline__ void block_weights(const float* __restrict__ th, cons
 
 // The drop test without a division: for q = w/M it checks q <= 0.499 and
 // u + Rf*(q*(1+1e-4) + 1e-6) <= 1 - 1e-4, both multiplied through by M > 0
-// (the margins cover the few roundings of this evaluation).  ZeroTest holds the two terms that
-// depend only on the bound Rf; x is the raw random word of the topic (u = (2*(x>>9)+1)/2^24).
+// (the margins cover the few roundings of this evaluation), in one comparison A*w <= d*M:
+//   d = (1-1e-4) - Rf*1e-6 - u', with u' = x * 2^-32 rounded, never below u - 2^-24 (x is the raw
+//       random word of the topic, u = (2*(x>>9)+1)/2^24; the 2^-24 is taken off in Bp);
+//   A = max(Rf*(1+1e-4), 2.0041): since d < 1, A*w <= d*M also gives w/M < 1/2.0041 < 0.499.
+// ZeroTest holds the two terms that depend only on the bound Rf.
 struct ZeroTest {
     float A, Bp;
     __device__ __forceinline__ explicit ZeroTest(float Rf)
-        : A(Rf * 1.0001f), Bp((0.9999f - Rf * 1.0e-6f) - 5.9604644775390625e-8f) {}
+        : A(fmaxf(Rf * 1.0001f, 2.0041f)), Bp((0.9999f - Rf * 1.0e-6f) - 5.9604644775390625e-8f) {}
     // true when Bin(R', w/M) is certainly 0 for every R' <= Rf (see the header comment)
     __device__ __forceinline__ bool surely_zero(float wk, float Mk, uint32_t x) const
     {
-        const float d = __builtin_fmaf((float)(x >> 9), -1.1920928955078125e-7f, Bp);   // (1-1e-4) - Rf*1e-6 - u
-        return (wk <= 0.499f * Mk) && (A * wk <= d * Mk);
+        const float d = __builtin_fmaf((float)x, -2.3283064365386963e-10f, Bp);
+        return A * wk <= d * Mk;
     }
 };
 
@@ -323,6 +326,7 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
                 u = uniform_from_word(xk);
                 qh = (qh + 1 == kQCap) ? 0 : qh + 1;
                 --cnt;
+                if (!POISSON && kk == kstar) continue;             // the scan does not single out the heaviest topic
                 if (POISSON || !ZeroTest((float)R).surely_zero(wq, Mq, xk)) { found = true; break; }
             }
             if (R == 0) cnt = 0;                                   // nothing left to place: the rest is void
@@ -423,7 +427,8 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
                     const int k = b * kBlk + g * 4 + j;
                     const float wk = wv[g * 4 + j];
                     const float Mk = POISSON ? mu : Pv[g * 4 + j] + (k < kstar ? wmax : 0.0f);   // weight not yet decided at k
-                    const bool cand = (POISSON || k != kstar) && (VEC || k < K) && !zt.surely_zero(wk, Mk, x[j]);   // a zero weight passes the test
+                    // a zero weight passes the test; the heaviest topic may be queued: the chain skips it
+                    const bool cand = (VEC || k < K) && !zt.surely_zero(wk, Mk, x[j]);
                     if (cand) {
                         int e = qh + cnt;
                         e = e >= kQCap ? e - kQCap : e;
