@@ -5,7 +5,7 @@ import os
 import subprocess
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-SRC = os.path.join(HERE, "csrc", "same_lda.hip")
+SRC = [os.path.join(HERE, "csrc", "same_lda.hip"), os.path.join(HERE, "csrc", "worklist.hip")]
 LIB = os.path.join(HERE, "libsame_lda.so")
 
 # -ffp-contract=off: every binary32 step of the draw is rounded once (no fused multiply-add);
@@ -17,7 +17,7 @@ FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-ffp-contract=off",
 
 def build(verbose: bool = False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *FLAGS, "-o", LIB, SRC]
+    cmd = [hipcc, *FLAGS, "-o", LIB, *SRC]
     res = subprocess.run(cmd, capture_output=True, text=True)
     if verbose or res.returncode != 0:
         print(" ".join(cmd))

@@ -13,6 +13,7 @@
 #include <vector>
 
 #include "update_kernels.h"
+#include "worklist_kernels.h"
 
 namespace {
 
@@ -33,6 +34,7 @@ struct Matrix {
     int32_t*  tile_start = nullptr;// [n_tiles+1] first task id of every document tile
     uint32_t* cost = nullptr;      // [n_tasks] drain work each task reported in the last pass
     int32_t   n_tiles = 0;
+    int32_t*  colptr = nullptr;    // [D+1]
     int32_t*  nz_doc = nullptr;    // [nnz]
     int32_t*  rowidx = nullptr;    // [nnz]
     float*    val = nullptr;       // [nnz]
@@ -95,13 +97,32 @@ int dev_alloc(same_lda* h, T** p, size_t n)
 
 void free_matrix(Matrix& M)
 {
-    hipFree(M.t_doc); hipFree(M.t_word); hipFree(M.t_g); hipFree(M.order); hipFree(M.tile_start); hipFree(M.cost); hipFree(M.nz_doc);
+    hipFree(M.colptr); hipFree(M.t_doc); hipFree(M.t_word); hipFree(M.t_g); hipFree(M.order); hipFree(M.tile_start); hipFree(M.cost); hipFree(M.nz_doc);
     hipFree(M.rowidx); hipFree(M.val); hipFree(M.theta); hipFree(M.ndk);
     hipFree(M.pairs); hipFree(M.t_slot); hipFree(M.slot_word);
     M = Matrix();
 }
 
-// Validates the matrix, builds the work list on the host and uploads it.
+int grid_for(size_t n, int threads = 256, int cap = 256 * 32);
+
+// Device temporaries of one build, released together at the end (hipFree waits for the device,
+// so it is called once).
+struct Temps {
+    std::vector<void*> ptrs;
+    template <class T> hipError_t get(T** p, size_t n)
+    {
+        *p = nullptr;
+        void* v = nullptr;
+        const hipError_t e = hipMalloc(&v, (n ? n : 1) * sizeof(T));
+        if (e == hipSuccess) { ptrs.push_back(v); *p = static_cast<T*>(v); }
+        return e;
+    }
+    ~Temps() { for (void* v : ptrs) hipFree(v); }
+};
+
+// Validates the matrix and builds its work list on the device (worklist_kernels.h).  The matrix may
+// live on the host or on the device; it is copied once.  All work is enqueued on st; the call
+// waits for st twice (to learn the number of tasks and of pair-list slots).
 int build_matrix(same_lda* h, const same_lda_csc* X, int32_t V, int32_t K, int32_t G, Matrix& M, hipStream_t st,
                  bool with_pairs)
 {
@@ -113,127 +134,126 @@ int build_matrix(same_lda* h, const same_lda_csc* X, int32_t V, int32_t K, int32
         return fail(h, SAME_LDA_EINVAL, "matrix arrays are null");
     const int32_t D = X->D;
     const int64_t nnz = X->nnz;
-    std::vector<int32_t> colptr_h, rowidx_h;
-    std::vector<float> val_h;
-    const int32_t* colptr = X->colptr;
-    const int32_t* rowidx = X->rowidx;
-    const float* val = X->val;
-    try {
-        if (X->on_device) {
-            colptr_h.resize((size_t)D + 1); rowidx_h.resize((size_t)nnz); val_h.resize((size_t)nnz);
-            HIP_TRY(h, hipMemcpy(colptr_h.data(), X->colptr, ((size_t)D + 1) * 4, hipMemcpyDeviceToHost));
-            if (nnz) {
-                HIP_TRY(h, hipMemcpy(rowidx_h.data(), X->rowidx, (size_t)nnz * 4, hipMemcpyDeviceToHost));
-                HIP_TRY(h, hipMemcpy(val_h.data(), X->val, (size_t)nnz * 4, hipMemcpyDeviceToHost));
-            }
-            colptr = colptr_h.data(); rowidx = rowidx_h.data(); val = val_h.data();
-        }
-        if (colptr[0] != 0 || (int64_t)colptr[D] != nnz)
-            return fail(h, SAME_LDA_ECSC, "colptr[0]=%d colptr[D]=%d do not match nnz=%lld", colptr[0], colptr[D],
-                        (long long)nnz);
-        std::vector<int32_t> t_doc, t_word, nz_doc((size_t)nnz);
-        std::vector<uint32_t> t_g;
-        t_doc.reserve((size_t)nnz + 16); t_word.reserve((size_t)nnz + 16); t_g.reserve((size_t)nnz + 16);
-        uint32_t max_group = 0;
-        double tokens = 0.0;
-        for (int32_t d = 0; d < D; ++d) {
-            if (colptr[d + 1] < colptr[d])
-                return fail(h, SAME_LDA_ECSC, "colptr decreases at document %d", d);
-            for (int64_t i = colptr[d]; i < colptr[d + 1]; ++i) {
-                const int32_t w = rowidx[i];
-                const float c = val[i];
-                if (w < 0 || w >= V) return fail(h, SAME_LDA_ECSC, "word id %d out of range at entry %lld", w, (long long)i);
-                if (!(c >= 1.0f) || c >= 16777216.0f || c != std::floor(c))
-                    return fail(h, SAME_LDA_ECSC, "count %g at entry %lld is not an integer in [1, 2^24)", (double)c, (long long)i);
-                nz_doc[(size_t)i] = d;
-                uint32_t left = (uint32_t)c;
-                tokens += (double)left;
-                while (left > 0) {
-                    const uint32_t g = left < (uint32_t)G ? left : (uint32_t)G;
-                    t_doc.push_back(d); t_word.push_back(w); t_g.push_back(g);
-                    if (g > max_group) max_group = g;
-                    left -= g;
-                }
-            }
-        }
-        if (t_doc.size() >= ((size_t)1 << 31))
-            return fail(h, SAME_LDA_ECSC, "too many draw tasks (%zu); raise tokens_per_draw", t_doc.size());
-        // Processing order: documents are taken in tiles of kTileDocs (the theta rows a wave touches
-        // stay within one small tile); inside a tile the order starts as storage order and is
-        // re-sorted before every sweep by the cost each task reported in the previous pass, so that
-        // the 64 lanes of a wave run chains of similar length.  The order does not affect results:
-        // tasks are independent and keyed by their id.
-        std::vector<int32_t> order(t_doc.size()), tile_start;
-        for (size_t i = 0; i < t_doc.size(); ++i) {
-            order[i] = (int32_t)i;
-            if (i == 0 || t_doc[i] / kTileDocs != t_doc[i - 1] / kTileDocs) tile_start.push_back((int32_t)i);
-        }
-        tile_start.push_back((int32_t)t_doc.size());
-        M.n_tiles = (int32_t)tile_start.size() - 1;
-        M.D = D; M.nnz = nnz; M.n_tasks = (int64_t)t_doc.size(); M.max_group = max_group; M.tokens = tokens;
-        int rc;
-        if ((rc = dev_alloc(h, &M.t_doc, t_doc.size()))) return rc;
-        if ((rc = dev_alloc(h, &M.t_word, t_word.size()))) return rc;
-        if ((rc = dev_alloc(h, &M.t_g, t_g.size()))) return rc;
-        if ((rc = dev_alloc(h, &M.order, order.size()))) return rc;
-        if ((rc = dev_alloc(h, &M.tile_start, tile_start.size()))) return rc;
-        if ((rc = dev_alloc(h, &M.cost, order.size()))) return rc;
-        if ((rc = dev_alloc(h, &M.nz_doc, (size_t)nnz))) return rc;
-        if ((rc = dev_alloc(h, &M.rowidx, (size_t)nnz))) return rc;
-        if ((rc = dev_alloc(h, &M.val, (size_t)nnz))) return rc;
-        if ((rc = dev_alloc(h, &M.theta, (size_t)D * K))) return rc;
-        if ((rc = dev_alloc(h, &M.ndk, (size_t)D * K))) return rc;
-        if (M.n_tasks) {
-            HIP_TRY(h, hipMemcpyAsync(M.t_doc, t_doc.data(), t_doc.size() * 4, hipMemcpyHostToDevice, st));
-            HIP_TRY(h, hipMemcpyAsync(M.t_word, t_word.data(), t_word.size() * 4, hipMemcpyHostToDevice, st));
-            HIP_TRY(h, hipMemcpyAsync(M.t_g, t_g.data(), t_g.size() * 4, hipMemcpyHostToDevice, st));
-            HIP_TRY(h, hipMemcpyAsync(M.order, order.data(), order.size() * 4, hipMemcpyHostToDevice, st));
-            HIP_TRY(h, hipMemcpyAsync(M.tile_start, tile_start.data(), tile_start.size() * 4, hipMemcpyHostToDevice, st));
-            HIP_TRY(h, hipMemsetAsync(M.cost, 0, order.size() * 4, st));
-            HIP_TRY(h, hipMemcpyAsync(M.nz_doc, nz_doc.data(), (size_t)nnz * 4, hipMemcpyHostToDevice, st));
-            HIP_TRY(h, hipMemcpyAsync(M.rowidx, rowidx, (size_t)nnz * 4, hipMemcpyHostToDevice, st));
-            HIP_TRY(h, hipMemcpyAsync(M.val, val, (size_t)nnz * 4, hipMemcpyHostToDevice, st));
-        }
-        // Pair list: slots in (word, task id) order for the tasks of frequent words.  Optional: without
-        // it the draw kernel updates the word rows directly.
-        if (with_pairs && M.n_tasks > 0) {
-            std::vector<int32_t> cursor((size_t)V + 1, 0), t_slot(t_word.size());
-            for (int32_t w : t_word) cursor[(size_t)w + 1] += 1;
-            int64_t n_slots = 0;
-            for (int32_t w = 0; w < V; ++w) {                      // cursor[w+1] = tasks of w -> first slot of w, or -1
-                const int32_t c = cursor[(size_t)w + 1];
-                cursor[(size_t)w] = c >= same::kSlotMinTasks ? (int32_t)n_slots : -1;
-                if (c >= same::kSlotMinTasks) n_slots += c;
-            }
-            std::vector<int32_t> slot_word((size_t)n_slots);
-            for (size_t i = 0; i < t_word.size(); ++i) {
-                int32_t& cur = cursor[(size_t)t_word[i]];
-                t_slot[i] = cur;
-                if (cur >= 0) { slot_word[(size_t)cur] = t_word[i]; cur += 1; }
-            }
-            const size_t n = t_word.size();
-            if (n_slots > 0 &&
-                hipMalloc(reinterpret_cast<void**>(&M.pairs), (size_t)n_slots * same::kPairWords * sizeof(uint32_t)) == hipSuccess &&
-                hipMalloc(reinterpret_cast<void**>(&M.t_slot), n * 4) == hipSuccess &&
-                hipMalloc(reinterpret_cast<void**>(&M.slot_word), (size_t)n_slots * 4) == hipSuccess) {
-                M.n_slots = n_slots;
-                HIP_TRY(h, hipMemcpyAsync(M.t_slot, t_slot.data(), n * 4, hipMemcpyHostToDevice, st));
-                HIP_TRY(h, hipMemcpyAsync(M.slot_word, slot_word.data(), (size_t)n_slots * 4, hipMemcpyHostToDevice, st));
-                HIP_TRY(h, hipStreamSynchronize(st));
-            } else {
-                (void)hipGetLastError();
-                hipFree(M.pairs); hipFree(M.t_slot); hipFree(M.slot_word);
-                M.pairs = nullptr; M.t_slot = nullptr; M.slot_word = nullptr; M.n_slots = 0;
-            }
-        }
-        HIP_TRY(h, hipStreamSynchronize(st));   // the host vectors go out of scope below
-    } catch (const std::bad_alloc&) {
-        return fail(h, SAME_LDA_ENOMEM, "host allocation failed while building the work list");
+    const hipMemcpyKind kind = X->on_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice;
+    int32_t ends[2] = {0, 0};
+    if (X->on_device) {
+        HIP_TRY(h, hipMemcpy(&ends[0], X->colptr, 4, hipMemcpyDeviceToHost));
+        HIP_TRY(h, hipMemcpy(&ends[1], X->colptr + D, 4, hipMemcpyDeviceToHost));
+    } else {
+        ends[0] = X->colptr[0]; ends[1] = X->colptr[D];
     }
+    if (ends[0] != 0 || (int64_t)ends[1] != nnz)
+        return fail(h, SAME_LDA_ECSC, "colptr[0]=%d colptr[D]=%d do not match nnz=%lld", ends[0], ends[1], (long long)nnz);
+
+    M.D = D; M.nnz = nnz;
+    int rc;
+    if ((rc = dev_alloc(h, &M.colptr, (size_t)D + 1))) return rc;
+    if ((rc = dev_alloc(h, &M.nz_doc, (size_t)nnz))) return rc;
+    if ((rc = dev_alloc(h, &M.rowidx, (size_t)nnz))) return rc;
+    if ((rc = dev_alloc(h, &M.val, (size_t)nnz))) return rc;
+    HIP_TRY(h, hipMemcpyAsync(M.colptr, X->colptr, ((size_t)D + 1) * 4, kind, st));
+    if (nnz) {
+        HIP_TRY(h, hipMemcpyAsync(M.rowidx, X->rowidx, (size_t)nnz * 4, kind, st));
+        HIP_TRY(h, hipMemcpyAsync(M.val, X->val, (size_t)nnz * 4, kind, st));
+    }
+
+    Temps tmp;
+    same::BuildStats* d_stats = nullptr;
+    uint32_t *ntask = nullptr, *tbase = nullptr;
+    void* scan_tmp = nullptr;
+    const size_t scan_bytes = same::wl_exclusive_sum_bytes((size_t)nnz + 1);
+    HIP_TRY(h, tmp.get(&d_stats, 1));
+    HIP_TRY(h, tmp.get(&ntask, (size_t)nnz + 1));
+    HIP_TRY(h, tmp.get(&tbase, (size_t)nnz + 1));
+    HIP_TRY(h, tmp.get(reinterpret_cast<char**>(&scan_tmp), scan_bytes));
+    hipLaunchKernelGGL(same::wl_init_stats, dim3(1), dim3(1), 0, st, d_stats);
+    if (D > 0) hipLaunchKernelGGL(same::wl_check_cols, dim3((unsigned)((D + 255) / 256)), dim3(256), 0, st, M.colptr, D, d_stats);
+    hipLaunchKernelGGL(same::wl_scan_nonzeros, dim3(grid_for((size_t)nnz + 1)), dim3(256), 0, st, M.colptr, M.rowidx,
+                       M.val, D, nnz, V, (uint32_t)G, M.nz_doc, ntask, d_stats);
+    HIP_TRY(h, hipGetLastError());
+    same::BuildStats stats;
+    HIP_TRY(h, hipMemcpyAsync(&stats, d_stats, sizeof(stats), hipMemcpyDeviceToHost, st));
+    HIP_TRY(h, hipStreamSynchronize(st));
+    if (stats.first_bad != ~0ull) {
+        const long long where = (long long)(stats.first_bad >> 2);
+        switch ((int)(stats.first_bad & 3ull)) {
+            case 1:  return fail(h, SAME_LDA_ECSC, "colptr decreases at document %lld", where);
+            case 2:  return fail(h, SAME_LDA_ECSC, "word id out of range at entry %lld", where);
+            default: return fail(h, SAME_LDA_ECSC, "count at entry %lld is not an integer in [1, 2^24)", where);
+        }
+    }
+    if (stats.n_tasks >= (1ull << 31))
+        return fail(h, SAME_LDA_ECSC, "too many draw tasks (%llu); raise tokens_per_draw", stats.n_tasks);
+    const size_t n = (size_t)stats.n_tasks;
+    M.n_tasks = (int64_t)n; M.max_group = stats.max_group; M.tokens = (double)stats.tokens;
+
+    // Processing order: documents are taken in tiles of kTileDocs (the theta rows a wave touches stay
+    // within one small tile); inside a tile the order starts as storage order and is re-sorted before
+    // every sweep by the cost each task reported in the previous pass, so that the 64 lanes of a wave
+    // run chains of similar length.  The order does not affect results: tasks are independent and
+    // keyed by their id.
+    M.n_tiles = (D + kTileDocs - 1) / kTileDocs;
+    if ((rc = dev_alloc(h, &M.t_doc, n))) return rc;
+    if ((rc = dev_alloc(h, &M.t_word, n))) return rc;
+    if ((rc = dev_alloc(h, &M.t_g, n))) return rc;
+    if ((rc = dev_alloc(h, &M.order, n))) return rc;
+    if ((rc = dev_alloc(h, &M.cost, n))) return rc;
+    if ((rc = dev_alloc(h, &M.tile_start, (size_t)M.n_tiles + 1))) return rc;
+    if ((rc = dev_alloc(h, &M.theta, (size_t)D * K))) return rc;
+    if ((rc = dev_alloc(h, &M.ndk, (size_t)D * K))) return rc;
+    HIP_TRY(h, same::wl_exclusive_sum(scan_tmp, scan_bytes, ntask, tbase, (size_t)nnz + 1, st));
+    if (nnz)
+        hipLaunchKernelGGL(same::wl_expand, dim3(grid_for((size_t)nnz)), dim3(256), 0, st, M.nz_doc, M.rowidx, M.val,
+                           tbase, nnz, (uint32_t)G, M.t_doc, M.t_word, M.t_g, M.order, M.cost);
+    hipLaunchKernelGGL(same::wl_tiles, dim3((unsigned)((M.n_tiles + 256) / 256)), dim3(256), 0, st, M.colptr, tbase, D,
+                       kTileDocs, M.n_tiles, M.tile_start);
+    HIP_TRY(h, hipGetLastError());
+
+    // Pair list: slots in (word, task id) order for the tasks of frequent words.  Optional: without
+    // it the draw kernel updates the word rows directly.
+    if (with_pairs && n > 0) {
+        int bits = 1;
+        while (((int64_t)1 << bits) < (int64_t)V) ++bits;
+        int32_t *iota = nullptr, *keys = nullptr, *tasks = nullptr, *wstart = nullptr;
+        uint32_t *flag = nullptr, *pos = nullptr;
+        void *sort_tmp = nullptr, *scan2_tmp = nullptr;
+        const size_t sort_bytes = same::wl_sort_pairs_bytes(n, bits);
+        const size_t scan2_bytes = same::wl_exclusive_sum_bytes(n + 1);
+        bool ok = tmp.get(&iota, n) == hipSuccess && tmp.get(&keys, n) == hipSuccess && tmp.get(&tasks, n) == hipSuccess &&
+                  tmp.get(&wstart, (size_t)V + 1) == hipSuccess && tmp.get(&flag, n + 1) == hipSuccess &&
+                  tmp.get(&pos, n + 1) == hipSuccess &&
+                  tmp.get(reinterpret_cast<char**>(&sort_tmp), sort_bytes) == hipSuccess &&
+                  tmp.get(reinterpret_cast<char**>(&scan2_tmp), scan2_bytes) == hipSuccess &&
+                  hipMalloc(reinterpret_cast<void**>(&M.t_slot), n * 4) == hipSuccess &&
+                  hipMalloc(reinterpret_cast<void**>(&M.slot_word), n * 4) == hipSuccess;
+        if (ok) {
+            hipLaunchKernelGGL(same::wl_iota, dim3(grid_for(n)), dim3(256), 0, st, iota, (int64_t)n);
+            HIP_TRY(h, same::wl_sort_pairs(sort_tmp, sort_bytes, M.t_word, keys, iota, tasks, n, bits, st));
+            hipLaunchKernelGGL(same::wl_word_starts, dim3((unsigned)((V + 256) / 256)), dim3(256), 0, st, keys,
+                               (int32_t)n, V, wstart);
+            hipLaunchKernelGGL(same::wl_slot_flags, dim3(grid_for(n + 1)), dim3(256), 0, st, keys, wstart, (int64_t)n,
+                               (int32_t)same::kSlotMinTasks, flag);
+            HIP_TRY(h, same::wl_exclusive_sum(scan2_tmp, scan2_bytes, flag, pos, n + 1, st));
+            hipLaunchKernelGGL(same::wl_slot_scatter, dim3(grid_for(n)), dim3(256), 0, st, keys, tasks, flag, pos,
+                               (int64_t)n, M.t_slot, M.slot_word, d_stats);
+            HIP_TRY(h, hipGetLastError());
+            HIP_TRY(h, hipMemcpyAsync(&stats, d_stats, sizeof(stats), hipMemcpyDeviceToHost, st));
+            HIP_TRY(h, hipStreamSynchronize(st));
+            M.n_slots = (int64_t)stats.n_slots;
+            ok = M.n_slots > 0 &&
+                 hipMalloc(reinterpret_cast<void**>(&M.pairs), (size_t)M.n_slots * same::kPairWords * sizeof(uint32_t)) == hipSuccess;
+        }
+        if (!ok) {
+            (void)hipGetLastError();
+            hipFree(M.pairs); hipFree(M.t_slot); hipFree(M.slot_word);
+            M.pairs = nullptr; M.t_slot = nullptr; M.slot_word = nullptr; M.n_slots = 0;
+        }
+    }
+    HIP_TRY(h, hipStreamSynchronize(st));   // the temporaries are released on return
     return SAME_LDA_OK;
 }
 
-int grid_for(size_t n, int threads = 256, int cap = 256 * 32)
+int grid_for(size_t n, int threads, int cap)
 {
     size_t g = (n + (size_t)threads - 1) / (size_t)threads;
     if (g < 1) g = 1;

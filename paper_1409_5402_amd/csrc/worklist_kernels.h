@@ -1,0 +1,166 @@
+// Device-side construction of the draw work list from a CSC matrix (columns = documents).
+//
+// A nonzero (d, w, c) stands for c tokens with identical conditionals; its tokens are drawn in
+// groups ("tasks") of at most G.  These kernels validate the matrix and produce, without a host
+// copy of the matrix: the document of every nonzero, the tasks (document, word, group size) in
+// storage order, the first task of every tile of documents, and the slots of the word-ordered pair
+// list.  The two library primitives they need (an exclusive sum and a stable radix sort) are wrapped
+// in worklist.hip.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace same {
+
+// Filled by the kernels below; first_bad is the smallest (index << 2 | code) over all defects found,
+// ~0 if the matrix is sound: code 1 = column pointer decreases (index = document), 2 = word id out
+// of range, 3 = count not an integer in [1, 2^24) (index = nonzero).
+struct BuildStats {
+    unsigned long long tokens;
+    unsigned long long n_tasks;
+    unsigned long long first_bad;
+    uint32_t max_group;
+    uint32_t n_slots;
+};
+
+__global__ void wl_init_stats(BuildStats* s)
+{
+    s->tokens = 0ull; s->n_tasks = 0ull; s->first_bad = ~0ull; s->max_group = 0u; s->n_slots = 0u;
+}
+
+__global__ void wl_check_cols(const int32_t* __restrict__ colptr, int32_t D, BuildStats* s)
+{
+    const int32_t d = (int32_t)(blockIdx.x * blockDim.x + threadIdx.x);
+    if (d < D && colptr[d + 1] < colptr[d]) atomicMin(&s->first_bad, ((unsigned long long)d << 2) | 1ull);
+}
+
+// Per nonzero: its document (the last d with colptr[d] <= i), validity, number of tasks.
+// ntask has nnz + 1 entries; the last one is set to 0 so that an exclusive sum over all of them
+// ends with the total.
+__global__ __launch_bounds__(256) void wl_scan_nonzeros(const int32_t* __restrict__ colptr,
+                                                        const int32_t* __restrict__ rowidx,
+                                                        const float* __restrict__ val, int32_t D, int64_t nnz,
+                                                        int32_t V, uint32_t G, int32_t* __restrict__ nz_doc,
+                                                        uint32_t* __restrict__ ntask, BuildStats* s)
+{
+    __shared__ unsigned long long sh_tok[256], sh_task[256];
+    __shared__ uint32_t sh_max[256];
+    unsigned long long tok = 0ull, tasks = 0ull;
+    uint32_t gmax = 0u;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i <= nnz; i += stride) {
+        if (i == nnz) { ntask[i] = 0u; break; }
+        int32_t lo = 0, hi = D;                                    // colptr[lo] <= i < colptr[hi] when sound
+        while (hi - lo > 1) { const int32_t mid = lo + (hi - lo) / 2; if ((int64_t)colptr[mid] <= i) lo = mid; else hi = mid; }
+        nz_doc[i] = lo;
+        const int32_t w = rowidx[i];
+        const float c = val[i];
+        uint32_t nt = 0u;
+        if (w < 0 || w >= V) {
+            atomicMin(&s->first_bad, ((unsigned long long)i << 2) | 2ull);
+        } else if (!(c >= 1.0f) || c >= 16777216.0f || c != floorf(c)) {
+            atomicMin(&s->first_bad, ((unsigned long long)i << 2) | 3ull);
+        } else {
+            const uint32_t ci = (uint32_t)c;
+            nt = (ci + G - 1u) / G;
+            tok += ci; tasks += nt;
+            gmax = max(gmax, ci < G ? ci : G);
+        }
+        ntask[i] = nt;
+    }
+    sh_tok[threadIdx.x] = tok; sh_task[threadIdx.x] = tasks; sh_max[threadIdx.x] = gmax;
+    __syncthreads();
+    for (int off = 128; off > 0; off >>= 1) {
+        if ((int)threadIdx.x < off) {
+            sh_tok[threadIdx.x] += sh_tok[threadIdx.x + off];
+            sh_task[threadIdx.x] += sh_task[threadIdx.x + off];
+            sh_max[threadIdx.x] = max(sh_max[threadIdx.x], sh_max[threadIdx.x + off]);
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        if (sh_tok[0]) atomicAdd(&s->tokens, sh_tok[0]);
+        if (sh_task[0]) atomicAdd(&s->n_tasks, sh_task[0]);
+        if (sh_max[0]) atomicMax(&s->max_group, sh_max[0]);
+    }
+}
+
+// The tasks of every nonzero, consecutive from tbase[i]; the processing order starts as storage order.
+__global__ void wl_expand(const int32_t* __restrict__ nz_doc, const int32_t* __restrict__ rowidx,
+                          const float* __restrict__ val, const uint32_t* __restrict__ tbase, int64_t nnz, uint32_t G,
+                          int32_t* __restrict__ t_doc, int32_t* __restrict__ t_word, uint32_t* __restrict__ t_g,
+                          int32_t* __restrict__ order, uint32_t* __restrict__ cost)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < nnz; i += stride) {
+        const uint32_t t0 = tbase[i], t1 = tbase[i + 1];
+        const int32_t d = nz_doc[i], w = rowidx[i];
+        uint32_t left = (uint32_t)val[i];
+        for (uint32_t t = t0; t < t1; ++t) {
+            const uint32_t g = left < G ? left : G;
+            t_doc[t] = d; t_word[t] = w; t_g[t] = g;
+            order[t] = (int32_t)t; cost[t] = 0u;
+            left -= g;
+        }
+    }
+}
+
+// tile_start[T] = first task of document tile T (tile_docs documents per tile), n_tiles + 1 entries.
+__global__ void wl_tiles(const int32_t* __restrict__ colptr, const uint32_t* __restrict__ tbase, int32_t D,
+                         int32_t tile_docs, int32_t n_tiles, int32_t* __restrict__ tile_start)
+{
+    const int32_t T = (int32_t)(blockIdx.x * blockDim.x + threadIdx.x);
+    if (T > n_tiles) return;
+    const int64_t d = (int64_t)T * tile_docs;
+    tile_start[T] = (int32_t)tbase[colptr[d < D ? d : D]];
+}
+
+__global__ void wl_iota(int32_t* __restrict__ a, int64_t n)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) a[i] = (int32_t)i;
+}
+
+// wstart[w] = first position of word w in the word-sorted task list (n for words beyond the last), V + 1 entries.
+__global__ void wl_word_starts(const int32_t* __restrict__ keys, int32_t n, int32_t V, int32_t* __restrict__ wstart)
+{
+    const int32_t w = (int32_t)(blockIdx.x * blockDim.x + threadIdx.x);
+    if (w > V) return;
+    int32_t lo = 0, hi = n;                                        // first position with keys[pos] >= w
+    while (lo < hi) { const int32_t mid = lo + (hi - lo) / 2; if (keys[mid] < w) lo = mid + 1; else hi = mid; }
+    wstart[w] = lo;
+}
+
+// flag[i] = 1 if the word at sorted position i has at least min_tasks tasks (its tasks get slots).
+__global__ void wl_slot_flags(const int32_t* __restrict__ keys, const int32_t* __restrict__ wstart, int64_t n,
+                              int32_t min_tasks, uint32_t* __restrict__ flag)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i <= n; i += stride) {
+        if (i == n) { flag[i] = 0u; break; }
+        const int32_t w = keys[i];
+        flag[i] = (wstart[w + 1] - wstart[w] >= min_tasks) ? 1u : 0u;
+    }
+}
+
+// Slots in (word, task id) order: pos is the exclusive sum of flag (n + 1 entries, the last = number of slots).
+__global__ void wl_slot_scatter(const int32_t* __restrict__ keys, const int32_t* __restrict__ tasks,
+                                const uint32_t* __restrict__ flag, const uint32_t* __restrict__ pos, int64_t n,
+                                int32_t* __restrict__ t_slot, int32_t* __restrict__ slot_word, BuildStats* s)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+        if (flag[i]) { t_slot[tasks[i]] = (int32_t)pos[i]; slot_word[pos[i]] = keys[i]; }
+        else t_slot[tasks[i]] = -1;
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0) s->n_slots = pos[n];
+}
+
+// Library primitives (worklist.hip): temporary storage is taken from the caller's arena.
+size_t wl_exclusive_sum_bytes(size_t n);
+hipError_t wl_exclusive_sum(void* tmp, size_t tmp_bytes, const uint32_t* in, uint32_t* out, size_t n, hipStream_t st);
+size_t wl_sort_pairs_bytes(size_t n, int end_bit);
+hipError_t wl_sort_pairs(void* tmp, size_t tmp_bytes, const int32_t* keys_in, int32_t* keys_out,
+                         const int32_t* vals_in, int32_t* vals_out, size_t n, int end_bit, hipStream_t st);
+
+}  // namespace same
