@@ -112,6 +112,23 @@ void same_lda_free(same_lda_t* h);
  * m_init copies per token.  Reallocates per-document state; synchronises.                      */
 int same_lda_set_batch(same_lda_t* h, const same_lda_csc* X, int32_t m_init);
 
+/* The same in two steps, for streams of minibatches (Section 5.2: the data as a stream of
+ * minibatches; one sweep per minibatch): same_lda_stage_batch copies the next minibatch, builds
+ * its work list and draws the initial pass of its documents on a second stream of the library,
+ * while sweeps already enqueued on the handle's stream keep running; same_lda_commit_batch then
+ * makes it the resident matrix.  Call order for overlap: same_lda_sweep (asynchronous), then
+ * same_lda_stage_batch for the next minibatch, then same_lda_commit_batch.
+ *   sweeps_ahead  number of same_lda_sweep / _sweep_poisson calls that will still be made before the
+ *                 commit (0 in the order above).  The initial pass takes the pass index it would
+ *                 have had in same_lda_set_batch at that point; if the count turns out different,
+ *                 the commit draws the initial pass again, so results never depend on it.
+ * A device matrix must be complete when stage_batch is called (it is read on another stream than the
+ * handle's); a host matrix should be in pinned memory for the copy to overlap.  stage_batch returns when the
+ * staged minibatch is complete (it waits for the device once, to release temporaries); a second
+ * stage_batch replaces a staged minibatch that was not committed.                               */
+int same_lda_stage_batch(same_lda_t* h, const same_lda_csc* X, int32_t m_init, int32_t sweeps_ahead);
+int same_lda_commit_batch(same_lda_t* h);
+
 /* Copy a state matrix out of / into the handle.  bytes must equal the matrix size.
  * same_lda_set accepts SAME_LDA_THETA and SAME_LDA_PHI only.  Both synchronise.                */
 int same_lda_get(same_lda_t* h, int32_t which, void* dst, size_t bytes, int32_t dst_on_device);

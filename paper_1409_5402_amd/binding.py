@@ -19,7 +19,7 @@ THETA, PHI, NDK, NWK, NK = 0, 1, 2, 3, 4
 _DTYPES = {THETA: np.float32, PHI: np.float32, NDK: np.uint32, NWK: np.uint32, NK: np.uint64}
 
 EXPORTS = ["same_lda_init", "same_lda_sweep", "same_lda_sweep_poisson", "same_lda_loglik", "same_lda_free",
-           "same_lda_set_batch", "same_lda_debug_draw_poisson",
+           "same_lda_set_batch", "same_lda_stage_batch", "same_lda_commit_batch", "same_lda_debug_draw_poisson",
            "same_lda_get", "same_lda_set", "same_lda_get_pass", "same_lda_set_pass", "same_lda_task_count",
            "same_lda_debug_draw", "same_lda_set_timing", "same_lda_get_timing", "same_lda_selftest",
            "same_lda_synchronize",
@@ -56,6 +56,8 @@ def load() -> ctypes.CDLL:
         L.same_lda_free.argtypes = [c_void_p]
         L.same_lda_free.restype = None
         L.same_lda_set_batch.argtypes = [c_void_p, POINTER(_Csc), c_int32]
+        L.same_lda_stage_batch.argtypes = [c_void_p, POINTER(_Csc), c_int32, c_int32]
+        L.same_lda_commit_batch.argtypes = [c_void_p]
         L.same_lda_get.argtypes = [c_void_p, c_int32, c_void_p, c_size_t, c_int32]
         L.same_lda_set.argtypes = [c_void_p, c_int32, c_void_p, c_size_t, c_int32]
         L.same_lda_get_pass.argtypes = [c_void_p, POINTER(c_int32)]
@@ -150,6 +152,16 @@ class SameLDA:
         self._check(self._lib.same_lda_set_batch(self._h, byref(c), int(m_init)))
         self.D = int(D)
         del keep
+
+    def stage_batch(self, D, colptr, rowidx, val, m_init, sweeps_ahead=0):
+        c, keep = _csc(D, self.V, colptr, rowidx, val)
+        self._check(self._lib.same_lda_stage_batch(self._h, byref(c), int(m_init), int(sweeps_ahead)))
+        self._staged_D = int(D)
+        del keep
+
+    def commit_batch(self):
+        self._check(self._lib.same_lda_commit_batch(self._h))
+        self.D = self._staged_D
 
     def loglik(self, D, colptr, rowidx, val, foldin_sweeps, m_eval) -> float:
         c, keep = _csc(D, self.V, colptr, rowidx, val)

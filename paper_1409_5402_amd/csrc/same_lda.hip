@@ -56,6 +56,12 @@ struct same_lda {
     int32_t pass = 0;              // next pass index of the training stream
     hipStream_t stream = nullptr;
     Matrix X;
+    // the next minibatch, prepared on a second stream while the current one is swept
+    Matrix staged;
+    bool has_staged = false;
+    int32_t staged_pass = 0;       // pass index its initial pass was drawn with
+    int32_t staged_m = 0;
+    hipStream_t copy_stream = nullptr;
     float* phi = nullptr;          // [V][K]
     uint32_t* nwk = nullptr;       // [V][K]
     unsigned long long* nk = nullptr;  // [K]
@@ -363,9 +369,9 @@ int update_phi(same_lda* h, float m, float rho, hipStream_t st)
 }
 
 // One pass of draws on M.  uniform: weights are all ones (initialisation).
-int run_pass(same_lda* h, Matrix& M, Copies c, uint32_t pword, bool uniform, bool with_words, bool timed)
+int run_pass(same_lda* h, Matrix& M, Copies c, uint32_t pword, bool uniform, bool with_words, bool timed,
+             hipStream_t st)
 {
-    hipStream_t st = h->stream;
     int rc;
     if ((rc = zero_u32(h, M.ndk, (size_t)M.D * h->K, st))) return rc;
     if (with_words && (rc = zero_u32(h, h->nwk, (size_t)h->V * h->K, st))) return rc;
@@ -449,7 +455,7 @@ int same_lda_init(same_lda_t** out, const same_lda_csc* X, int32_t K, float alph
     if (!rc) rc = dev_alloc(h, &h->phi, (size_t)h->V * K);
     if (!rc) rc = dev_alloc(h, &h->nwk, (size_t)h->V * K);
     if (!rc) rc = dev_alloc(h, &h->nk, (size_t)K);
-    if (!rc) rc = run_pass(h, h->X, Copies::whole((uint32_t)m0), pass_word(0, 0), true, true, false);
+    if (!rc) rc = run_pass(h, h->X, Copies::whole((uint32_t)m0), pass_word(0, 0), true, true, false, h->stream);
     if (!rc) rc = update_theta(h, h->X, (float)m0, h->stream);
     if (!rc) rc = update_phi(h, (float)m0, 1.0f, h->stream);
     if (!rc) { hipError_t e = hipStreamSynchronize(h->stream); if (e != hipSuccess) rc = fail(h, SAME_LDA_EHIP, "init: %s", hipGetErrorString(e)); }
@@ -464,7 +470,7 @@ int same_lda_sweep(same_lda_t* h, int32_t m_t, float rho_t)
     if (!h) return SAME_LDA_EINVAL;
     if (!(rho_t > 0.f) || rho_t > 1.f) return fail(h, SAME_LDA_EINVAL, "rho must be in (0, 1] (got %g)", (double)rho_t);
     int rc = check_m(h, m_t, h->X);
-    if (!rc) rc = run_pass(h, h->X, Copies::whole((uint32_t)m_t), pass_word(h->pass, 0), false, true, h->timing);
+    if (!rc) rc = run_pass(h, h->X, Copies::whole((uint32_t)m_t), pass_word(h->pass, 0), false, true, h->timing, h->stream);
     if (!rc) rc = update_theta(h, h->X, (float)m_t, h->stream);
     if (!rc) rc = update_phi(h, (float)m_t, rho_t, h->stream);
     if (!rc) h->pass += 1;
@@ -476,9 +482,46 @@ int same_lda_sweep_poisson(same_lda_t* h, float m_t, float rho_t)
     if (!h) return SAME_LDA_EINVAL;
     if (!(rho_t > 0.f) || rho_t > 1.f) return fail(h, SAME_LDA_EINVAL, "rho must be in (0, 1] (got %g)", (double)rho_t);
     int rc = check_mf(h, m_t, h->X);
-    if (!rc) rc = run_pass(h, h->X, Copies::real(m_t), pass_word(h->pass, 0), false, true, h->timing);
+    if (!rc) rc = run_pass(h, h->X, Copies::real(m_t), pass_word(h->pass, 0), false, true, h->timing, h->stream);
     if (!rc) rc = update_theta(h, h->X, m_t, h->stream);
     if (!rc) rc = update_phi(h, m_t, rho_t, h->stream);
+    if (!rc) h->pass += 1;
+    return rc;
+}
+
+int same_lda_stage_batch(same_lda_t* h, const same_lda_csc* X, int32_t m_init, int32_t sweeps_ahead)
+{
+    if (!h) return SAME_LDA_EINVAL;
+    if (sweeps_ahead < 0) return fail(h, SAME_LDA_EINVAL, "sweeps_ahead must be >= 0");
+    if (!h->copy_stream) HIP_TRY(h, hipStreamCreateWithFlags(&h->copy_stream, hipStreamNonBlocking));
+    if (h->has_staged) { free_matrix(h->staged); h->has_staged = false; }
+    Matrix M;
+    int rc = build_matrix(h, X, h->V, h->K, h->G, M, h->copy_stream, true);
+    if (!rc) rc = check_m(h, m_init, M);
+    // the initial pass of the new documents needs neither phi nor the word counts: it can run now
+    const int32_t pass = h->pass + sweeps_ahead;
+    if (!rc) rc = run_pass(h, M, Copies::whole((uint32_t)m_init), pass_word(pass, 0), true, false, false, h->copy_stream);
+    if (!rc) rc = update_theta(h, M, (float)m_init, h->copy_stream);
+    if (!rc) { hipError_t e = hipStreamSynchronize(h->copy_stream); if (e != hipSuccess) rc = fail(h, SAME_LDA_EHIP, "stage_batch: %s", hipGetErrorString(e)); }
+    if (rc) { free_matrix(M); return rc; }
+    h->staged = M; h->has_staged = true; h->staged_pass = pass; h->staged_m = m_init;
+    return SAME_LDA_OK;
+}
+
+int same_lda_commit_batch(same_lda_t* h)
+{
+    if (!h) return SAME_LDA_EINVAL;
+    if (!h->has_staged) return fail(h, SAME_LDA_EINVAL, "no staged batch to commit");
+    HIP_TRY(h, hipStreamSynchronize(h->stream));           // the old matrix may still be in use
+    free_matrix(h->X);
+    h->X = h->staged;
+    h->staged = Matrix(); h->has_staged = false;
+    int rc = SAME_LDA_OK;
+    if (h->staged_pass != h->pass) {                       // not the announced number of sweeps: draw the initial pass again
+        rc = run_pass(h, h->X, Copies::whole((uint32_t)h->staged_m), pass_word(h->pass, 0), true, false, false, h->stream);
+        if (!rc) rc = update_theta(h, h->X, (float)h->staged_m, h->stream);
+        if (!rc) HIP_TRY(h, hipStreamSynchronize(h->stream));
+    }
     if (!rc) h->pass += 1;
     return rc;
 }
@@ -486,17 +529,9 @@ int same_lda_sweep_poisson(same_lda_t* h, float m_t, float rho_t)
 int same_lda_set_batch(same_lda_t* h, const same_lda_csc* X, int32_t m_init)
 {
     if (!h) return SAME_LDA_EINVAL;
-    HIP_TRY(h, hipStreamSynchronize(h->stream));
-    Matrix M;
-    int rc = build_matrix(h, X, h->V, h->K, h->G, M, h->stream, true);
-    if (!rc) rc = check_m(h, m_init, M);
-    if (rc) { free_matrix(M); return rc; }
-    free_matrix(h->X);
-    h->X = M;
-    rc = run_pass(h, h->X, Copies::whole((uint32_t)m_init), pass_word(h->pass, 0), true, false, false);
-    if (!rc) rc = update_theta(h, h->X, (float)m_init, h->stream);
-    if (!rc) HIP_TRY(h, hipStreamSynchronize(h->stream));
-    if (!rc) h->pass += 1;
+    HIP_TRY(h, hipStreamSynchronize(h->stream));           // a device matrix written on this stream is complete
+    int rc = same_lda_stage_batch(h, X, m_init, 0);
+    if (!rc) rc = same_lda_commit_batch(h);
     return rc;
 }
 
@@ -511,10 +546,10 @@ int same_lda_loglik(same_lda_t* h, const same_lda_csc* Xtest, int32_t foldin_swe
     const int nblocks = (int)((M.nnz + 255) / 256);
     if (!rc) rc = dev_alloc(h, &doc_log, (size_t)M.D);
     if (!rc) rc = dev_alloc(h, &part, (size_t)nblocks);
-    if (!rc) rc = run_pass(h, M, Copies::whole((uint32_t)m_eval), pass_word(0, 1), true, false, false);
+    if (!rc) rc = run_pass(h, M, Copies::whole((uint32_t)m_eval), pass_word(0, 1), true, false, false, h->stream);
     if (!rc) rc = update_theta(h, M, (float)m_eval, h->stream);
     for (int32_t s = 1; !rc && s <= foldin_sweeps; ++s) {
-        rc = run_pass(h, M, Copies::whole((uint32_t)m_eval), pass_word(s, 1), false, false, false);
+        rc = run_pass(h, M, Copies::whole((uint32_t)m_eval), pass_word(s, 1), false, false, false, h->stream);
         if (!rc) rc = update_theta(h, M, (float)m_eval, h->stream);
     }
     double total = 0.0;
@@ -544,6 +579,8 @@ void same_lda_free(same_lda_t* h)
     if (!h) return;
     hipStreamSynchronize(h->stream);
     free_matrix(h->X);
+    if (h->has_staged) free_matrix(h->staged);
+    if (h->copy_stream) { hipStreamSynchronize(h->copy_stream); hipStreamDestroy(h->copy_stream); }
     hipFree(h->phi); hipFree(h->nwk); hipFree(h->nk);
     for (auto& e : h->events) { hipEventDestroy(e.first); hipEventDestroy(e.second); }
     for (auto& e : h->pool) { hipEventDestroy(e.first); hipEventDestroy(e.second); }

@@ -292,6 +292,46 @@ def test_streamed_minibatches_abstract_shape():
     g.close()
 
 
+def test_staged_minibatches_overlap_order_and_wrong_announcement():
+    """The same stream of minibatches with the next minibatch staged (copy, work list, initial pass on the
+    library's second stream) while the current sweep is still running, from pinned host memory and from device
+    memory; once with a wrong sweeps_ahead (the commit then redraws the initial pass) and once replacing a
+    staged minibatch that is never committed.  Results must equal the set_batch sequence of the oracle."""
+    c = synth.generate(D=1200, V=30_000, K=32, alpha=0.1, beta=0.01, seed=14, length="poisson", mean_len=80.0, zipf_s=1.05)
+    X = corpus_to_csc(c)
+    batches = [X.slice_docs(300 * i, 300 * (i + 1)) for i in range(4)]
+    ms = [2, 5, 20, 50]
+    K = 32
+    o = oracle.OracleLDA(batches[0], K, 0.1, 0.01, seed=19, m0=ms[0], G=16)
+    g = make_gpu(batches[0], K, 0.1, 0.01, 19, ms[0], 16)
+    dev = torch.device("cuda:0")
+
+    def arrays(B, where):
+        a = [torch.from_numpy(B.colptr), torch.from_numpy(B.rowidx), torch.from_numpy(B.val)]
+        return [t.pin_memory() for t in a] if where == "pinned" else [t.to(dev) for t in a]
+
+    for t, m in enumerate(ms):
+        rho = float(np.float32(schedule.rho(t)))
+        o.sweep(m, rho)
+        g.sweep(m, rho)                                  # asynchronous: still running while the next batch is staged
+        if t + 1 < len(ms):
+            B = batches[t + 1]
+            o.set_batch(B, ms[t + 1])
+            if t == 1:                                   # a staged minibatch that is replaced before any commit
+                g.stage_batch(batches[0].D, *arrays(batches[0], "device"), 3, 0)
+            keep = arrays(B, "pinned" if t % 2 == 0 else "device")
+            torch.cuda.synchronize()
+            g.stage_batch(B.D, *keep, ms[t + 1], 1 if t == 2 else 0)     # t == 2 announces a sweep that never comes
+            g.commit_batch()
+            assert g.D == B.D
+            np.testing.assert_allclose(g.get(binding.THETA), o.theta, rtol=RTOL, err_msg=f"theta after commit {t + 1}")
+    assert_state_equal(g, o, "after the last minibatch")
+    assert g.pass_index == o.t
+    with pytest.raises(binding.SameLdaError):
+        g.commit_batch()                                 # nothing staged
+    g.close()
+
+
 # --------------------------------------------------------------------------- #
 # Poisson form of the factored draw (Section 4, second part; Algorithm 3's sampling line)
 @pytest.mark.parametrize("K,G,ms", [(16, 8, [10.0, 0.5, 3.25]), (24, 1, [1.0, 30.0]), (40, 3, [100.0, 2.5]),
