@@ -140,7 +140,7 @@ def main():
                          "the last 40 with the workload's m; the timed sweeps then complete a 50-sweep run at m")
     ap.add_argument("--workload", default="news")
     ap.add_argument("--scale", type=float, default=1.0, help="fraction of the workload's documents (1.0 = full size)")
-    ap.add_argument("--tokens-per-draw", type=int, default=32)
+    ap.add_argument("--tokens-per-draw", type=int, default=None, help="default: binding.DEFAULT_TOKENS_PER_DRAW")
     ap.add_argument("--form", choices=["multinomial", "poisson"], default="multinomial",
                     help="form of the factored draw: the exact-total multinomial (the headline path) or the "
                          "independent Poisson counts of Algorithm 3 as printed")
@@ -156,6 +156,9 @@ def main():
 
     import torch
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if args.tokens_per_draw is None:
+        from paper_1409_5402_amd.binding import DEFAULT_TOKENS_PER_DRAW
+        args.tokens_per_draw = DEFAULT_TOKENS_PER_DRAW
     if args.mode == "stream":
         if args.warmup == 140:
             args.warmup, args.steps = 20, max(args.steps, 40)

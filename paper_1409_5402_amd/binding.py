@@ -16,6 +16,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libsame_lda.so")
 
 THETA, PHI, NDK, NWK, NK = 0, 1, 2, 3, 4
+# Tokens of a nonzero drawn as one multinomial (one task).  Large groups measure fastest (fewer tasks,
+# and a nonzero's copies share one scan); m * min(count, this) must stay below 2^24.
+DEFAULT_TOKENS_PER_DRAW = 1024
 _DTYPES = {THETA: np.float32, PHI: np.float32, NDK: np.uint32, NWK: np.uint32, NK: np.uint64}
 
 EXPORTS = ["same_lda_init", "same_lda_sweep", "same_lda_sweep_poisson", "same_lda_loglik", "same_lda_free",
@@ -120,7 +123,7 @@ def selftest() -> int:
 class SameLDA:
     """A SAME Gibbs LDA model resident on the current GPU (one handle of the C library)."""
 
-    def __init__(self, D, V, colptr, rowidx, val, K, alpha, beta, seed, m0, tokens_per_draw=32, stream=None):
+    def __init__(self, D, V, colptr, rowidx, val, K, alpha, beta, seed, m0, tokens_per_draw=DEFAULT_TOKENS_PER_DRAW, stream=None):
         self._lib = load()
         self._h = c_void_p()
         self.V, self.K, self.D = int(V), int(K), int(D)

@@ -20,7 +20,7 @@ def test_device_selftest():
 def test_news_full_size_properties_and_sampled_parity():
     dev = torch.device("cuda:0")
     p = synth.PRESETS["news"]
-    K, m, alpha, beta, G = p["K"], p["m"], p["alpha"], p["beta"], 8
+    K, m, alpha, beta, G = p["K"], p["m"], p["alpha"], p["beta"], binding.DEFAULT_TOKENS_PER_DRAW
     corpus = synth.preset("news", device=dev)
     train = corpus.slice_docs(0, corpus.D - corpus.D // 10)
     theta_t, phi_t = synth.state(train, K, alpha, beta, seed=123, zipf_s=1.1)
@@ -42,6 +42,11 @@ def test_news_full_size_properties_and_sampled_parity():
     ref = oracle.draw_tasks(X, K, G, m, 5, pword, theta, phi, ids)
     assert np.array_equal(got, ref)
 
+    # the same sampled tasks in the Poisson form (a non-integer m)
+    got_p = g.debug_draw_poisson(37.5, ids[::4])
+    ref_p = oracle.draw_tasks_poisson(X, K, G, 37.5, 5, pword, theta, phi, ids[::4])
+    assert np.array_equal(got_p, ref_p)
+
     g.sweep(m)                                        # the full-size launch that bench.py times
     ndk, nwk, nk = g.get(binding.NDK), g.get(binding.NWK), g.get(binding.NK)
     # properties at full size: every document and every word keeps m times its tokens
@@ -62,4 +67,19 @@ def test_news_full_size_properties_and_sampled_parity():
     ph = g.get(binding.PHI)
     wrows = rng.choice(X.V, 200, replace=False)
     np.testing.assert_allclose(ph[wrows], (nwk[wrows] / m + beta) / (nk.astype(np.float64) / m + X.V * beta), rtol=1e-5)
+
+    # one full-size sweep in the Poisson form: both count matrices hold the same copies, document totals are
+    # Poisson around m * tokens (checked in units of their standard deviation), sampled documents match the oracle
+    theta2, phi2 = g.get(binding.THETA), g.get(binding.PHI)
+    pword2 = oracle.pass_word(g.pass_index)
+    g.sweep_poisson(float(m))
+    ndk, nwk, nk = g.get(binding.NDK), g.get(binding.NWK), g.get(binding.NK)
+    assert ndk.sum(dtype=np.int64) == nwk.sum(dtype=np.int64) == int(nk.sum())
+    tot = ndk.sum(axis=1, dtype=np.int64).astype(np.float64)
+    z = (tot - m * doc_tokens) / np.sqrt(np.maximum(m * doc_tokens, 1.0))
+    assert np.abs(z).max() < 6.5 and abs(z.mean()) < 0.02 and abs(z.std() - 1.0) < 0.02
+    for d in [0, 777, X.D - 1]:
+        t0, t1 = int(base[X.colptr[d]]), int(base[X.colptr[d + 1]])
+        vec = oracle.draw_tasks_poisson(X, K, G, float(m), 5, pword2, theta2, phi2, np.arange(t0, t1))
+        assert np.array_equal(vec.sum(axis=0, dtype=np.int64), ndk[d].astype(np.int64)), d
     g.close()
