@@ -131,6 +131,52 @@ def stream_bench(args):
     print(json.dumps(out))
 
 
+def sddmm_bench(args):
+    """The normaliser of Algorithm 3 alone (SDDMM, Section 5.3) over the news-shaped matrix at full size."""
+    import torch
+    from paper_1409_5402_amd import binding, synth
+
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    p = synth.PRESETS[args.workload]
+    K = p["K"]
+    corpus = synth.preset(args.workload, device=dev, scale=args.scale)
+    n_train = corpus.D - corpus.D // 10 if corpus.D >= 10 else corpus.D
+    train = corpus.slice_docs(0, n_train)
+    st = train.stats()
+    g = binding.SameLDA(train.D, train.V, train.colptr, train.rowidx, train.val, K, p["alpha"], p["beta"],
+                        seed=2, m0=1, tokens_per_draw=args.tokens_per_draw)
+    for _ in range(5):
+        g.sweep(1)                                       # a non-trivial theta / phi
+    mu = torch.empty(train.nnz, dtype=torch.float32, device=dev)
+    warm = min(args.warmup, 10)
+    for _ in range(warm):
+        g.sddmm(mu)
+    g.synchronize()
+    g.set_timing(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        g.sddmm(mu)
+    g.synchronize()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    kernel_ms, launches = g.get_timing()
+    g.close()
+    bytes_per_launch = float(st["nnz"]) * (12 + 4 * K) + float(st["D"]) * 4 * K   # ids, phi row, mu; theta rows once
+    achieved = bytes_per_launch / (kernel_ms / launches * 1e-3) / 1e9
+    print(json.dumps({
+        "metric": "nonzeros/sec of the stand-alone SDDMM normaliser (K=256) + achieved HBM GB/s vs 8 TB/s",
+        "value": st["nnz"] / (dt / args.steps), "unit": "nonzeros/s", "n_gpus": 1, "steps": args.steps, "warmup": warm,
+        "ms_per_step": 1e3 * dt / args.steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{args.workload} (LDA-generated, scale {args.scale})", "D": st["D"], "V": st["V"], "K": K,
+                   "nnz": st["nnz"]},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel": "sddmm_kernel",
+                     "kernel_ms": kernel_ms / launches, "bytes_per_launch": bytes_per_launch}}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -144,9 +190,9 @@ def main():
     ap.add_argument("--form", choices=["multinomial", "poisson"], default="multinomial",
                     help="form of the factored draw: the exact-total multinomial (the headline path) or the "
                          "independent Poisson counts of Algorithm 3 as printed")
-    ap.add_argument("--mode", choices=["resident", "stream"], default="resident",
+    ap.add_argument("--mode", choices=["resident", "stream", "sddmm"], default="resident",
                     help="resident: sweeps over one matrix held in HBM (the headline); stream: one sweep per "
-                         "minibatch of a stream of host-resident minibatches")
+                         "minibatch of a stream of host-resident minibatches; sddmm: the normaliser alone")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-loglik", action="store_true")
     args = ap.parse_args()
@@ -163,6 +209,8 @@ def main():
         if args.warmup == 140:
             args.warmup, args.steps = 20, max(args.steps, 40)
         return stream_bench(args)
+    if args.mode == "sddmm":
+        return sddmm_bench(args)
     import oracle
     from paper_1409_5402_amd import binding, synth
 

@@ -153,6 +153,16 @@ int same_lda_debug_draw(same_lda_t* h, int32_t m_t, const int64_t* task_ids, int
 int same_lda_debug_draw_poisson(same_lda_t* h, float m_t, const int64_t* task_ids, int32_t n,
                                 uint32_t* counts_out);
 
+/* The normaliser of Algorithm 3 as an operation of its own (Section 5.3, SDDMM: a product of two
+ * dense matrices evaluated at the nonzeros of a sparse one): mu[i] = sum_k theta[d][k] * phi[w][k]
+ * for every nonzero i = (d, w) of the resident matrix, in its storage order, from the current
+ * theta and phi.  Accumulated in binary32 in a fixed tree order (not the running sum of the draw:
+ * the two agree to rounding).  State is not changed.
+ *   mu_out         [nnz] float, device (asynchronous) or host (synchronises)
+ *   out_on_device  1 if mu_out is a device pointer
+ * When kernel timing is enabled the launch is recorded like a draw launch.                       */
+int same_lda_sddmm(same_lda_t* h, float* mu_out, int32_t out_on_device);
+
 /* Kernel timing.  When enabled, HIP events bracket the draw-and-scatter kernel of every sweep on
  * the handle's stream.  same_lda_get_timing synchronises, returns the summed duration (ms) and
  * the number of launches since the last call, and resets both.                                  */

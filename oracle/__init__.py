@@ -85,6 +85,8 @@ def lib() -> ctypes.CDLL:
         L.oracle_theta_update_real.restype = None
         L.oracle_phi_update_real.argtypes = [c_int32, c_int32, u32p, c_float, c_float, c_float, f32p]
         L.oracle_phi_update_real.restype = None
+        L.oracle_sddmm.argtypes = [c_int32, i32p, i32p, c_int32, f32p, f32p, ctypes.POINTER(c_double)]
+        L.oracle_sddmm.restype = None
         L.oracle_loglik_eval.argtypes = [c_int32, i32p, i32p, f32p, c_int32, f32p, f32p]
         L.oracle_loglik_eval.restype = c_double
         _lib = L
@@ -256,6 +258,16 @@ def phi_update_real(nwk, m: float, beta, rho, phi) -> np.ndarray:
     out = np.zeros((V, K), dtype=np.float32) if phi is None else np.ascontiguousarray(phi, dtype=np.float32).copy()
     lib().oracle_phi_update_real(V, K, _p(nwk, c_uint32), c_float(m), c_float(beta), c_float(rho), _p(out, c_float))
     return out
+
+
+def sddmm(X: CSC, theta, phi) -> np.ndarray:
+    """mu[i] = sum_k theta[d][k] * phi[w][k] for every nonzero (the normaliser of Algorithm 3), in double."""
+    theta = np.ascontiguousarray(theta, dtype=np.float32)
+    phi = np.ascontiguousarray(phi, dtype=np.float32)
+    mu = np.zeros(X.nnz, dtype=np.float64)
+    lib().oracle_sddmm(X.D, _p(X.colptr, c_int32), _p(X.rowidx, c_int32), theta.shape[1],
+                       _p(theta, c_float), _p(phi, c_float), _p(mu, c_double))
+    return mu
 
 
 def loglik_eval(X: CSC, theta, phi) -> float:

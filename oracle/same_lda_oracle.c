@@ -455,6 +455,24 @@ void oracle_draw_tasks_poisson(int32_t D, const int32_t* colptr, const int32_t* 
 }
 
 /* ------------------------------------------------------------------------- */
+/* The normaliser of Algorithm 3 as an operation of its own (Section 5.3: a sampled
+ * dense-dense matrix product): mu[i] = sum_k theta[d][k] * phi[w][k] for every
+ * nonzero i = (d, w) of the matrix, evaluated in double.                        */
+void oracle_sddmm(int32_t D, const int32_t* colptr, const int32_t* rowidx, int32_t K,
+                  const float* theta, const float* phi, double* mu)
+{
+    for (int32_t d = 0; d < D; ++d) {
+        for (int64_t i = colptr[d]; i < colptr[d + 1]; ++i) {
+            const float* t = theta + (size_t)d * K;
+            const float* p = phi + (size_t)rowidx[i] * K;
+            double acc = 0.0;
+            for (int32_t k = 0; k < K; ++k) acc += (double)t[k] * (double)p[k];
+            mu[i] = acc;
+        }
+    }
+}
+
+/* ------------------------------------------------------------------------- */
 /* Parameter update (Eq. 6 and Algorithm 3's last three steps).  Counts hold all
  * m copies, so they are divided by m; theta keeps its prior and stays
  * unnormalised (its per-document normaliser cancels in the draw); phi gets its

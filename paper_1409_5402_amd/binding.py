@@ -22,7 +22,7 @@ DEFAULT_TOKENS_PER_DRAW = 1024
 _DTYPES = {THETA: np.float32, PHI: np.float32, NDK: np.uint32, NWK: np.uint32, NK: np.uint64}
 
 EXPORTS = ["same_lda_init", "same_lda_sweep", "same_lda_sweep_poisson", "same_lda_loglik", "same_lda_free",
-           "same_lda_set_batch", "same_lda_stage_batch", "same_lda_commit_batch", "same_lda_debug_draw_poisson",
+           "same_lda_set_batch", "same_lda_stage_batch", "same_lda_commit_batch", "same_lda_debug_draw_poisson", "same_lda_sddmm",
            "same_lda_get", "same_lda_set", "same_lda_get_pass", "same_lda_set_pass", "same_lda_task_count",
            "same_lda_debug_draw", "same_lda_set_timing", "same_lda_get_timing", "same_lda_selftest",
            "same_lda_synchronize",
@@ -67,6 +67,7 @@ def load() -> ctypes.CDLL:
         L.same_lda_set_pass.argtypes = [c_void_p, c_int32]
         L.same_lda_task_count.argtypes = [c_void_p, POINTER(c_int64)]
         L.same_lda_debug_draw.argtypes = [c_void_p, c_int32, c_void_p, c_int32, c_void_p]
+        L.same_lda_sddmm.argtypes = [c_void_p, c_void_p, c_int32]
         L.same_lda_set_timing.argtypes = [c_void_p, c_int32]
         L.same_lda_get_timing.argtypes = [c_void_p, POINTER(c_double), POINTER(c_int64)]
         L.same_lda_selftest.argtypes = [POINTER(c_int64)]
@@ -127,6 +128,7 @@ class SameLDA:
         self._lib = load()
         self._h = c_void_p()
         self.V, self.K, self.D = int(V), int(K), int(D)
+        self.nnz = int(rowidx.shape[0])
         if stream is None:
             try:
                 import torch
@@ -153,18 +155,18 @@ class SameLDA:
     def set_batch(self, D, colptr, rowidx, val, m_init):
         c, keep = _csc(D, self.V, colptr, rowidx, val)
         self._check(self._lib.same_lda_set_batch(self._h, byref(c), int(m_init)))
-        self.D = int(D)
+        self.D, self.nnz = int(D), int(rowidx.shape[0])
         del keep
 
     def stage_batch(self, D, colptr, rowidx, val, m_init, sweeps_ahead=0):
         c, keep = _csc(D, self.V, colptr, rowidx, val)
         self._check(self._lib.same_lda_stage_batch(self._h, byref(c), int(m_init), int(sweeps_ahead)))
-        self._staged_D = int(D)
+        self._staged_D, self._staged_nnz = int(D), int(rowidx.shape[0])
         del keep
 
     def commit_batch(self):
         self._check(self._lib.same_lda_commit_batch(self._h))
-        self.D = self._staged_D
+        self.D, self.nnz = self._staged_D, self._staged_nnz
 
     def loglik(self, D, colptr, rowidx, val, foldin_sweeps, m_eval) -> float:
         c, keep = _csc(D, self.V, colptr, rowidx, val)
@@ -225,6 +227,16 @@ class SameLDA:
         self._check(self._lib.same_lda_debug_draw_poisson(self._h, float(m), ids.ctypes.data if ids.size else None,
                                                           ids.shape[0], out.ctypes.data if out.size else None))
         return out
+
+    def sddmm(self, out=None):
+        """mu of every nonzero of the resident matrix; ``out``: a float32 torch tensor on the device (filled
+        asynchronously) or None (a numpy array is returned)."""
+        if out is not None:
+            self._check(self._lib.same_lda_sddmm(self._h, out.data_ptr(), 1))
+            return out
+        mu = np.zeros(self.nnz, np.float32)
+        self._check(self._lib.same_lda_sddmm(self._h, mu.ctypes.data if mu.size else None, 0))
+        return mu
 
     def set_timing(self, enabled: bool):
         self._check(self._lib.same_lda_set_timing(self._h, 1 if enabled else 0))

@@ -676,6 +676,40 @@ int same_lda_debug_draw_poisson(same_lda_t* h, float m_t, const int64_t* task_id
     return debug_draw(h, Copies::real(m_t), task_ids, n, counts_out);
 }
 
+int same_lda_sddmm(same_lda_t* h, float* mu_out, int32_t out_on_device)
+{
+    if (!h) return SAME_LDA_EINVAL;
+    const Matrix& M = h->X;
+    if (M.nnz == 0) return SAME_LDA_OK;
+    if (!mu_out) return fail(h, SAME_LDA_EINVAL, "mu_out is null");
+    float* dst = mu_out;
+    if (!out_on_device) { int rc = dev_alloc(h, &dst, (size_t)M.nnz); if (rc) return rc; }
+    const int waves_per_block = 4;
+    const int64_t waves = (M.nnz + same::kSddmmChunk - 1) / same::kSddmmChunk;
+    const int64_t blocks = (waves + waves_per_block - 1) / waves_per_block;
+    std::pair<hipEvent_t, hipEvent_t> ev{nullptr, nullptr};
+    if (h->timing) {
+        if (!h->pool.empty()) { ev = h->pool.back(); h->pool.pop_back(); }
+        else { HIP_TRY(h, hipEventCreate(&ev.first)); HIP_TRY(h, hipEventCreate(&ev.second)); }
+        HIP_TRY(h, hipEventRecord(ev.first, h->stream));
+    }
+    if (h->K % 4 == 0)
+        hipLaunchKernelGGL(same::sddmm_kernel<true>, dim3((unsigned)blocks), dim3(64 * waves_per_block), 0, h->stream,
+                           M.nz_doc, M.rowidx, M.nnz, h->K, M.theta, h->phi, dst);
+    else
+        hipLaunchKernelGGL(same::sddmm_kernel<false>, dim3((unsigned)blocks), dim3(64 * waves_per_block), 0, h->stream,
+                           M.nz_doc, M.rowidx, M.nnz, h->K, M.theta, h->phi, dst);
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess && h->timing) { e = hipEventRecord(ev.second, h->stream); if (e == hipSuccess) h->events.push_back(ev); }
+    if (e == hipSuccess && !out_on_device) {
+        e = hipMemcpyAsync(mu_out, dst, (size_t)M.nnz * 4, hipMemcpyDeviceToHost, h->stream);
+        if (e == hipSuccess) e = hipStreamSynchronize(h->stream);
+    }
+    if (!out_on_device) hipFree(dst);
+    if (e != hipSuccess) return fail(h, SAME_LDA_EHIP, "sddmm: %s", hipGetErrorString(e));
+    return SAME_LDA_OK;
+}
+
 int same_lda_set_timing(same_lda_t* h, int32_t enabled)
 {
     if (!h) return SAME_LDA_EINVAL;

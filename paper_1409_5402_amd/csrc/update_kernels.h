@@ -155,4 +155,70 @@ __global__ __launch_bounds__(256) void loglik_kernel(int64_t nnz, const int32_t*
     if (threadIdx.x == 0) part[blockIdx.x] = red[0];
 }
 
+// The normaliser of Algorithm 3 as a kernel of its own (Section 5.3: SDDMM, the product of two dense
+// matrices evaluated at the nonzeros of a sparse one): mu[i] = sum_k theta[d][k] * phi[w][k].
+// One wave per nonzero at a time, lanes across topics: a lane multiplies four consecutive topics
+// (16-byte loads: the 64 lanes read a row's 1 KB in one instruction), the wave sums its 64 partial
+// results inside rows of 16 lanes by DPP moves, the four row sums by lane reads.  A wave owns
+// kSddmmChunk consecutive nonzeros (mostly one document: its theta row stays in cache) and keeps
+// the loads of four of them in flight.
+constexpr int kSddmmChunk = 32;
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float v)
+{
+    return v + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
+}
+
+__device__ __forceinline__ float wave_sum(float v)
+{
+    v = dpp_add<0xB1>(v);      // quad_perm [1,0,3,2]
+    v = dpp_add<0x4E>(v);      // quad_perm [2,3,0,1]
+    v = dpp_add<0x141>(v);     // row_half_mirror
+    v = dpp_add<0x140>(v);     // row_mirror: every lane of a row of 16 holds the row's sum
+    const int b = __float_as_int(v);
+    const float r0 = __int_as_float(__builtin_amdgcn_readlane(b, 0)), r1 = __int_as_float(__builtin_amdgcn_readlane(b, 16));
+    const float r2 = __int_as_float(__builtin_amdgcn_readlane(b, 32)), r3 = __int_as_float(__builtin_amdgcn_readlane(b, 48));
+    return (r0 + r1) + (r2 + r3);
+}
+
+template <bool VEC>   // VEC: K is a multiple of 4
+__global__ __launch_bounds__(256) void sddmm_kernel(const int32_t* __restrict__ nz_doc,
+                                                    const int32_t* __restrict__ rowidx, int64_t nnz, int K,
+                                                    const float* __restrict__ theta, const float* __restrict__ phi,
+                                                    float* __restrict__ mu)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t wave = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    const int64_t i0 = wave * kSddmmChunk;
+    const int64_t i1 = i0 + kSddmmChunk < nnz ? i0 + kSddmmChunk : nnz;
+    for (int64_t i = i0; i < i1; i += 4) {
+        float acc[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (i + j < i1) {                                      // uniform over the wave
+                const float* __restrict__ t = theta + (size_t)nz_doc[i + j] * K;
+                const float* __restrict__ p = phi + (size_t)rowidx[i + j] * K;
+                if (VEC) {
+                    for (int q = lane; q < (K >> 2); q += 64) {
+                        const float4 a = *reinterpret_cast<const float4*>(t + 4 * q);
+                        const float4 b = *reinterpret_cast<const float4*>(p + 4 * q);
+                        acc[j] = __builtin_fmaf(a.x, b.x, acc[j]);
+                        acc[j] = __builtin_fmaf(a.y, b.y, acc[j]);
+                        acc[j] = __builtin_fmaf(a.z, b.z, acc[j]);
+                        acc[j] = __builtin_fmaf(a.w, b.w, acc[j]);
+                    }
+                } else {
+                    for (int k = lane; k < K; k += 64) acc[j] = __builtin_fmaf(t[k], p[k], acc[j]);
+                }
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float total = wave_sum(acc[j]);
+            if (i + j < i1 && lane == 0) mu[i + j] = total;
+        }
+    }
+}
+
 }  // namespace same

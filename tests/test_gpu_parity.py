@@ -393,3 +393,31 @@ def test_poisson_rejects_bad_m():
     g.sweep_poisson(0.25)
     g.synchronize()
     g.close()
+
+
+# --------------------------------------------------------------------------- #
+# the normaliser as a stand-alone sampled dense-dense product (Section 5.3)
+@pytest.mark.parametrize("K", [1, 3, 16, 40, 256, 1024])
+def test_sddmm_against_double_oracle(K):
+    """mu of every nonzero from the current theta and phi: binary32 tree sum on the GPU against the oracle's
+    double sum; host and device output; K not a multiple of 4 takes the scalar path."""
+    X = toy(seed=15, D=90, V=70, density=0.25, cmax=5)
+    o = oracle.OracleLDA(X, K, 0.3, 0.02, seed=2, m0=4, G=8)
+    g = make_gpu(X, K, 0.3, 0.02, 2, 4, 8)
+    o.sweep(7); g.sweep(7)
+    want = oracle.sddmm(X, o.theta, o.phi)
+    got = g.sddmm()
+    np.testing.assert_allclose(got, want, rtol=1e-5, atol=0)
+    out = torch.empty(X.nnz, dtype=torch.float32, device="cuda:0")
+    g.sddmm(out)
+    g.synchronize()
+    assert np.array_equal(out.cpu().numpy(), got)
+    assert_state_equal(g, o, "state untouched by sddmm")
+    g.close()
+
+
+def test_sddmm_empty_matrix():
+    X = oracle.CSC(3, 10, np.zeros(4, np.int32), np.zeros(0, np.int32), np.zeros(0, np.float32))
+    g = make_gpu(X, 4, 0.1, 0.01, 1, 5, 8)
+    assert g.sddmm().shape == (0,)
+    g.close()

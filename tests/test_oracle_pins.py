@@ -501,3 +501,34 @@ def test_poisson_sweep_update_uses_real_m():
     np.testing.assert_allclose(o.phi[:, 0], (o.nwk[:, 0].astype(np.float32) / m + np.float32(0.1))
                                / (nk / m + np.float32(3) * np.float32(0.1)), rtol=1e-6)
     assert abs(o.phi[:, 0].sum() - 1.0) < 1e-5
+
+
+# --------------------------------------------------------------------------- #
+# the normaliser as a stand-alone sampled dense-dense product (Section 5.3)
+def test_sddmm_closed_forms_and_brute_force():
+    rng = np.random.default_rng(2)
+    counts = rng.integers(1, 4, size=(9, 7)) * (rng.uniform(size=(9, 7)) < 0.5)
+    counts[3, :] = 0
+    X = csc_from_dense(counts)
+    K = 5
+    theta = rng.uniform(0.1, 2.0, size=(X.D, K)).astype(np.float32)
+    phi = rng.uniform(0.01, 1.0, size=(X.V, K)).astype(np.float32)
+    mu = oracle.sddmm(X, theta, phi)
+    assert mu.shape == (X.nnz,)
+    i = 0
+    for d in range(X.D):                                  # element by element, plain loops, documents by theta rows
+        for w in np.nonzero(counts[d])[0]:
+            want = sum(float(theta[d, k]) * float(phi[w, k]) for k in range(K))
+            assert abs(mu[i] - want) <= 1e-12 * want
+            i += 1
+    assert i == X.nnz
+    # theta constant over topics and phi rows summing to one: mu is that constant
+    phi1 = (phi / phi.sum(axis=1, keepdims=True)).astype(np.float32)
+    mu1 = oracle.sddmm(X, np.full((X.D, K), 3.0, np.float32), phi1)
+    np.testing.assert_allclose(mu1, 3.0 * phi1.astype(np.float64).sum(axis=1)[X.rowidx], rtol=1e-12)
+    # K = 1: a plain product; and the value agrees with the normaliser the draw returns
+    mu_k1 = oracle.sddmm(X, theta[:, :1].copy(), phi[:, :1].copy())
+    doc = np.repeat(np.arange(X.D), np.diff(X.colptr))
+    np.testing.assert_allclose(mu_k1, theta[doc, 0].astype(np.float64) * phi[X.rowidx, 0].astype(np.float64), rtol=1e-15)
+    _, _, mu_draw = oracle.run_pass(X, K, 8, 1, 1, PW(1), theta, phi, want_mu=True)
+    np.testing.assert_allclose(mu_draw, mu, rtol=1e-6)
