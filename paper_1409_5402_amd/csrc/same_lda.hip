@@ -8,8 +8,10 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <map>
 #include <new>
 #include <string>
+#include <unordered_map>
 #include <vector>
 
 #include "update_kernels.h"
@@ -49,8 +51,53 @@ struct Matrix {
 
 }  // namespace
 
+// Device blocks handed back by the library's own buffers are kept for the next request of similar
+// size instead of being freed: a stream of minibatches then allocates nothing after its first steps
+// (hipFree waits for the whole device).  Blocks are only put back once no enqueued work uses them.
+struct BlockCache {
+    std::unordered_map<void*, size_t> live;      // blocks handed out, with their size
+    std::multimap<size_t, void*> spare;          // blocks waiting for reuse, by size
+    size_t spare_bytes = 0, limit = (size_t)1 << 30;
+
+    hipError_t get(void** p, size_t bytes)
+    {
+        bytes = (bytes + 255) & ~(size_t)255;
+        if (bytes == 0) bytes = 256;
+        auto it = spare.lower_bound(bytes);
+        if (it != spare.end() && it->first <= 2 * bytes + 4096) {
+            *p = it->second; live[*p] = it->first; spare_bytes -= it->first; spare.erase(it);
+            return hipSuccess;
+        }
+        hipError_t e = hipMalloc(p, bytes);
+        if (e != hipSuccess && !spare.empty()) {                   // give the spare blocks back and try again
+            (void)hipGetLastError();
+            clear_spare();
+            e = hipMalloc(p, bytes);
+        }
+        if (e == hipSuccess) live[*p] = bytes;
+        return e;
+    }
+    void put(void* p)
+    {
+        if (!p) return;
+        auto it = live.find(p);
+        if (it == live.end()) { hipFree(p); return; }
+        spare.emplace(it->second, p); spare_bytes += it->second; live.erase(it);
+        while (spare_bytes > limit && !spare.empty()) {            // drop the smallest blocks first
+            auto sm = spare.begin();
+            spare_bytes -= sm->first; hipFree(sm->second); spare.erase(sm);
+        }
+    }
+    void clear_spare()
+    {
+        for (auto& kv : spare) hipFree(kv.second);
+        spare.clear(); spare_bytes = 0;
+    }
+};
+
 struct same_lda {
     int32_t V = 0, K = 0, G = 0;
+    BlockCache cache;
     float alpha = 0.f, beta = 0.f;
     uint64_t seed = 0;
     int32_t pass = 0;              // next pass index of the training stream
@@ -97,33 +144,44 @@ int dev_alloc(same_lda* h, T** p, size_t n)
 {
     *p = nullptr;
     if (n == 0) return SAME_LDA_OK;
-    HIP_TRY(h, hipMalloc(reinterpret_cast<void**>(p), n * sizeof(T)));
+    HIP_TRY(h, h->cache.get(reinterpret_cast<void**>(p), n * sizeof(T)));
     return SAME_LDA_OK;
 }
 
-void free_matrix(Matrix& M)
+template <class T>
+void dev_free(same_lda* h, T*& p)
 {
-    hipFree(M.colptr); hipFree(M.t_doc); hipFree(M.t_word); hipFree(M.t_g); hipFree(M.order); hipFree(M.tile_start); hipFree(M.cost); hipFree(M.nz_doc);
-    hipFree(M.rowidx); hipFree(M.val); hipFree(M.theta); hipFree(M.ndk);
-    hipFree(M.pairs); hipFree(M.t_slot); hipFree(M.slot_word);
+    h->cache.put(p);
+    p = nullptr;
+}
+
+// Only after every launch that uses M has completed.
+void free_matrix(same_lda* h, Matrix& M)
+{
+    dev_free(h, M.colptr); dev_free(h, M.t_doc); dev_free(h, M.t_word); dev_free(h, M.t_g); dev_free(h, M.order);
+    dev_free(h, M.tile_start); dev_free(h, M.cost); dev_free(h, M.nz_doc); dev_free(h, M.rowidx); dev_free(h, M.val);
+    dev_free(h, M.theta); dev_free(h, M.ndk); dev_free(h, M.pairs); dev_free(h, M.t_slot); dev_free(h, M.slot_word);
     M = Matrix();
 }
 
 int grid_for(size_t n, int threads = 256, int cap = 256 * 32);
 
-// Device temporaries of one build, released together at the end (hipFree waits for the device,
-// so it is called once).
+// Device temporaries of one build, handed back together at the end (after the build's stream has
+// been waited for).
 struct Temps {
+    same_lda* h;
+    hipStream_t st;
     std::vector<void*> ptrs;
+    Temps(same_lda* handle, hipStream_t stream) : h(handle), st(stream) {}
     template <class T> hipError_t get(T** p, size_t n)
     {
         *p = nullptr;
         void* v = nullptr;
-        const hipError_t e = hipMalloc(&v, (n ? n : 1) * sizeof(T));
+        const hipError_t e = h->cache.get(&v, (n ? n : 1) * sizeof(T));
         if (e == hipSuccess) { ptrs.push_back(v); *p = static_cast<T*>(v); }
         return e;
     }
-    ~Temps() { for (void* v : ptrs) hipFree(v); }
+    ~Temps() { (void)hipStreamSynchronize(st); for (void* v : ptrs) h->cache.put(v); }
 };
 
 // Validates the matrix and builds its work list on the device (worklist_kernels.h).  The matrix may
@@ -163,7 +221,7 @@ int build_matrix(same_lda* h, const same_lda_csc* X, int32_t V, int32_t K, int32
         HIP_TRY(h, hipMemcpyAsync(M.val, X->val, (size_t)nnz * 4, kind, st));
     }
 
-    Temps tmp;
+    Temps tmp(h, st);
     same::BuildStats* d_stats = nullptr;
     uint32_t *ntask = nullptr, *tbase = nullptr;
     void* scan_tmp = nullptr;
@@ -230,8 +288,8 @@ int build_matrix(same_lda* h, const same_lda_csc* X, int32_t V, int32_t K, int32
                   tmp.get(&pos, n + 1) == hipSuccess &&
                   tmp.get(reinterpret_cast<char**>(&sort_tmp), sort_bytes) == hipSuccess &&
                   tmp.get(reinterpret_cast<char**>(&scan2_tmp), scan2_bytes) == hipSuccess &&
-                  hipMalloc(reinterpret_cast<void**>(&M.t_slot), n * 4) == hipSuccess &&
-                  hipMalloc(reinterpret_cast<void**>(&M.slot_word), n * 4) == hipSuccess;
+                  h->cache.get(reinterpret_cast<void**>(&M.t_slot), n * 4) == hipSuccess &&
+                  h->cache.get(reinterpret_cast<void**>(&M.slot_word), n * 4) == hipSuccess;
         if (ok) {
             hipLaunchKernelGGL(same::wl_iota, dim3(grid_for(n)), dim3(256), 0, st, iota, (int64_t)n);
             HIP_TRY(h, same::wl_sort_pairs(sort_tmp, sort_bytes, M.t_word, keys, iota, tasks, n, bits, st));
@@ -247,15 +305,18 @@ int build_matrix(same_lda* h, const same_lda_csc* X, int32_t V, int32_t K, int32
             HIP_TRY(h, hipStreamSynchronize(st));
             M.n_slots = (int64_t)stats.n_slots;
             ok = M.n_slots > 0 &&
-                 hipMalloc(reinterpret_cast<void**>(&M.pairs), (size_t)M.n_slots * same::kPairWords * sizeof(uint32_t)) == hipSuccess;
+                 h->cache.get(reinterpret_cast<void**>(&M.pairs), (size_t)M.n_slots * same::kPairWords * sizeof(uint32_t)) == hipSuccess;
         }
         if (!ok) {
             (void)hipGetLastError();
-            hipFree(M.pairs); hipFree(M.t_slot); hipFree(M.slot_word);
-            M.pairs = nullptr; M.t_slot = nullptr; M.slot_word = nullptr; M.n_slots = 0;
+            dev_free(h, M.pairs); dev_free(h, M.t_slot); dev_free(h, M.slot_word);
+            M.n_slots = 0;
         }
     }
-    HIP_TRY(h, hipStreamSynchronize(st));   // the temporaries are released on return
+    HIP_TRY(h, hipStreamSynchronize(st));   // the temporaries are handed back on return
+    // blocks worth keeping for the next matrix of this size: the matrix itself and the temporaries
+    const size_t matrix_bytes = (size_t)nnz * 12 + n * 28 + (size_t)M.n_slots * 68 + (size_t)D * K * 8;
+    if (h->cache.limit < 2 * matrix_bytes + ((size_t)1 << 30)) h->cache.limit = 2 * matrix_bytes + ((size_t)1 << 30);
     return SAME_LDA_OK;
 }
 
@@ -461,6 +522,7 @@ int same_lda_init(same_lda_t** out, const same_lda_csc* X, int32_t K, float alph
     if (!rc) { hipError_t e = hipStreamSynchronize(h->stream); if (e != hipSuccess) rc = fail(h, SAME_LDA_EHIP, "init: %s", hipGetErrorString(e)); }
     if (rc) { g_init_error = h->error; same_lda_free(h); return rc; }
     h->pass = 1;
+    h->cache.clear_spare();                                // the build's temporaries: a single resident matrix needs them no more
     *out = h;
     return SAME_LDA_OK;
 }
@@ -494,7 +556,7 @@ int same_lda_stage_batch(same_lda_t* h, const same_lda_csc* X, int32_t m_init, i
     if (!h) return SAME_LDA_EINVAL;
     if (sweeps_ahead < 0) return fail(h, SAME_LDA_EINVAL, "sweeps_ahead must be >= 0");
     if (!h->copy_stream) HIP_TRY(h, hipStreamCreateWithFlags(&h->copy_stream, hipStreamNonBlocking));
-    if (h->has_staged) { free_matrix(h->staged); h->has_staged = false; }
+    if (h->has_staged) { free_matrix(h, h->staged); h->has_staged = false; }
     Matrix M;
     int rc = build_matrix(h, X, h->V, h->K, h->G, M, h->copy_stream, true);
     if (!rc) rc = check_m(h, m_init, M);
@@ -503,7 +565,7 @@ int same_lda_stage_batch(same_lda_t* h, const same_lda_csc* X, int32_t m_init, i
     if (!rc) rc = run_pass(h, M, Copies::whole((uint32_t)m_init), pass_word(pass, 0), true, false, false, h->copy_stream);
     if (!rc) rc = update_theta(h, M, (float)m_init, h->copy_stream);
     if (!rc) { hipError_t e = hipStreamSynchronize(h->copy_stream); if (e != hipSuccess) rc = fail(h, SAME_LDA_EHIP, "stage_batch: %s", hipGetErrorString(e)); }
-    if (rc) { free_matrix(M); return rc; }
+    if (rc) { (void)hipStreamSynchronize(h->copy_stream); free_matrix(h, M); return rc; }
     h->staged = M; h->has_staged = true; h->staged_pass = pass; h->staged_m = m_init;
     return SAME_LDA_OK;
 }
@@ -513,7 +575,7 @@ int same_lda_commit_batch(same_lda_t* h)
     if (!h) return SAME_LDA_EINVAL;
     if (!h->has_staged) return fail(h, SAME_LDA_EINVAL, "no staged batch to commit");
     HIP_TRY(h, hipStreamSynchronize(h->stream));           // the old matrix may still be in use
-    free_matrix(h->X);
+    free_matrix(h, h->X);
     h->X = h->staged;
     h->staged = Matrix(); h->has_staged = false;
     int rc = SAME_LDA_OK;
@@ -569,8 +631,9 @@ int same_lda_loglik(same_lda_t* h, const same_lda_csc* Xtest, int32_t foldin_swe
         if (e != hipSuccess) rc = fail(h, SAME_LDA_EHIP, "loglik: %s", hipGetErrorString(e));
     }
     if (!rc) *ll_per_word = M.tokens > 0.0 ? total / M.tokens : 0.0;
-    hipFree(doc_log); hipFree(part);
-    free_matrix(M);
+    if (rc) (void)hipStreamSynchronize(h->stream);         // nothing enqueued may still use the blocks handed back
+    dev_free(h, doc_log); dev_free(h, part);
+    free_matrix(h, M);
     return rc;
 }
 
@@ -578,10 +641,11 @@ void same_lda_free(same_lda_t* h)
 {
     if (!h) return;
     hipStreamSynchronize(h->stream);
-    free_matrix(h->X);
-    if (h->has_staged) free_matrix(h->staged);
+    free_matrix(h, h->X);
+    if (h->has_staged) free_matrix(h, h->staged);
     if (h->copy_stream) { hipStreamSynchronize(h->copy_stream); hipStreamDestroy(h->copy_stream); }
-    hipFree(h->phi); hipFree(h->nwk); hipFree(h->nk);
+    dev_free(h, h->phi); dev_free(h, h->nwk); dev_free(h, h->nk);
+    h->cache.clear_spare();
     for (auto& e : h->events) { hipEventDestroy(e.first); hipEventDestroy(e.second); }
     for (auto& e : h->pool) { hipEventDestroy(e.first); hipEventDestroy(e.second); }
     delete h;
@@ -658,7 +722,8 @@ int debug_draw(same_lda_t* h, Copies c, const int64_t* task_ids, int32_t n, uint
         if (e == hipSuccess) e = hipStreamSynchronize(h->stream);
         if (e != hipSuccess) rc = fail(h, SAME_LDA_EHIP, "debug_draw: %s", hipGetErrorString(e));
     }
-    hipFree(ids_d); hipFree(out_d);
+    if (rc) (void)hipStreamSynchronize(h->stream);
+    dev_free(h, ids_d); dev_free(h, out_d);
     return rc;
 }
 }  // namespace
@@ -705,7 +770,7 @@ int same_lda_sddmm(same_lda_t* h, float* mu_out, int32_t out_on_device)
         e = hipMemcpyAsync(mu_out, dst, (size_t)M.nnz * 4, hipMemcpyDeviceToHost, h->stream);
         if (e == hipSuccess) e = hipStreamSynchronize(h->stream);
     }
-    if (!out_on_device) hipFree(dst);
+    if (!out_on_device) dev_free(h, dst);
     if (e != hipSuccess) return fail(h, SAME_LDA_EHIP, "sddmm: %s", hipGetErrorString(e));
     return SAME_LDA_OK;
 }
