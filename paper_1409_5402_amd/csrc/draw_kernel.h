@@ -47,6 +47,7 @@ constexpr int kWalkSteps = SAME_WALK_STEPS;   // pmf steps per trip of the chain
 #ifndef SAME_POOL_MIN
 #define SAME_POOL_MIN 8
 #endif
+constexpr float kPieceMean = 32.0f;     // a binomial whose mean exceeds this is cut into pieces of about this mean
 constexpr int kPoolMin = SAME_POOL_MIN;       // waiting multi-piece binomials that trigger a shared pass
 
 struct DrawArgs {
@@ -360,13 +361,13 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
                     r = qq / sc;
                     bR = R;
                     SAME_COUNT(a, 3, 1);                           // binomials set up
-                    if (((float)R * qq) <= 32.0f) {                // one piece of R trials
+                    if (((float)R * qq) <= kPieceMean) {                // one piece of R trials
                         L = R;
                         const float pm0 = ipow(sc, R);
                         xw = 0; pm = pm0; cdf = pm0; stalled = false;
                         st = 1;
                     } else {                                       // pieces of L trials: shared by the wave
-                        L = (uint32_t)(32.0f / qq);
+                        L = (uint32_t)(kPieceMean / qq);
                         st = 3;
                     }
                 }
@@ -455,7 +456,9 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
     while (__any(st != 0 || (cnt > 0 && R > 0))) trip();
     if (!POISSON && R > 0) emit(kstar, R);
     if (pslot && live) pslot[0] = npairs < (uint32_t)(kPairWords - 1) ? npairs : (uint32_t)(kPairWords - 1);
-    if (!DEBUG && live && a.cost) a.cost[tau] = busy;
+    // The ordering key for the next pass: a running mean (weight 1/4 on this pass) predicts a task's next
+    // cost a little better than this pass's cost alone.
+    if (!DEBUG && live && a.cost) a.cost[tau] = (3u * a.cost[tau] + busy + 2u) >> 2;
 }
 
 // Adds the recorded pairs to the word rows.  Slots are in word order and exist only for words with
