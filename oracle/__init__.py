@@ -20,6 +20,8 @@ _LIB = os.path.join(_HERE, "liboracle_same_lda.so")
 
 DOMAIN_TRAIN = 0
 DOMAIN_HELDOUT = 1
+DOMAIN_THETA = 2      # Gamma variables of the sampled theta step
+DOMAIN_PHI = 3        # Gamma variables of the sampled phi step
 
 
 def build(force: bool = False) -> str:
@@ -85,6 +87,18 @@ def lib() -> ctypes.CDLL:
         L.oracle_theta_update_real.restype = None
         L.oracle_phi_update_real.argtypes = [c_int32, c_int32, u32p, c_float, c_float, c_float, f32p]
         L.oracle_phi_update_real.restype = None
+        L.oracle_flog.argtypes = [c_float]
+        L.oracle_flog.restype = c_float
+        L.oracle_cos2pi.argtypes = [c_float]
+        L.oracle_cos2pi.restype = c_float
+        L.oracle_normal.argtypes = [c_float, c_float]
+        L.oracle_normal.restype = c_float
+        L.oracle_gamma.argtypes = [c_float, c_uint64, c_uint32, c_uint32, c_uint32]
+        L.oracle_gamma.restype = c_float
+        L.oracle_theta_sample.argtypes = [c_int32, c_int32, u32p, c_float, c_float, c_uint64, c_uint32, f32p]
+        L.oracle_theta_sample.restype = None
+        L.oracle_phi_sample.argtypes = [c_int32, c_int32, u32p, c_float, c_float, c_uint64, c_uint32, f32p]
+        L.oracle_phi_sample.restype = None
         L.oracle_sddmm.argtypes = [c_int32, i32p, i32p, c_int32, f32p, f32p, ctypes.POINTER(c_double)]
         L.oracle_sddmm.restype = None
         L.oracle_loglik_eval.argtypes = [c_int32, i32p, i32p, f32p, c_int32, f32p, f32p]
@@ -260,6 +274,39 @@ def phi_update_real(nwk, m: float, beta, rho, phi) -> np.ndarray:
     return out
 
 
+def flog(x: float) -> float:
+    return float(lib().oracle_flog(c_float(x)))
+
+
+def cos2pi(u: float) -> float:
+    return float(lib().oracle_cos2pi(c_float(u)))
+
+
+def normal(u1: float, u2: float) -> float:
+    return float(lib().oracle_normal(c_float(u1), c_float(u2)))
+
+
+def gamma(a: float, seed: int, row: int, k: int, pword: int) -> float:
+    """One Gamma(a, 1) variable of the sampled parameter step (element (row, k) of its stream)."""
+    return float(lib().oracle_gamma(c_float(a), seed, row, k, pword))
+
+
+def theta_sample(ndk, m: float, alpha, seed: int, pword: int) -> np.ndarray:
+    """theta_d ~ Dirichlet(n_dk + m*alpha), left unnormalised with mean n_dk/m + alpha."""
+    D, K = ndk.shape
+    theta = np.empty((D, K), dtype=np.float32)
+    lib().oracle_theta_sample(D, K, _p(ndk, c_uint32), c_float(m), c_float(alpha), seed, pword, _p(theta, c_float))
+    return theta
+
+
+def phi_sample(nwk, m: float, beta, seed: int, pword: int) -> np.ndarray:
+    """phi_k ~ Dirichlet over words (n_wk + m*beta), normalised over words."""
+    V, K = nwk.shape
+    phi = np.empty((V, K), dtype=np.float32)
+    lib().oracle_phi_sample(V, K, _p(nwk, c_uint32), c_float(m), c_float(beta), seed, pword, _p(phi, c_float))
+    return phi
+
+
 def sddmm(X: CSC, theta, phi) -> np.ndarray:
     """mu[i] = sum_k theta[d][k] * phi[w][k] for every nonzero (the normaliser of Algorithm 3), in double."""
     theta = np.ascontiguousarray(theta, dtype=np.float32)
@@ -299,6 +346,15 @@ class OracleLDA:
                                          self.theta, self.phi)
         self.theta = theta_update(self.ndk, m, self.alpha)
         self.phi = phi_update(self.nwk, m, self.beta, rho, self.phi)
+        self.t += 1
+
+    def sweep_sampled(self, m: int):
+        """One sweep whose parameter step draws theta and phi from their Dirichlet conditionals
+        (Algorithm 2, third step) instead of taking their means."""
+        self.ndk, self.nwk, _ = run_pass(self.X, self.K, self.G, m, self.seed, pass_word(self.t),
+                                         self.theta, self.phi)
+        self.theta = theta_sample(self.ndk, float(m), self.alpha, self.seed, pass_word(self.t, DOMAIN_THETA))
+        self.phi = phi_sample(self.nwk, float(m), self.beta, self.seed, pass_word(self.t, DOMAIN_PHI))
         self.t += 1
 
     def sweep_poisson(self, m: float, rho: float = 1.0):

@@ -521,6 +521,177 @@ void oracle_phi_update(int32_t V, int32_t K, const uint32_t* nwk, uint32_t m, fl
     oracle_phi_update_real(V, K, nwk, (float)m, beta, rho, phi);
 }
 
+/* ------------------------------------------------------------------------- */
+/* The sampled parameter step (Algorithm 2, third step; Section 3.1: the
+ * conditional of the parameters given the m copies is the product of the m
+ * single-copy conditionals, for LDA a Dirichlet again).  Taken here as
+ *   theta_d ~ Dirichlet(n_dk + m*alpha),   phi_k ~ Dirichlet over words (n_wk + m*beta),
+ * whose means are exactly the collapsed update of Eq. 6 and whose spread
+ * shrinks as m grows.  A Dirichlet vector is a vector of independent
+ * Gamma(shape, 1) variables divided by their sum.  theta is left unnormalised
+ * as in the collapsed update (its Gamma variables are divided by m, so that its
+ * mean is n_dk/m + alpha); phi is normalised over words per topic.
+ *
+ * Gamma variables: Marsaglia and Tsang, "A simple method for generating gamma
+ * variables" (ACM TOMS 26, 2000): with d = a - 1/3 and c = 1/sqrt(9d), draw a
+ * standard normal z, set v = (1 + c z)^3, accept d*v when v > 0 and
+ * log u < z^2/2 + d (1 - v + log v) (first tried without logarithms:
+ * u < 1 - 0.0331 z^4); a shape below one uses Gamma(a+1) * u'^(1/a).  The normal
+ * comes from two uniforms (Box and Muller).  Attempt j of element (row, k) takes
+ * the Philox block with counter (row, k, j, pass word); its words give the two
+ * uniforms of the normal, the acceptance uniform and the uniform of the
+ * small-shape factor.  After 64 refused attempts (probability below 1e-80) the
+ * shape itself is returned.
+ *
+ * Logarithm, cosine and exponential are evaluated from + - * / only, one
+ * rounding each, so that a second implementation takes the same decisions.   */
+
+/* log x for a positive normal x: x = 2^e * f with f in [sqrt(1/2), sqrt(2)),
+ * log f = 2 atanh(s), s = (f-1)/(f+1), by the odd series up to s^11.         */
+float oracle_flog(float x)
+{
+    uint32_t bits;
+    memcpy(&bits, &x, sizeof bits);
+    int32_t e = (int32_t)(bits >> 23) - 127;
+    uint32_t fb = (bits & 0x007FFFFFu) | 0x3F800000u;
+    float f;
+    memcpy(&f, &fb, sizeof f);
+    if (f > 1.41421354f) { f = f * 0.5f; e += 1; }
+    float num = f - 1.0f, den = f + 1.0f;
+    float s = num / den;
+    float z = s * s;
+    float p = 0.0909090936f;
+    p = p * z; p = p + 0.111111112f;
+    p = p * z; p = p + 0.142857149f;
+    p = p * z; p = p + 0.2f;
+    p = p * z; p = p + 0.333333343f;
+    p = p * z; p = p + 1.0f;
+    float lf = 2.0f * s;
+    lf = lf * p;
+    float le = (float)e * 0.693147182f;
+    return le + lf;
+}
+
+/* cos(2 pi u) for u in (0,1): the quarter turn and the angle inside it, then the
+ * Taylor polynomial of sine or cosine on [0, pi/2).                           */
+float oracle_cos2pi(float u)
+{
+    float t = u * 4.0f;
+    int32_t quarter = (int32_t)t;
+    float frac = t - (float)quarter;
+    float x = frac * 1.57079637f;
+    float x2 = x * x;
+    float sn = 1.60590444e-10f;
+    sn = sn * x2; sn = sn + -2.50521079e-08f;
+    sn = sn * x2; sn = sn + 2.75573188e-06f;
+    sn = sn * x2; sn = sn + -0.000198412701f;
+    sn = sn * x2; sn = sn + 0.00833333377f;
+    sn = sn * x2; sn = sn + -0.166666672f;
+    sn = sn * x2; sn = sn + 1.0f;
+    sn = sn * x;
+    float cs = -1.14707454e-11f;
+    cs = cs * x2; cs = cs + 2.08767570e-09f;
+    cs = cs * x2; cs = cs + -2.75573188e-07f;
+    cs = cs * x2; cs = cs + 2.48015876e-05f;
+    cs = cs * x2; cs = cs + -0.00138888892f;
+    cs = cs * x2; cs = cs + 0.0416666679f;
+    cs = cs * x2; cs = cs + -0.5f;
+    cs = cs * x2; cs = cs + 1.0f;
+    switch (quarter & 3) {
+        case 0:  return cs;
+        case 1:  return -sn;
+        case 2:  return -cs;
+        default: return sn;
+    }
+}
+
+/* Standard normal from two uniforms in (0,1). */
+float oracle_normal(float u1, float u2)
+{
+    float l = oracle_flog(u1);
+    float r2 = -2.0f * l;
+    float r = sqrtf(r2);
+    return r * oracle_cos2pi(u2);
+}
+
+float oracle_gamma(float a, uint64_t seed, uint32_t row, uint32_t k, uint32_t pass)
+{
+    uint32_t key[2] = { (uint32_t)seed, (uint32_t)(seed >> 32) };
+    int small = a < 1.0f;
+    float a1 = small ? a + 1.0f : a;
+    float d = a1 - 0.333333343f;
+    float nine_d = 9.0f * d;
+    float c = 1.0f / sqrtf(nine_d);
+    float g = a1;
+    uint32_t out[4] = { 0, 0, 0, 0 };
+    for (uint32_t attempt = 0; attempt < 64u; ++attempt) {
+        uint32_t ctr[4] = { row, k, attempt, pass };
+        oracle_philox4x32_10(ctr, key, out);
+        float z = oracle_normal(oracle_uniform_from_word(out[0]), oracle_uniform_from_word(out[1]));
+        float u = oracle_uniform_from_word(out[2]);
+        float cz = c * z;
+        float t = 1.0f + cz;
+        if (!(t > 0.0f)) continue;
+        float v = t * t;
+        v = v * t;
+        float z2 = z * z;
+        float z4 = z2 * z2;
+        float squeeze = 0.0331f * z4;
+        squeeze = 1.0f - squeeze;
+        int accept = u < squeeze;
+        if (!accept) {
+            float lhs = oracle_flog(u);
+            float half = 0.5f * z2;
+            float one_minus_v = 1.0f - v;
+            float inner = one_minus_v + oracle_flog(v);
+            float rhs = d * inner;
+            rhs = half + rhs;
+            accept = lhs < rhs;
+        }
+        if (accept) { g = d * v; break; }
+    }
+    if (small) {
+        float l = oracle_flog(oracle_uniform_from_word(out[3]));
+        float y = -l;
+        y = y / a;
+        if (y > 200.0f) y = 200.0f;
+        g = g * oracle_expneg(y);
+    }
+    if (g < 1e-30f) g = 1e-30f;
+    return g;
+}
+
+void oracle_theta_sample(int32_t D, int32_t K, const uint32_t* ndk, float mf, float alpha,
+                         uint64_t seed, uint32_t pass, float* theta)
+{
+    float prior = mf * alpha;
+#pragma omp parallel for schedule(static)
+    for (int32_t d = 0; d < D; ++d)
+        for (int32_t k = 0; k < K; ++k) {
+            float a = (float)ndk[(size_t)d * K + k] + prior;
+            float g = oracle_gamma(a, seed, (uint32_t)d, (uint32_t)k, pass);
+            theta[(size_t)d * K + k] = g / mf;
+        }
+}
+
+void oracle_phi_sample(int32_t V, int32_t K, const uint32_t* nwk, float mf, float beta,
+                       uint64_t seed, uint32_t pass, float* phi)
+{
+    float prior = mf * beta;
+#pragma omp parallel for schedule(static)
+    for (int32_t k = 0; k < K; ++k) {
+        double total = 0.0;
+        for (int32_t w = 0; w < V; ++w) {
+            float a = (float)nwk[(size_t)w * K + k] + prior;
+            float g = oracle_gamma(a, seed, (uint32_t)w, (uint32_t)k, pass);
+            phi[(size_t)w * K + k] = g;
+            total += (double)g;
+        }
+        float den = (float)total;
+        for (int32_t w = 0; w < V; ++w) phi[(size_t)w * K + k] = phi[(size_t)w * K + k] / den;
+    }
+}
+
 /* Per-word log-likelihood of a matrix under (theta, phi) (Section 6.1.1):
  * sum_i c_i * log( sum_k theta_dk phi_wk / sum_k theta_dk ) / sum_i c_i.
  * phi is already normalised over words.  The inner sum is the fp32 normaliser

@@ -532,3 +532,104 @@ def test_sddmm_closed_forms_and_brute_force():
     np.testing.assert_allclose(mu_k1, theta[doc, 0].astype(np.float64) * phi[X.rowidx, 0].astype(np.float64), rtol=1e-15)
     _, _, mu_draw = oracle.run_pass(X, K, 8, 1, 1, PW(1), theta, phi, want_mu=True)
     np.testing.assert_allclose(mu_draw, mu, rtol=1e-6)
+
+
+# --------------------------------------------------------------------------- #
+# the sampled parameter step (Algorithm 2, third step): Gamma variables and Dirichlet vectors
+def test_log_and_cosine_match_the_library_functions():
+    rng = np.random.default_rng(21)
+    xs = np.concatenate([rng.uniform(1e-7, 1, 1500), rng.uniform(0.5, 2, 1500), 10.0 ** rng.uniform(-30, 30, 1500)])
+    for x in xs.astype(np.float32):
+        want = math.log(float(x))
+        assert abs(oracle.flog(float(x)) - want) <= 4e-7 * max(abs(want), 1e-3)
+    assert oracle.flog(1.0) == 0.0
+    for u in rng.uniform(0, 1, 3000).astype(np.float32):
+        assert abs(oracle.cos2pi(float(u)) - math.cos(2 * math.pi * float(u))) <= 4e-7
+    assert oracle.cos2pi(0.25) == pytest.approx(0.0, abs=1e-7) and oracle.cos2pi(0.5) == pytest.approx(-1.0, abs=1e-7)
+
+
+def test_two_uniforms_give_a_standard_normal():
+    rng = np.random.default_rng(22)
+    u = rng.uniform(0, 1, size=(40000, 2)).astype(np.float32)
+    u = np.clip(u, 2.0 ** -24, 1 - 2.0 ** -24)
+    z = np.array([oracle.normal(float(a), float(b)) for a, b in u])
+    assert stats.kstest(z, "norm").pvalue > 1e-4
+    assert abs(z.mean()) < 0.03 and z.var() == pytest.approx(1.0, abs=0.03)
+    # the closed form itself, in double
+    for a, b in u[:200]:
+        want = math.sqrt(-2 * math.log(float(a))) * math.cos(2 * math.pi * float(b))
+        assert oracle.normal(float(a), float(b)) == pytest.approx(want, abs=3e-6)
+
+
+@pytest.mark.parametrize("a", [0.195, 0.9, 1.0, 1.5, 19.5, 500.0, 1.0e4])
+def test_gamma_variables_follow_the_gamma_law(a):
+    n = 30000
+    g = np.array([oracle.gamma(a, 7, r, 3, PW(5, oracle.DOMAIN_THETA)) for r in range(n)])
+    assert np.all(g > 0)
+    assert stats.kstest(g, stats.gamma(a).cdf).pvalue > 1e-4
+    assert g.mean() == pytest.approx(a, abs=5 * math.sqrt(a / n))
+    assert g.var() == pytest.approx(a, rel=0.06)
+    # another element or pass of the stream is another variable
+    assert oracle.gamma(a, 7, 0, 3, PW(5, oracle.DOMAIN_THETA)) != oracle.gamma(a, 7, 0, 4, PW(5, oracle.DOMAIN_THETA))
+    assert oracle.gamma(a, 7, 0, 3, PW(5, oracle.DOMAIN_THETA)) != oracle.gamma(a, 7, 0, 3, PW(6, oracle.DOMAIN_THETA))
+
+
+def test_gamma_of_a_very_small_shape_keeps_its_quantiles():
+    """Shape 0.05 puts 3% of its mass below the floor of 1e-30; the quantiles above it are those of the law."""
+    a, n = 0.05, 40000
+    g = np.array([oracle.gamma(a, 9, r, 0, PW(1, oracle.DOMAIN_PHI)) for r in range(n)])
+    assert g.min() >= 1e-30
+    for p in (0.5, 0.8, 0.95, 0.99):
+        frac = np.mean(g <= stats.gamma(a).ppf(p))
+        assert frac == pytest.approx(p, abs=5 * math.sqrt(p * (1 - p) / n))
+
+
+def test_sampled_theta_has_the_collapsed_update_as_mean_and_cools_with_m():
+    """theta ~ Gamma(n + m alpha)/m: mean n/m + alpha (Eq. 6's numerator), variance (n/m + alpha)/m."""
+    c = np.array([[0, 1, 3, 10]], np.uint32)
+    alpha = 0.25
+    for m in (1, 10, 100):
+        ndk = (c * m).astype(np.uint32)
+        draws = np.stack([oracle.theta_sample(ndk, float(m), alpha, 3, PW(t, oracle.DOMAIN_THETA))[0] for t in range(6000)])
+        mean_want = c[0] + alpha
+        assert np.all(np.abs(draws.mean(axis=0) - mean_want) < 5 * np.sqrt(mean_want / m / 6000))
+        np.testing.assert_allclose(draws.var(axis=0) * m / mean_want, 1.0, atol=0.1)
+    # many documents and topics: every element is its own variable
+    ndk = np.full((50, 8), 40, np.uint32)
+    th = oracle.theta_sample(ndk, 2.0, 0.5, 3, PW(1, oracle.DOMAIN_THETA))
+    assert len(np.unique(th)) == th.size
+
+
+def test_sampled_phi_is_a_dirichlet_vector_over_words_for_every_topic():
+    rng = np.random.default_rng(23)
+    V, K, m, beta = 6, 3, 4.0, 0.3
+    nwk = rng.integers(0, 30, size=(V, K)).astype(np.uint32)
+    draws = np.stack([oracle.phi_sample(nwk, m, beta, 5, PW(t, oracle.DOMAIN_PHI)) for t in range(8000)])
+    np.testing.assert_allclose(draws.sum(axis=1), 1.0, atol=1e-5)
+    a = nwk.astype(np.float64) + m * beta
+    A = a.sum(axis=0, keepdims=True)
+    mean_want = a / A
+    var_want = a * (A - a) / (A * A * (A + 1))
+    assert np.all(np.abs(draws.mean(axis=0) - mean_want) < 5 * np.sqrt(var_want / 8000) + 1e-6)
+    np.testing.assert_allclose(draws.var(axis=0) / var_want, 1.0, atol=0.12)
+    # two words of one topic are negatively correlated: cov = -a_i a_j / (A^2 (A+1))
+    cov = np.cov(draws[:, 0, 1], draws[:, 1, 1])[0, 1]
+    want = -a[0, 1] * a[1, 1] / (A[0, 1] ** 2 * (A[0, 1] + 1))
+    assert cov == pytest.approx(want, rel=0.2)
+
+
+def test_sampled_sweep_advances_the_model_and_repeats_for_a_seed():
+    counts, X = _toy(seed=4)
+    a = oracle.OracleLDA(X, 6, 0.2, 0.05, seed=11, m0=1, G=8)
+    b = oracle.OracleLDA(X, 6, 0.2, 0.05, seed=11, m0=1, G=8)
+    for _ in range(3):
+        a.sweep_sampled(5); b.sweep_sampled(5)
+    np.testing.assert_array_equal(a.theta, b.theta)
+    np.testing.assert_array_equal(a.phi, b.phi)
+    assert a.t == 4 and np.all(a.theta > 0) and np.all(a.phi > 0)
+    np.testing.assert_allclose(a.phi.sum(axis=0), 1.0, atol=1e-5)
+    assert int(a.ndk.sum()) == 5 * int(counts.sum())
+    c = oracle.OracleLDA(X, 6, 0.2, 0.05, seed=11, m0=1, G=8)
+    for _ in range(3):
+        c.sweep(5)
+    assert not np.array_equal(a.theta, c.theta)          # not the mean update
