@@ -41,7 +41,7 @@ def measured_traffic(workload: str, form: str = "multinomial"):
     return None
 
 
-def cpu_baseline(X_np, K, alpha, beta, m, m0, G, target_s=12.0, poisson=False):
+def cpu_baseline(X_np, K, alpha, beta, m, m0, G, target_s=12.0, poisson=False, sampled=False):
     """Times one sweep of the oracle (as it stands) on a leading slice of documents sized for ~target_s."""
     import oracle
     cores = len(os.sched_getaffinity(0))
@@ -50,7 +50,7 @@ def cpu_baseline(X_np, K, alpha, beta, m, m0, G, target_s=12.0, poisson=False):
         sl = X_np.slice_docs(0, docs)
         o = oracle.OracleLDA(sl, K, alpha, beta, seed=1, m0=m0, G=G)
         t0 = time.perf_counter()
-        o.sweep_poisson(float(m)) if poisson else o.sweep(m)
+        o.sweep_poisson(float(m)) if poisson else (o.sweep_sampled(m) if sampled else o.sweep(m))
         dt = max(time.perf_counter() - t0, 1e-4)
         if dt >= 0.5 * target_s or docs >= X_np.D:
             break
@@ -190,6 +190,9 @@ def main():
     ap.add_argument("--form", choices=["multinomial", "poisson"], default="multinomial",
                     help="form of the factored draw: the exact-total multinomial (the headline path) or the "
                          "independent Poisson counts of Algorithm 3 as printed")
+    ap.add_argument("--update", choices=["collapsed", "sampled"], default="collapsed",
+                    help="parameter step: the posterior means of Eq. 6 (what the paper runs, the headline) or "
+                         "Dirichlet draws of theta and phi (Algorithm 2, third step; multinomial form only)")
     ap.add_argument("--mode", choices=["resident", "stream", "sddmm"], default="resident",
                     help="resident: sweeps over one matrix held in HBM (the headline); stream: one sweep per "
                          "minibatch of a stream of host-resident minibatches; sddmm: the normaliser alone")
@@ -235,7 +238,11 @@ def main():
     t_init = time.perf_counter() - t0
 
     poisson = args.form == "poisson"
-    sweep = (lambda mm: g.sweep_poisson(float(mm))) if poisson else (lambda mm: g.sweep(mm))
+    sampled = args.update == "sampled"
+    if poisson and sampled:
+        sys.exit("bench.py: --update sampled goes with the multinomial form")
+    sweep = ((lambda mm: g.sweep_poisson(float(mm))) if poisson else
+             (lambda mm: g.sweep_sampled(mm)) if sampled else (lambda mm: g.sweep(mm)))
     for s in range(args.warmup):
         sweep(1 if s < args.warmup - 40 else m)
     g.synchronize()
@@ -258,14 +265,15 @@ def main():
     achieved = bytes_per_launch / (draw_ms_avg * 1e-3) / 1e9
 
     out = {
-        "metric": ("tokens/sec per SAME sweep (K=256, m=100) + achieved HBM GB/s vs 8 TB/s" if not poisson else
-                   "tokens/sec per SAME sweep in the Poisson form (K=256, m=100) + achieved HBM GB/s vs 8 TB/s"),
+        "metric": ("tokens/sec per SAME sweep in the Poisson form (K=256, m=100) + achieved HBM GB/s vs 8 TB/s" if poisson else
+                   "tokens/sec per SAME sweep with sampled theta and phi (K=256, m=100) + achieved HBM GB/s vs 8 TB/s" if sampled else
+                   "tokens/sec per SAME sweep (K=256, m=100) + achieved HBM GB/s vs 8 TB/s"),
         "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{args.workload} (LDA-generated, scale {args.scale})", "D": st["D"], "V": st["V"],
                    "K": K, "m": m, "nnz": st["nnz"], "tokens": st["tokens"], "max_count": st["max_count"],
-                   "form": args.form, "tokens_per_draw": G, "draw_tasks": g.task_count, "alpha": alpha, "beta": beta,
+                   "form": args.form, "update": args.update, "tokens_per_draw": G, "draw_tasks": g.task_count, "alpha": alpha, "beta": beta,
                    "m_init": m0,
                    "warmup_schedule": f"{max(0, args.warmup - 40)} sweeps at m=1 then {min(40, args.warmup)} at m={m}",
                    "generate_s": round(t_gen, 2), "init_s": round(t_init, 2)},
@@ -280,7 +288,7 @@ def main():
     if not args.no_cpu_baseline:
         X_np = oracle.CSC(train.D, train.V, train.colptr.cpu().numpy(), train.rowidx.cpu().numpy(),
                           train.val.cpu().numpy())
-        out["cpu_baseline"] = cpu_baseline(X_np, K, alpha, beta, m, m0, G, poisson=poisson)
+        out["cpu_baseline"] = cpu_baseline(X_np, K, alpha, beta, m, m0, G, poisson=poisson, sampled=sampled)
     print(json.dumps(out))
 
 

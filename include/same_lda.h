@@ -96,6 +96,19 @@ int same_lda_sweep(same_lda_t* h, int32_t m_t, float rho_t);
  *   rho_t  in (0, 1]                                                                           */
 int same_lda_sweep_poisson(same_lda_t* h, float m_t, float rho_t);
 
+/* A sweep whose parameter step is sampled instead of collapsed (Algorithm 2, third step; Section
+ * 3.1: given the m copies the parameters follow the product of the single-copy conditionals, for
+ * LDA a Dirichlet again): the draws and counts are those of same_lda_sweep; then
+ *   theta_d ~ Dirichlet(n_dk' + m_t*alpha), kept unnormalised with mean n_dk'/m_t + alpha,
+ *   phi_k   ~ Dirichlet over words (n_wk' + m_t*beta),
+ * whose means are the update of Eq. 6 and whose spread shrinks as m_t grows.  The Gamma variables
+ * come from the handle's seed on streams of their own (Marsaglia-Tsang on Philox blocks, one per
+ * attempt), so the result is a function of (seed, pass index, counts).  Takes the next pass index
+ * like same_lda_sweep; the sweep forms may alternate on one handle.  Allocates (V/64 + 1) * K
+ * doubles of device memory on its first call.  Asynchronous.
+ *   m_t    >= 1, and m_t * (largest group size) < 2^24                                         */
+int same_lda_sweep_sampled(same_lda_t* h, int32_t m_t);
+
 /* Per-word log-likelihood of held-out documents (Section 6.1.1): theta of the held-out
  * documents is fitted with phi frozen (a uniform-weight pass, then foldin_sweeps passes with
  * m_eval copies, on a separate random stream), then

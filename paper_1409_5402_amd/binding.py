@@ -21,7 +21,7 @@ THETA, PHI, NDK, NWK, NK = 0, 1, 2, 3, 4
 DEFAULT_TOKENS_PER_DRAW = 1024
 _DTYPES = {THETA: np.float32, PHI: np.float32, NDK: np.uint32, NWK: np.uint32, NK: np.uint64}
 
-EXPORTS = ["same_lda_init", "same_lda_sweep", "same_lda_sweep_poisson", "same_lda_loglik", "same_lda_free",
+EXPORTS = ["same_lda_init", "same_lda_sweep", "same_lda_sweep_poisson", "same_lda_sweep_sampled", "same_lda_loglik", "same_lda_free",
            "same_lda_set_batch", "same_lda_stage_batch", "same_lda_commit_batch", "same_lda_debug_draw_poisson", "same_lda_sddmm",
            "same_lda_get", "same_lda_set", "same_lda_get_pass", "same_lda_set_pass", "same_lda_task_count",
            "same_lda_debug_draw", "same_lda_set_timing", "same_lda_get_timing", "same_lda_selftest",
@@ -49,10 +49,15 @@ def load() -> ctypes.CDLL:
     if _lib is None:
         if not os.path.exists(LIB_PATH):
             raise FileNotFoundError(f"{LIB_PATH} is missing: run paper_1409_5402_amd.build.build() first")
+        try:
+            import torch  # noqa: F401  (where torch is installed, its HIP runtime must be the one loaded first:
+        except ImportError:             # the library then binds to the same runtime as the tensors it is given)
+            pass
         L = ctypes.CDLL(LIB_PATH)
         L.same_lda_init.argtypes = [POINTER(c_void_p), POINTER(_Csc), c_int32, c_float, c_float, c_uint64,
                                     c_int32, c_int32, c_void_p]
         L.same_lda_sweep.argtypes = [c_void_p, c_int32, c_float]
+        L.same_lda_sweep_sampled.argtypes = [c_void_p, c_int32]
         L.same_lda_sweep_poisson.argtypes = [c_void_p, c_float, c_float]
         L.same_lda_debug_draw_poisson.argtypes = [c_void_p, c_float, c_void_p, c_int32, c_void_p]
         L.same_lda_loglik.argtypes = [c_void_p, POINTER(_Csc), c_int32, c_int32, POINTER(c_double)]
@@ -148,6 +153,9 @@ class SameLDA:
 
     def sweep(self, m, rho=1.0):
         self._check(self._lib.same_lda_sweep(self._h, int(m), float(rho)))
+
+    def sweep_sampled(self, m):
+        self._check(self._lib.same_lda_sweep_sampled(self._h, int(m)))
 
     def sweep_poisson(self, m, rho=1.0):
         self._check(self._lib.same_lda_sweep_poisson(self._h, float(m), float(rho)))

@@ -14,6 +14,7 @@
 #include <unordered_map>
 #include <vector>
 
+#include "gamma_kernels.h"
 #include "update_kernels.h"
 #include "worklist_kernels.h"
 
@@ -112,6 +113,8 @@ struct same_lda {
     float* phi = nullptr;          // [V][K]
     uint32_t* nwk = nullptr;       // [V][K]
     unsigned long long* nk = nullptr;  // [K]
+    double* gamma_partial = nullptr;   // [blocks][K] block sums of the sampled phi step (allocated on first use)
+    float* gamma_total = nullptr;      // [K]
     bool timing = false;
     std::vector<std::pair<hipEvent_t, hipEvent_t>> events;   // recorded, not yet read
     std::vector<std::pair<hipEvent_t, hipEvent_t>> pool;     // free event pairs
@@ -429,6 +432,40 @@ int update_phi(same_lda* h, float m, float rho, hipStream_t st)
     return SAME_LDA_OK;
 }
 
+constexpr int kGammaRows = 64;     // rows of n_wk per workgroup of the sampled phi step
+
+// theta of M drawn from its Dirichlet conditional (unnormalised, mean n_dk/m + alpha).
+int sample_theta(same_lda* h, Matrix& M, float m, uint32_t pword, hipStream_t st)
+{
+    const size_t n = (size_t)M.D * h->K;
+    if (n == 0) return SAME_LDA_OK;
+    hipLaunchKernelGGL(same::gamma_theta_kernel, dim3(grid_for(n)), dim3(256), 0, st, M.ndk, M.theta, n, h->K, m,
+                       m * h->alpha, (uint32_t)h->seed, (uint32_t)(h->seed >> 32), pword);
+    HIP_TRY(h, hipGetLastError());
+    return SAME_LDA_OK;
+}
+
+// phi drawn from its Dirichlet conditionals: Gamma variables, their sums over words in a fixed order, division.
+int sample_phi(same_lda* h, float m, uint32_t pword, hipStream_t st)
+{
+    const size_t n = (size_t)h->V * h->K;
+    const int blocks = (h->V + kGammaRows - 1) / kGammaRows;
+    int rc;
+    if (!h->gamma_partial && (rc = dev_alloc(h, &h->gamma_partial, (size_t)blocks * h->K))) return rc;
+    if (!h->gamma_total && (rc = dev_alloc(h, &h->gamma_total, (size_t)h->K))) return rc;
+    // the topic totals are part of the readable state, kept current as after a collapsed update
+    hipLaunchKernelGGL(same::zero_u64_kernel, dim3(1), dim3(256), 0, st, h->nk, (size_t)h->K);
+    hipLaunchKernelGGL(same::topic_totals_kernel, dim3(blocks), dim3(256), 0, st, h->nwk, h->V, h->K, h->nk, kGammaRows);
+    hipLaunchKernelGGL(same::gamma_phi_kernel, dim3(blocks), dim3(256), 0, st, h->nwk, h->phi, h->V, h->K,
+                       m * h->beta, (uint32_t)h->seed, (uint32_t)(h->seed >> 32), pword, kGammaRows, h->gamma_partial);
+    hipLaunchKernelGGL(same::gamma_phi_totals_kernel, dim3((h->K + 255) / 256), dim3(256), 0, st, h->gamma_partial,
+                       blocks, h->K, h->gamma_total);
+    hipLaunchKernelGGL(same::gamma_phi_normalise_kernel, dim3(grid_for(n)), dim3(256), 0, st, h->phi, n, h->K,
+                       h->gamma_total);
+    HIP_TRY(h, hipGetLastError());
+    return SAME_LDA_OK;
+}
+
 // One pass of draws on M.  uniform: weights are all ones (initialisation).
 int run_pass(same_lda* h, Matrix& M, Copies c, uint32_t pword, bool uniform, bool with_words, bool timed,
              hipStream_t st)
@@ -539,6 +576,17 @@ int same_lda_sweep(same_lda_t* h, int32_t m_t, float rho_t)
     return rc;
 }
 
+int same_lda_sweep_sampled(same_lda_t* h, int32_t m_t)
+{
+    if (!h) return SAME_LDA_EINVAL;
+    int rc = check_m(h, m_t, h->X);
+    if (!rc) rc = run_pass(h, h->X, Copies::whole((uint32_t)m_t), pass_word(h->pass, 0), false, true, h->timing, h->stream);
+    if (!rc) rc = sample_theta(h, h->X, (float)m_t, pass_word(h->pass, 2), h->stream);
+    if (!rc) rc = sample_phi(h, (float)m_t, pass_word(h->pass, 3), h->stream);
+    if (!rc) h->pass += 1;
+    return rc;
+}
+
 int same_lda_sweep_poisson(same_lda_t* h, float m_t, float rho_t)
 {
     if (!h) return SAME_LDA_EINVAL;
@@ -645,6 +693,7 @@ void same_lda_free(same_lda_t* h)
     if (h->has_staged) free_matrix(h, h->staged);
     if (h->copy_stream) { hipStreamSynchronize(h->copy_stream); hipStreamDestroy(h->copy_stream); }
     dev_free(h, h->phi); dev_free(h, h->nwk); dev_free(h, h->nk);
+    dev_free(h, h->gamma_partial); dev_free(h, h->gamma_total);
     h->cache.clear_spare();
     for (auto& e : h->events) { hipEventDestroy(e.first); hipEventDestroy(e.second); }
     for (auto& e : h->pool) { hipEventDestroy(e.first); hipEventDestroy(e.second); }

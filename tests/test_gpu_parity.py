@@ -333,6 +333,38 @@ def test_staged_minibatches_overlap_order_and_wrong_announcement():
 
 
 # --------------------------------------------------------------------------- #
+# The sampled parameter step (Algorithm 2, third step): theta and phi as Dirichlet draws
+@pytest.mark.parametrize("K,G,ms", [(16, 8, [10, 1, 3]), (40, 3, [100, 2]), (5, 1000, [400, 1])])
+def test_sampled_sweeps_match_the_oracle(K, G, ms):
+    """Counts bit-exact, theta and phi to 1e-5: one differently decided acceptance of a Gamma variable
+    would show as a wholly different value.  m = 1 with small priors takes the small-shape branch."""
+    X = toy(seed=18, D=70, V=50, density=0.3, cmax=40)
+    o = oracle.OracleLDA(X, K, 0.1, 0.01, seed=5, m0=3, G=G)
+    g = make_gpu(X, K, 0.1, 0.01, 5, 3, G, on_device=True)
+    for s, m in enumerate(ms):
+        o.sweep_sampled(m); g.sweep_sampled(m)
+        assert_state_equal(g, o, f"K={K} G={G} sampled sweep {s + 1} m={m}")
+    o.sweep(7); g.sweep(7)                                  # and back to the collapsed update on the same handle
+    assert_state_equal(g, o, "collapsed sweep after sampled ones")
+    assert g.pass_index == o.t
+    g.close()
+
+
+def test_sampled_sweep_news_shape_slice():
+    """News workload shape (K=256, V=100000) on a 600-document slice: most n_wk are zero, so most Gamma
+    variables of phi have shape m*beta (1 at m=100, 0.01 at m=1: both branches) and the sums run over 1563 blocks."""
+    p = synth.PRESETS["news"]
+    X = corpus_to_csc(synth.preset("news", scale=0.002))
+    o = oracle.OracleLDA(X, p["K"], p["alpha"], p["beta"], seed=9, m0=1, G=32)
+    g = make_gpu(X, p["K"], p["alpha"], p["beta"], 9, 1, 32)
+    o.sweep_sampled(100); g.sweep_sampled(100)
+    assert_state_equal(g, o, "sampled m=100")
+    o.sweep_sampled(1); g.sweep_sampled(1)
+    assert_state_equal(g, o, "sampled m=1")
+    np.testing.assert_allclose(g.get(binding.PHI).astype(np.float64).sum(axis=0), 1.0, atol=1e-4)
+    g.close()
+
+
 # Poisson form of the factored draw (Section 4, second part; Algorithm 3's sampling line)
 @pytest.mark.parametrize("K,G,ms", [(16, 8, [10.0, 0.5, 3.25]), (24, 1, [1.0, 30.0]), (40, 3, [100.0, 2.5]),
                                     (5, 1000, [400.0, 0.1])])
