@@ -22,6 +22,13 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 
 
+def draw_kernel_compulsory_bytes(nnz: int, D: int, V: int, K: int) -> float:
+    """Bytes of one draw-and-scatter launch if every array were touched once (phi served from cache after
+    its first read): word ids and counts, theta and the new document counts, phi, the new word counts
+    read and written."""
+    return float(nnz) * 8 + float(D) * (4 + 8 * K) + float(V) * K * 12
+
+
 def draw_kernel_bytes(nnz: int, D: int, K: int) -> float:
     """Algorithmic bytes of one draw-and-scatter launch: per nonzero its word id, its count and the
     K floats of phi_w; per document its column pointer, the K floats of theta_d and the K new counts."""
@@ -279,7 +286,8 @@ def main():
                    "generate_s": round(t_gen, 2), "init_s": round(t_init, 2)},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(args.workload, args.form),
-                     "kernel": "draw_kernel", "kernel_ms": draw_ms_avg, "bytes_per_launch": bytes_per_launch},
+                     "kernel": "draw_kernel", "kernel_ms": draw_ms_avg, "bytes_per_launch": bytes_per_launch,
+                     "compulsory_bytes_per_launch": draw_kernel_compulsory_bytes(st["nnz"], st["D"], st["V"], K)},
     }
     if test is not None and not args.no_loglik:
         out["config"]["heldout_ll_per_word"] = g.loglik(test.D, test.colptr, test.rowidx, test.val, 3, m)

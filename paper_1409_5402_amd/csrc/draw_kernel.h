@@ -181,7 +181,8 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
     const int64_t slot = (int64_t)blockIdx.x * kWave + lane;
     const bool live = slot < a.n;
     const int64_t row = live ? slot : a.n - 1;
-    const int64_t tau = DEBUG ? a.ids[row] : (int64_t)a.order[row];
+    // order holds non-negative 32-bit ids: the high byte of tau is then a constant zero for the whole launch
+    const int64_t tau = DEBUG ? a.ids[row] : (int64_t)(uint32_t)a.order[row];
     const int32_t d = a.t_doc[tau];
     const int32_t w = a.t_word[tau];
     const uint32_t N = POISSON ? (live ? 1u : 0u) : (live ? a.m * a.t_g[tau] : 0u);
@@ -195,6 +196,7 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
     key.seed_lo = a.seed_lo; key.seed_hi = a.seed_hi;
     key.tau_lo = (uint32_t)tau; key.tau_hi = (uint32_t)((uint64_t)tau >> 32) & 0xFFu;
     key.pass = a.pass;
+    const PrimaryPre pre = primary_pre(key);
 
     // ---- pass 1: running sum, checkpoint before every block; heaviest topic (highest index among ties)
     float wmax = -1.0f;
@@ -422,7 +424,7 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
 #pragma unroll
             for (int g = kBlk / 4 - 1; g >= 0; --g) {
                 uint32_t x[4];
-                primary_block(key, (uint32_t)(b * (kBlk / 4) + g), x);
+                primary_block(key, pre, (uint32_t)(b * (kBlk / 4) + g), x);
 #pragma unroll
                 for (int j = 3; j >= 0; --j) {
                     const int k = b * kBlk + g * 4 + j;

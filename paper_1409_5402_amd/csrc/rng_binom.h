@@ -50,6 +50,58 @@ __device__ __forceinline__ void primary_block(const StreamKey& s, uint32_t quad,
     philox4x32_10(s.tau_lo, s.tau_hi, quad, s.pass, s.seed_lo, s.seed_hi, out);
 }
 
+// The same block with the first two rounds split by what their inputs depend on.  Of the four
+// products of those rounds, two depend only on the task (its id, the pass, the seed): PrimaryPre holds
+// them, computed once per task.  The other two depend on the quad and, through one exclusive-or, on
+// the high byte of the task id: where that byte is the same for the whole wave (it is zero for every
+// launch whose task ids fit 32 bits) they are scalar work.  Eight general rounds follow.
+struct PrimaryPre { uint32_t c2a, c3a, hi1, lo1; };
+
+__device__ __forceinline__ PrimaryPre primary_pre(const StreamKey& s)
+{
+    PrimaryPre r;
+    const uint64_t p0 = (uint64_t)0xD2511F53u * (uint64_t)s.tau_lo;     // round 1, counter word 0
+    r.c3a = (uint32_t)p0;
+    r.c2a = (uint32_t)(p0 >> 32) ^ s.pass ^ s.seed_hi;                  // counter word 2 after round 1
+    const uint64_t p1 = (uint64_t)0xCD9E8D57u * (uint64_t)r.c2a;        // round 2, counter word 2
+    r.hi1 = (uint32_t)(p1 >> 32);
+    r.lo1 = (uint32_t)p1;
+    return r;
+}
+
+__device__ __forceinline__ void primary_block(const StreamKey& s, const PrimaryPre& pre, uint32_t quad,
+                                              uint32_t (&out)[4])
+{
+    uint32_t k0 = s.seed_lo, k1 = s.seed_hi;
+    // round 1
+    const uint64_t q1 = (uint64_t)0xCD9E8D57u * (uint64_t)quad;
+    uint32_t c0 = (uint32_t)(q1 >> 32) ^ s.tau_hi ^ k0;
+    uint32_t c1 = (uint32_t)q1;
+    uint32_t c3 = pre.c3a;
+    k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
+    // round 2
+    const uint64_t p0 = (uint64_t)0xD2511F53u * (uint64_t)c0;
+    c0 = pre.hi1 ^ c1 ^ k0;
+    uint32_t c2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+    c1 = pre.lo1;
+    c3 = (uint32_t)p0;
+    k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
+#pragma unroll
+    for (int round = 2; round < 10; ++round) {
+        const uint64_t a0 = (uint64_t)0xD2511F53u * (uint64_t)c0;
+        const uint64_t a1 = (uint64_t)0xCD9E8D57u * (uint64_t)c2;
+        const uint32_t n0 = (uint32_t)(a1 >> 32) ^ c1 ^ k0;
+        const uint32_t n2 = (uint32_t)(a0 >> 32) ^ c3 ^ k1;
+        c1 = (uint32_t)a1;
+        c3 = (uint32_t)a0;
+        c0 = n0;
+        c2 = n2;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
 // Block holding the uniforms of pieces 4*pb+1 .. 4*pb+4 of topic k.
 __device__ __forceinline__ void piece_block(const StreamKey& s, uint32_t k, uint32_t pb, uint32_t (&out)[4])
 {
