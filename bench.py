@@ -188,9 +188,13 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=140,
-                    help="untimed sweeps before timing: all but the last 40 run with m=1 (annealing burn-in), "
-                         "the last 40 with the workload's m; the timed sweeps then complete a 50-sweep run at m")
+    ap.add_argument("--warmup", type=int, default=None,
+                    help="untimed steps right before the timed ones, same kind as the timed ones "
+                         "(default 10; 20 minibatches in stream mode)")
+    ap.add_argument("--burn-in", type=int, nargs=2, default=[100, 30], metavar=("AT_M1", "AT_M"),
+                    help="resident mode: state preparation before the warm-up, untimed: sweeps at m=1 (an annealing "
+                         "burn-in that breaks the symmetry of the random start), then sweeps at the workload's m.  "
+                         "With the defaults the timed sweeps complete a 50-sweep run at m from a converged state")
     ap.add_argument("--workload", default="news")
     ap.add_argument("--scale", type=float, default=1.0, help="fraction of the workload's documents (1.0 = full size)")
     ap.add_argument("--tokens-per-draw", type=int, default=None, help="default: binding.DEFAULT_TOKENS_PER_DRAW")
@@ -216,9 +220,11 @@ def main():
         from paper_1409_5402_amd.binding import DEFAULT_TOKENS_PER_DRAW
         args.tokens_per_draw = DEFAULT_TOKENS_PER_DRAW
     if args.mode == "stream":
-        if args.warmup == 140:
+        if args.warmup is None:
             args.warmup, args.steps = 20, max(args.steps, 40)
         return stream_bench(args)
+    if args.warmup is None:
+        args.warmup = 10
     if args.mode == "sddmm":
         return sddmm_bench(args)
     import oracle
@@ -250,8 +256,12 @@ def main():
         sys.exit("bench.py: --update sampled goes with the multinomial form")
     sweep = ((lambda mm: g.sweep_poisson(float(mm))) if poisson else
              (lambda mm: g.sweep_sampled(mm)) if sampled else (lambda mm: g.sweep(mm)))
-    for s in range(args.warmup):
-        sweep(1 if s < args.warmup - 40 else m)
+    for _ in range(args.burn_in[0]):        # state preparation: the sampler is timed where a run spends its time,
+        sweep(1)                            # with topics formed, not in the first sweeps after a random start
+    for _ in range(args.burn_in[1]):
+        sweep(m)
+    for _ in range(args.warmup):
+        sweep(m)
     g.synchronize()
     g.set_timing(True)
     torch.cuda.synchronize()
@@ -282,7 +292,7 @@ def main():
                    "K": K, "m": m, "nnz": st["nnz"], "tokens": st["tokens"], "max_count": st["max_count"],
                    "form": args.form, "update": args.update, "tokens_per_draw": G, "draw_tasks": g.task_count, "alpha": alpha, "beta": beta,
                    "m_init": m0,
-                   "warmup_schedule": f"{max(0, args.warmup - 40)} sweeps at m=1 then {min(40, args.warmup)} at m={m}",
+                   "state": f"untimed before the warm-up: {args.burn_in[0]} sweeps at m=1 then {args.burn_in[1]} at m={m}",
                    "generate_s": round(t_gen, 2), "init_s": round(t_init, 2)},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(args.workload, args.form),
