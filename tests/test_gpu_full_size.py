@@ -68,9 +68,13 @@ def test_news_full_size_properties_and_sampled_parity():
     wrows = rng.choice(X.V, 200, replace=False)
     np.testing.assert_allclose(ph[wrows], (nwk[wrows] / m + beta) / (nk.astype(np.float64) / m + X.V * beta), rtol=1e-5)
 
-    # one full-size sweep in the Poisson form: both count matrices hold the same copies, document totals are
-    # Poisson around m * tokens (checked in units of their standard deviation), sampled documents match the oracle
-    theta2, phi2 = g.get(binding.THETA), g.get(binding.PHI)
+    # one full-size sweep in the Poisson form, from a second seeded state: both count matrices hold the same
+    # copies, document totals are Poisson around m * tokens (checked in units of their standard deviation),
+    # sampled documents match the oracle
+    theta2_t, phi2_t = synth.state(train, K, alpha, beta, seed=124, zipf_s=1.1)
+    g.set(binding.THETA, theta2_t)
+    g.set(binding.PHI, phi2_t)
+    theta2, phi2 = theta2_t.cpu().numpy(), phi2_t.cpu().numpy()
     pword2 = oracle.pass_word(g.pass_index)
     g.sweep_poisson(float(m))
     ndk, nwk, nk = g.get(binding.NDK), g.get(binding.NWK), g.get(binding.NK)
@@ -82,4 +86,26 @@ def test_news_full_size_properties_and_sampled_parity():
         t0, t1 = int(base[X.colptr[d]]), int(base[X.colptr[d + 1]])
         vec = oracle.draw_tasks_poisson(X, K, G, float(m), 5, pword2, theta2, phi2, np.arange(t0, t1))
         assert np.array_equal(vec.sum(axis=0, dtype=np.int64), ndk[d].astype(np.int64)), d
+
+    # one full-size sweep with the sampled parameter step, from a third seeded state: sampled documents'
+    # counts from the oracle's draws, their theta rows from the oracle's Gamma variables one by one;
+    # phi is a probability vector over words for every topic
+    theta3_t, phi3_t = synth.state(train, K, alpha, beta, seed=125, zipf_s=1.1)
+    g.set(binding.THETA, theta3_t)
+    g.set(binding.PHI, phi3_t)
+    theta3, phi3 = theta3_t.cpu().numpy(), phi3_t.cpu().numpy()
+    t3 = g.pass_index
+    g.sweep_sampled(m)
+    ndk, th, ph = g.get(binding.NDK), g.get(binding.THETA), g.get(binding.PHI)
+    prior = np.float32(np.float32(m) * np.float32(alpha))
+    for d in [0, 777, X.D - 1]:
+        t0, t1 = int(base[X.colptr[d]]), int(base[X.colptr[d + 1]])
+        vec = oracle.draw_tasks(X, K, G, m, 5, oracle.pass_word(t3), theta3, phi3, np.arange(t0, t1))
+        n_d = vec.sum(axis=0, dtype=np.int64)
+        assert np.array_equal(n_d, ndk[d].astype(np.int64)), d
+        want = np.array([oracle.gamma(float(np.float32(n_d[k]) + prior), 5, d, k, oracle.pass_word(t3, oracle.DOMAIN_THETA))
+                         for k in range(K)], np.float32) / np.float32(m)
+        np.testing.assert_allclose(th[d], want, rtol=1e-5)
+    assert np.all(np.isfinite(ph)) and ph.min() > 0
+    np.testing.assert_allclose(ph.astype(np.float64).sum(axis=0), 1.0, atol=1e-4)
     g.close()
