@@ -333,6 +333,43 @@ def test_staged_minibatches_overlap_order_and_wrong_announcement():
 
 
 # --------------------------------------------------------------------------- #
+def test_random_small_configurations_all_sweep_forms():
+    """Eighty seeded random configurations (shapes, densities, counts up to 3000, K from 1 to 513 including ragged
+    ones, group sizes, priors, seeds), each swept two to four times with a random mix of the multinomial form
+    (with and without a blend), the Poisson form (real m from 0.3 up) and the sampled parameter step."""
+    rng = np.random.default_rng(20240)
+    for c in range(80):
+        D, V = int(rng.integers(1, 60)), int(rng.integers(1, 50))
+        dens = float(rng.choice([0.05, 0.2, 0.5, 1.0]))
+        cmax = int(rng.choice([1, 3, 12, 60, 400, 3000]))
+        K = int(rng.choice([1, 2, 3, 4, 7, 15, 16, 17, 31, 32, 33, 48, 64, 100, 128, 200, 256, 300, 513]))
+        G = int(rng.choice([1, 2, 7, 64, 1024]))
+        counts = rng.integers(1, cmax + 1, size=(D, V)) * (rng.uniform(size=(D, V)) < dens)
+        if counts.sum() == 0:
+            counts[0, 0] = 1
+        X = csc_from_dense(counts)
+        alpha, beta = float(rng.choice([0.01, 0.1, 0.5, 2.0])), float(rng.choice([0.001, 0.01, 0.3]))
+        m0, seed = int(rng.choice([1, 2, 10])), int(rng.integers(0, 2 ** 62))
+        mmax = max(1, min(1000, 20000 // cmax))
+        what = f"configuration {c}: D={D} V={V} density={dens} cmax={cmax} K={K} G={G} alpha={alpha} beta={beta} m0={m0}"
+        o = oracle.OracleLDA(X, K, alpha, beta, seed=seed, m0=m0, G=G)
+        g = make_gpu(X, K, alpha, beta, seed, m0, G)
+        for s in range(int(rng.integers(2, 5))):
+            kind = str(rng.choice(["multinomial", "multinomial", "poisson", "sampled"]))
+            if kind == "multinomial":
+                m, rho = int(rng.integers(1, mmax + 1)), float(rng.choice([1.0, 1.0, 0.7, 0.25]))
+                o.sweep(m, rho); g.sweep(m, rho)
+            elif kind == "poisson":
+                m = float(np.float32(rng.choice([0.3, 1.0, 2.5, 17.0, 100.0, mmax * 0.9])))
+                rho = float(rng.choice([1.0, 0.5]))
+                o.sweep_poisson(m, rho); g.sweep_poisson(m, rho)
+            else:
+                m = int(rng.integers(1, min(mmax, 300) + 1))
+                o.sweep_sampled(m); g.sweep_sampled(m)
+            assert_state_equal(g, o, f"{what}, sweep {s + 1} ({kind}, m={m})")
+        g.close()
+
+
 # The sampled parameter step (Algorithm 2, third step): theta and phi as Dirichlet draws
 @pytest.mark.parametrize("K,G,ms", [(16, 8, [10, 1, 3]), (40, 3, [100, 2]), (5, 1000, [400, 1])])
 def test_sampled_sweeps_match_the_oracle(K, G, ms):
