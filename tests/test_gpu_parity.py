@@ -370,6 +370,71 @@ def test_random_small_configurations_all_sweep_forms():
         g.close()
 
 
+def test_random_api_sequences():
+    """Forty seeded random sequences of calls on one handle: sweeps in the three forms, new minibatches through
+    set_batch or stage + commit (from host, pinned and device memory, with right and wrong announcements and
+    sweeps in between), held-out likelihoods, and a restored state; the oracle follows every step."""
+    rng = np.random.default_rng(77)
+    dev = torch.device("cuda:0")
+
+    def rand_matrix(V, cmax):
+        D, dens = int(rng.integers(1, 50)), float(rng.choice([0.1, 0.4, 1.0]))
+        counts = rng.integers(1, cmax + 1, size=(D, V)) * (rng.uniform(size=(D, V)) < dens)
+        if counts.sum() == 0:
+            counts[0, 0] = 1
+        return csc_from_dense(counts)
+
+    def arrays(B, where):
+        if where == "host":
+            return [B.colptr, B.rowidx, B.val]
+        a = [torch.from_numpy(B.colptr), torch.from_numpy(B.rowidx), torch.from_numpy(B.val)]
+        return [t.pin_memory() for t in a] if where == "pinned" else [t.to(dev) for t in a]
+
+    for c in range(40):
+        V, cmax = int(rng.integers(2, 60)), int(rng.choice([1, 5, 40, 300]))
+        K, G = int(rng.choice([1, 3, 8, 16, 20, 32, 64, 100, 256])), int(rng.choice([1, 4, 1024]))
+        mmax = max(1, min(200, 6000 // cmax))
+        X, seed, m0 = rand_matrix(V, cmax), int(rng.integers(0, 2 ** 62)), int(rng.choice([1, 3]))
+        o = oracle.OracleLDA(X, K, 0.1, 0.02, seed=seed, m0=m0, G=G)
+        g = make_gpu(X, K, 0.1, 0.02, seed, m0, G)
+        done = []
+        for s in range(int(rng.integers(3, 9))):
+            op = str(rng.choice(["sweep", "sweep", "poisson", "sampled", "set_batch", "stage", "loglik", "restore"]))
+            done.append(op)
+            what = f"sequence {c} (V={V} cmax={cmax} K={K} G={G}): {done}"
+            if op == "sweep":
+                m, rho = int(rng.integers(1, mmax + 1)), float(rng.choice([1.0, 0.6]))
+                o.sweep(m, rho); g.sweep(m, rho)
+            elif op == "poisson":
+                m = float(np.float32(rng.uniform(0.2, mmax)))
+                o.sweep_poisson(m); g.sweep_poisson(m)
+            elif op == "sampled":
+                m = int(rng.integers(1, mmax + 1))
+                o.sweep_sampled(m); g.sweep_sampled(m)
+            elif op == "set_batch":
+                B, mi = rand_matrix(V, cmax), int(rng.integers(1, 4))
+                o.set_batch(B, mi); g.set_batch(B.D, *arrays(B, str(rng.choice(["host", "device"]))), mi)
+            elif op == "stage":
+                B, mi = rand_matrix(V, cmax), int(rng.integers(1, 4))
+                announced, real = int(rng.integers(0, 3)), int(rng.integers(0, 3))
+                keep = arrays(B, str(rng.choice(["pinned", "device", "host"])))
+                g.stage_batch(B.D, *keep, mi, announced)
+                for _ in range(real):
+                    m = int(rng.integers(1, mmax + 1))
+                    o.sweep(m); g.sweep(m)
+                o.set_batch(B, mi); g.commit_batch()
+            elif op == "loglik":
+                T, f, me = rand_matrix(V, cmax), int(rng.integers(0, 3)), int(rng.integers(1, 10))
+                assert abs(g.loglik(T.D, T.colptr, T.rowidx, T.val, f, me) - o.loglik(T, f, me)) <= LL_ATOL, what
+                continue
+            else:
+                g.set(binding.THETA, o.theta); g.set(binding.PHI, o.phi); g.pass_index = o.t
+                continue
+            assert g.pass_index == o.t, what
+            assert_state_equal(g, o, what)
+        g.close()
+
+
 # The sampled parameter step (Algorithm 2, third step): theta and phi as Dirichlet draws
 @pytest.mark.parametrize("K,G,ms", [(16, 8, [10, 1, 3]), (40, 3, [100, 2]), (5, 1000, [400, 1])])
 def test_sampled_sweeps_match_the_oracle(K, G, ms):
