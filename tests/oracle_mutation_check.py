@@ -1,0 +1,99 @@
+"""Mutation check of the oracle's pins (CPU only, run by hand: `python tests/oracle_mutation_check.py`, ~10 min).
+
+One plausible mistake at a time (a dropped term, a wrong sign, index or operand) is planted in a COPY of
+oracle/same_lda_oracle.c under a temporary directory; the pins of tests/test_oracle_pins.py are run against
+the copy, and the mutants that no pin notices are listed.  Two of the mutants below change only which
+integers come out, not their distribution (which of two equally heavy topics keeps the remainder; the
+length of a binomial piece): they are build decisions that no mathematical pin can see and are expected
+to survive; every other one must be caught.  Not collected by pytest.
+"""
+import os
+import re
+import shutil
+import subprocess
+import sys
+import tempfile
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+EXPECTED_SURVIVORS = {"chain: heaviest = lowest index among ties", "binom: piece length wrong"}
+
+# (name, text in the oracle's source, its replacement); the first occurrence is replaced
+MUTS = [
+ ("chain: drop heaviest weight below h", "float M = (k > h) ? P[k] : P[k] + w[h];", "float M = P[k];"),
+ ("chain: heaviest = lowest index among ties", "if (w[k] >= w[h]) h = k;", "if (w[k] > w[h]) h = k;"),
+ ("chain: ascending order", "for (int32_t k = K - 1; k >= 0 && R > 0; --k) {", "for (int32_t k = 0; k < K && R > 0; ++k) {"),
+ ("chain: remainder not given to h", "counts[h] = R;", "counts[h] = 0;"),
+ ("chain: R not reduced", "        counts[k] = n;\n        R -= n;", "        counts[k] = n;"),
+ ("binom: complement not undone", "return flip ? R - total : total;", "return total;"),
+ ("binom: r = qq instead of qq/s", "float r = qq / s;", "float r = qq;"),
+ ("binom: piece length wrong", "uint32_t L = single ? R : (uint32_t)(32.0f / qq);", "uint32_t L = single ? R : (uint32_t)(16.0f / qq) + 7u;"),
+ ("binom: pieces share one uniform", "float u = stream_uniform(seed, tau, k, piece, pass);\n        total += oracle_binom_walk", "float u = stream_uniform(seed, tau, k, 0, pass);\n        total += oracle_binom_walk"),
+ ("walk: n-x instead of n-x+1", "pm = pm * (float)(n - x + 1u);", "pm = pm * (float)(n - x);"),
+ ("walk: starts cdf at 0", "float pm = pm0, cdf = pm0;\n    while (u > cdf && x < n) {", "float pm = pm0, cdf = 0.0f;\n    while (u > cdf && x < n) {"),
+ ("ipow: exponent off by one", "uint32_t e = n;\n    while (e > 0) {", "uint32_t e = n + 1u;\n    while (e > 0) {"),
+ ("uniform: can be 0", "(2u * (x >> 9) + 1u)", "(2u * (x >> 9))"),
+ ("stream: topic word index ignores k", "return oracle_uniform_from_word(out[k & 3u]);", "return oracle_uniform_from_word(out[0]);"),
+ ("weights: phi row of wrong word", "phi ? phi + (size_t)word * K : NULL, w);\n                uint32_t ntask", "phi ? phi + (size_t)((word + 1) % V) * K : NULL, w);\n                uint32_t ntask"),
+ ("weights: sum instead of product", "w[k] = theta_d[k] * phi_w[k];", "w[k] = theta_d[k] + phi_w[k];"),
+ ("pass: counts go to wrong topic", "ndk[(size_t)d * K + k] += cnt[k];", "ndk[(size_t)d * K + (K - 1 - k)] += cnt[k];"),
+ ("pass: N ignores group size", "oracle_draw(K, w, m * g, seed, (uint64_t)(base[i] + j), pass, cnt, scratch);\n                    if (mu", "oracle_draw(K, w, m, seed, (uint64_t)(base[i] + j), pass, cnt, scratch);\n                    if (mu"),
+ ("update: theta multiplied by m", "float avg = (float)ndk[e] / mf;", "float avg = (float)ndk[e] * mf;"),
+ ("update: alpha dropped", "theta[e] = avg + alpha;", "theta[e] = avg;"),
+ ("update: V*beta -> beta", "float vbeta = (float)V * beta;", "float vbeta = beta;"),
+ ("update: blend weights swapped", "float keep = one_minus_rho * phi[(size_t)w * K + k];\n                float add = rho * hat;", "float keep = rho * phi[(size_t)w * K + k];\n                float add = one_minus_rho * hat;"),
+ ("update: nk over wrong axis", "for (int32_t w = 0; w < V; ++w) nk += nwk[(size_t)w * K + k];", "for (int32_t w = 0; w < V; ++w) nk += nwk[(size_t)w * K + (k + 1) % K];"),
+ ("loglik: theta total not removed", "total += (double)val[i] * (log((double)S) - log_tsum);", "total += (double)val[i] * (log((double)S));"),
+ ("loglik: unweighted by count", "total += (double)val[i] * (log((double)S) - log_tsum);\n            tokens += (double)val[i];", "total += (log((double)S) - log_tsum);\n            tokens += 1.0;"),
+ ("poisson: rate ignores Nf", "float scaled = Nf * w[k];", "float scaled = w[k];"),
+ ("poisson: one piece too few", "J = (uint32_t)(lambda / 32.0f) + 1u;\n        rate = lambda / (float)J;", "J = (uint32_t)(lambda / 32.0f) + 1u;\n        rate = lambda / (float)(J + 1u);"),
+ ("poisson walk: divides by x+1", "float inv_x = 1.0f / (float)x;\n        pm = pm * rate;", "float inv_x = 1.0f / (float)(x + 1u);\n        pm = pm * rate;"),
+ ("expneg: wrong log2e", "1.4426950408889634f", "1.4326950408889634f"),
+ ("gamma: d = a", "float d = a1 - 0.333333343f;", "float d = a1;"),
+ ("gamma: c from 3d", "float nine_d = 9.0f * d;", "float nine_d = 3.0f * d;"),
+ ("gamma: accept test sign", "accept = lhs < rhs;", "accept = lhs > rhs;"),
+ ("gamma: small shape boost uses 1/(a+1)", "y = y / a;", "y = y / a1;"),
+ ("gamma: v squared not cubed", "float v = t * t;\n        v = v * t;", "float v = t * t;"),
+ ("normal: sine instead of cosine quadrant 0", "case 0:  return cs;", "case 0:  return sn;"),
+ ("flog: ln2 wrong", "0.693147182f", "0.683147182f"),
+ ("theta_sample: not divided by m", "theta[(size_t)d * K + k] = g / mf;", "theta[(size_t)d * K + k] = g;"),
+ ("theta_sample: prior alpha not m*alpha", "float prior = mf * alpha;", "float prior = alpha;"),
+ ("phi_sample: normalised over topics of a word", "float den = (float)total;", "float den = 1.0f;"),
+]
+
+
+def run_mutant(src: str, work: str, old: str, new: str):
+    """Builds a tree with the mutated oracle under work/ and runs the pins there; returns (caught, first failure)."""
+    shutil.rmtree(work, ignore_errors=True)
+    os.makedirs(work)
+    shutil.copytree(os.path.join(ROOT, "oracle"), os.path.join(work, "oracle"),
+                    ignore=shutil.ignore_patterns("*.so", "__pycache__"))
+    shutil.copytree(os.path.join(ROOT, "tests"), os.path.join(work, "tests"), ignore=shutil.ignore_patterns("__pycache__"))
+    os.symlink(os.path.join(ROOT, "paper_1409_5402_amd"), os.path.join(work, "paper_1409_5402_amd"))
+    with open(os.path.join(work, "oracle", "same_lda_oracle.c"), "w") as f:
+        f.write(src.replace(old, new, 1))
+    r = subprocess.run([sys.executable, "-m", "pytest", "tests/test_oracle_pins.py", "-x", "-q", "-p", "no:cacheprovider"],
+                       cwd=work, capture_output=True, text=True)
+    m = re.search(r"FAILED tests/test_oracle_pins.py::(\S+)", r.stdout)
+    return r.returncode != 0, (m.group(1) if m else "")
+
+
+def main():
+    src = open(os.path.join(ROOT, "oracle", "same_lda_oracle.c")).read()
+    base = tempfile.mkdtemp(prefix="oracle_mutants_")
+    survivors = []
+    for name, old, new in MUTS:
+        if old not in src:
+            sys.exit(f"the text of mutant '{name}' is no longer in the oracle: update this list")
+        caught, first = run_mutant(src, os.path.join(base, "w"), old, new)
+        print(("caught   " if caught else "SURVIVED ") + name + (f"  [{first}]" if first else ""), flush=True)
+        if not caught:
+            survivors.append(name)
+    shutil.rmtree(base, ignore_errors=True)
+    print("survivors:", survivors)
+    unexpected = sorted(set(survivors) - EXPECTED_SURVIVORS)
+    if unexpected:
+        sys.exit(f"no pin notices: {unexpected}")
+
+
+if __name__ == "__main__":
+    main()
