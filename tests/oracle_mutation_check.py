@@ -58,6 +58,16 @@ MUTS = [
  ("theta_sample: not divided by m", "theta[(size_t)d * K + k] = g / mf;", "theta[(size_t)d * K + k] = g;"),
  ("theta_sample: prior alpha not m*alpha", "float prior = mf * alpha;", "float prior = alpha;"),
  ("phi_sample: normalised over topics of a word", "float den = (float)total;", "float den = 1.0f;"),
+ ("tasks: one task too many per nonzero", "return (ci + (uint32_t)G - 1u) / (uint32_t)G;", "return ci / (uint32_t)G + 1u;"),
+ ("sddmm: theta row of the wrong document", "const float* t = theta + (size_t)d * K;\n            const float* p = phi + (size_t)rowidx[i] * K;\n            double acc", "const float* t = theta + (size_t)((d + 1) % D) * K;\n            const float* p = phi + (size_t)rowidx[i] * K;\n            double acc"),
+ ("sddmm: sum of squares of theta", "acc += (double)t[k] * (double)p[k];", "acc += (double)t[k] * (double)t[k];"),
+ ("poisson: rate not normalised", "float lambda = scaled / mu;", "float lambda = scaled;"),
+ ("poisson pass: copies ignore the group size", "float Nf = m * (float)g;", "float Nf = m;"),
+ ("update: beta dropped from the numerator", "float num = avg + beta;", "float num = avg;"),
+ ("loglik: inner product with phi of the wrong word", "const float* ph = phi + (size_t)rowidx[i] * K;\n            const float* th = theta + (size_t)d * K;", "const float* ph = phi + (size_t)rowidx[colptr[d]] * K;\n            const float* th = theta + (size_t)d * K;"),
+ ("phi_sample: prior beta not m*beta", "float prior = mf * beta;", "float prior = beta;"),
+ ("gamma: fallback boost uses the acceptance uniform", "float l = oracle_flog(oracle_uniform_from_word(out[3]));", "float l = oracle_flog(oracle_uniform_from_word(out[2]));"),
+ ("normal: radius without the factor two", "float r2 = -2.0f * l;", "float r2 = -1.0f * l;"),
 ]
 
 
