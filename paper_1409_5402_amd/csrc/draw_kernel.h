@@ -470,8 +470,9 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
 // one word have their large counts at the same topics, and aligned walks would meet at one address.
 constexpr int kReduceChunk = 2048;
 constexpr int kSlotMinTasks = 32;
+constexpr int kReduceThreads = 1024;    // two slots per thread: the kernel waits on its loads, many waves hide that
 
-__global__ __launch_bounds__(256) void word_reduce_kernel(const uint32_t* __restrict__ pairs,
+__global__ __launch_bounds__(kReduceThreads) void word_reduce_kernel(const uint32_t* __restrict__ pairs,
                                                           const int32_t* __restrict__ slot_word, int64_t n, int K,
                                                           int rows, uint32_t* __restrict__ nwk)
 {
@@ -487,7 +488,7 @@ __global__ __launch_bounds__(256) void word_reduce_kernel(const uint32_t* __rest
         const bool in_tab = w - w0 < rows;
         uint32_t* dst = in_tab ? tab + (size_t)(w - w0) * K : nwk + (size_t)w * K;
         const uint32_t cnt = src[0];
-        uint32_t idx = (threadIdx.x * cnt) >> 8;                   // start somewhere in [0, cnt)
+        uint32_t idx = ((threadIdx.x & 255u) * cnt) >> 8;          // start somewhere in [0, cnt)
         for (uint32_t i = 0; i < cnt; ++i) {
             const uint32_t p = src[1u + idx];
             idx = idx + 1u == cnt ? 0u : idx + 1u;

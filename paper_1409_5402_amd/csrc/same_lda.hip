@@ -497,7 +497,7 @@ int run_pass(same_lda* h, Matrix& M, Copies c, uint32_t pword, bool uniform, boo
     if (a.pairs && a.n > 0) {
         const int rows = same::reduce_rows(h->K);
         const int64_t blocks = (M.n_slots + same::kReduceChunk - 1) / same::kReduceChunk;
-        hipLaunchKernelGGL(same::word_reduce_kernel, dim3((unsigned)blocks), dim3(256),
+        hipLaunchKernelGGL(same::word_reduce_kernel, dim3((unsigned)blocks), dim3(same::kReduceThreads),
                            (size_t)rows * h->K * sizeof(uint32_t), st, a.pairs, M.slot_word, M.n_slots, h->K, rows,
                            h->nwk);
         HIP_TRY(h, hipGetLastError());
