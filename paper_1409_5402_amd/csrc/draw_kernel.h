@@ -489,10 +489,16 @@ __global__ __launch_bounds__(kReduceThreads) void word_reduce_kernel(const uint3
         uint32_t* dst = in_tab ? tab + (size_t)(w - w0) * K : nwk + (size_t)w * K;
         const uint32_t cnt = src[0];
         uint32_t idx = ((threadIdx.x & 255u) * cnt) >> 8;          // start somewhere in [0, cnt)
-        for (uint32_t i = 0; i < cnt; ++i) {
-            const uint32_t p = src[1u + idx];
-            idx = idx + 1u == cnt ? 0u : idx + 1u;
-            atomicAdd(dst + (p & ((1u << kPairShift) - 1u)), p >> kPairShift);
+        for (uint32_t i = 0; i < cnt; i += 4u) {                   // four loads in flight, then their updates
+            uint32_t p[4];
+#pragma unroll
+            for (uint32_t j = 0; j < 4u; ++j) {
+                p[j] = (i + j < cnt) ? src[1u + idx] : 0u;
+                idx = idx + 1u >= cnt ? 0u : idx + 1u;
+            }
+#pragma unroll
+            for (uint32_t j = 0; j < 4u; ++j)
+                if (i + j < cnt) atomicAdd(dst + (p[j] & ((1u << kPairShift) - 1u)), p[j] >> kPairShift);
         }
     }
     __syncthreads();
