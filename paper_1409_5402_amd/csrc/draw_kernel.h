@@ -405,97 +405,54 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
         }
     };
 
-    // ---- pass 2: blocks from last to first.  The random words of a block are drawn one block ahead of
-    // its weights: if the drop test already holds for the block's largest word with the whole block's
-    // weight in the place of a topic's (and the smallest undecided weight any of its topics can see),
-    // none of the lane's sixteen topics can receive a copy and the lane does not load the block at all.
-    // The block's weight is bounded from the two checkpoints around it: the sixteen rounded additions
-    // between them lose at most 16 * 2^-24 of the upper checkpoint, the subtraction 2^-24 more.
+    // ---- pass 2: blocks from last to first
     {
+        PhiBlock cur = load_phi<UNIFORM, VEC>(th, ph, nblk - 1);
         ZeroTest zt(POISSON ? Nf : (float)R);   // R bounds the remaining count from here on
-        uint32_t xc[kBlk], xn[kBlk];
-        auto block_words = [&](int blk, uint32_t (&xs)[kBlk]) {
-#pragma unroll
-            for (int g = 0; g < kBlk / 4; ++g) {
-                uint32_t t[4];
-                primary_block(key, pre, (uint32_t)(blk * (kBlk / 4) + g), t);
-                xs[4 * g + 0] = t[0]; xs[4 * g + 1] = t[1]; xs[4 * g + 2] = t[2]; xs[4 * g + 3] = t[3];
-            }
-        };
-        auto skippable = [&](int blk, const uint32_t (&xs)[kBlk]) -> bool {
-            if (UNIFORM) return false;
-            if (R == 0) return true;                               // nothing left to place
-            const float Ps = chk[blk * kWave + lane];
-            const float Pe = (blk + 1 < nblk) ? chk[(blk + 1) * kWave + lane] : mu;
-            const float Sup = (Pe - Ps) + Pe * 1.9073486328125e-6f;
-            const float Mlow = POISSON ? mu : Ps + ((blk * kBlk + kBlk - 1) < kstar ? wmax : 0.0f);
-            uint32_t xm = xs[0];
-#pragma unroll
-            for (int j = 1; j < kBlk; ++j) xm = xs[j] > xm ? xs[j] : xm;
-            return zt.surely_zero(Sup, Mlow, xm);
-        };
-        block_words(nblk - 1, xc);
-        bool skc = skippable(nblk - 1, xc);
-        PhiBlock cur{};
-        if (!skc) cur = load_phi<UNIFORM, VEC>(th, ph, nblk - 1);
         for (int b = nblk - 1; b >= 0; --b) {
             if (!__any(R > 0)) break;
             PhiBlock nxt = cur;
-            bool skn = true;
-            if (b > 0) {
-                block_words(b - 1, xn);
-                skn = skippable(b - 1, xn);
-                if (!skn) nxt = load_phi<UNIFORM, VEC>(th, ph, b - 1);
-            }
-            if (__any(!skc)) {
-                float wv[kBlk], Pv[kBlk];
-                if (VEC || !skc) {
-                    block_weights<UNIFORM, VEC>(th, ph, cur, b, K, wv);
-                } else {
-#pragma unroll
-                    for (int j = 0; j < kBlk; ++j) wv[j] = 0.0f;
-                }
-                {
-                    float P = chk[b * kWave + lane];
-#pragma unroll
-                    for (int j = 0; j < kBlk; ++j) { P = P + wv[j]; Pv[j] = P; }
-                }
-#pragma unroll
-                for (int g = kBlk / 4 - 1; g >= 0; --g) {
-#pragma unroll
-                    for (int j = 3; j >= 0; --j) {
-                        const int k = b * kBlk + g * 4 + j;
-                        const float wk = wv[g * 4 + j];
-                        const uint32_t xk = xc[g * 4 + j];
-                        const float Mk = POISSON ? mu : Pv[g * 4 + j] + (k < kstar ? wmax : 0.0f);   // weight not yet decided at k
-                        // a zero weight passes the test; the heaviest topic may be queued: the chain skips it
-                        const bool cand = !skc && (VEC || k < K) && !zt.surely_zero(wk, Mk, xk);
-                        if (cand) {
-                            int e = qh + cnt;
-                            e = e >= kQCap ? e - kQCap : e;
-                            que[(e * qw + 0) * kWave + lane] = __float_as_uint(wk);
-                            que[(e * qw + 1) * kWave + lane] = __float_as_uint(Mk);
-                            if (qw == 3) {
-                                que[(e * qw + 2) * kWave + lane] = (xk & ~511u) | (uint32_t)k;   // the uniform uses the top 23 bits
-                            } else {
-                                que[(e * qw + 2) * kWave + lane] = xk;
-                                que[(e * qw + 3) * kWave + lane] = (uint32_t)k;
-                            }
-                            cnt += 1;
-                            SAME_COUNT(a, 1, 1);                   // queued topics
-                        }
-                    }
-                    // trips are run only while some lane could not take the next four topics
-                    if (__any(cnt > kQCap - 4)) {
-                        do { trip(); } while (__any(cnt > kQCap - 4));
-                        if (!POISSON) zt = ZeroTest((float)R);
-                    }
-                }
-            }
+            if (b > 0) nxt = load_phi<UNIFORM, VEC>(th, ph, b - 1);
+            float wv[kBlk], Pv[kBlk];
+            block_weights<UNIFORM, VEC>(th, ph, cur, b, K, wv);
             cur = nxt;
-            skc = skn;
+            {
+                float P = chk[b * kWave + lane];
 #pragma unroll
-            for (int j = 0; j < kBlk; ++j) xc[j] = xn[j];
+                for (int j = 0; j < kBlk; ++j) { P = P + wv[j]; Pv[j] = P; }
+            }
+#pragma unroll
+            for (int g = kBlk / 4 - 1; g >= 0; --g) {
+                uint32_t x[4];
+                primary_block(key, pre, (uint32_t)(b * (kBlk / 4) + g), x);
+#pragma unroll
+                for (int j = 3; j >= 0; --j) {
+                    const int k = b * kBlk + g * 4 + j;
+                    const float wk = wv[g * 4 + j];
+                    const float Mk = POISSON ? mu : Pv[g * 4 + j] + (k < kstar ? wmax : 0.0f);   // weight not yet decided at k
+                    // a zero weight passes the test; the heaviest topic may be queued: the chain skips it
+                    const bool cand = (VEC || k < K) && !zt.surely_zero(wk, Mk, x[j]);
+                    if (cand) {
+                        int e = qh + cnt;
+                        e = e >= kQCap ? e - kQCap : e;
+                        que[(e * qw + 0) * kWave + lane] = __float_as_uint(wk);
+                        que[(e * qw + 1) * kWave + lane] = __float_as_uint(Mk);
+                        if (qw == 3) {
+                            que[(e * qw + 2) * kWave + lane] = (x[j] & ~511u) | (uint32_t)k;   // the uniform uses the top 23 bits
+                        } else {
+                            que[(e * qw + 2) * kWave + lane] = x[j];
+                            que[(e * qw + 3) * kWave + lane] = (uint32_t)k;
+                        }
+                        cnt += 1;
+                        SAME_COUNT(a, 1, 1);                       // queued topics
+                    }
+                }
+                // trips are run only while some lane could not take the next four topics
+                if (__any(cnt > kQCap - 4)) {
+                    do { trip(); } while (__any(cnt > kQCap - 4));
+                    if (!POISSON) zt = ZeroTest((float)R);
+                }
+            }
         }
     }
     while (__any(st != 0 || (cnt > 0 && R > 0))) trip();
