@@ -33,7 +33,7 @@
 namespace same {
 
 #ifndef SAME_QCAP
-#define SAME_QCAP 12
+#define SAME_QCAP 8
 #endif
 #ifndef SAME_WALK_STEPS
 #define SAME_WALK_STEPS 4
@@ -172,10 +172,11 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
     const int K = a.K;
     const int nblk = (K + kBlk - 1) / kBlk;
     const int qw = K <= 512 ? 3 : 4;                               // words per queue entry
-    float*    chk = reinterpret_cast<float*>(lds);                 // [nblk][64]
+    uint32_t* chk = lds;                                           // [nblk][64] checkpoints (binary32 bits)
     uint32_t* que = lds + (size_t)nblk * kWave;                    // [kQCap][qw][64], a ring per lane
-    uint32_t* acc = que + (size_t)kQCap * qw * kWave;              // [64] piece totals by owner lane
-    acc[lane] = 0u;
+    // [64] piece totals by owner lane: they take the place of the last block's checkpoint, which pass 2
+    // reads first and never again (it is cleared right after that read, before any trip can run)
+    uint32_t* acc = lds + (size_t)(nblk - 1) * kWave;
 
     // lanes past the end take the last task with zero copies: all loads stay valid, nothing is emitted
     const int64_t slot = (int64_t)blockIdx.x * kWave + lane;
@@ -208,7 +209,7 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
         for (int b = 0; b < nblk; ++b) {
             PhiBlock nxt = cur;
             if (b + 1 < nblk) nxt = load_phi<UNIFORM, VEC>(th, ph, b + 1);
-            chk[b * kWave + lane] = P;
+            chk[b * kWave + lane] = __float_as_uint(P);
             float wv[kBlk];
             block_weights<UNIFORM, VEC>(th, ph, cur, b, K, wv);
 #pragma unroll
@@ -417,7 +418,8 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
             block_weights<UNIFORM, VEC>(th, ph, cur, b, K, wv);
             cur = nxt;
             {
-                float P = chk[b * kWave + lane];
+                float P = __uint_as_float(chk[b * kWave + lane]);
+                if (b == nblk - 1) acc[lane] = 0u;
 #pragma unroll
                 for (int j = 0; j < kBlk; ++j) { P = P + wv[j]; Pv[j] = P; }
             }
@@ -515,7 +517,7 @@ inline size_t draw_lds_bytes(int K)
 {
     const int nblk = (K + kBlk - 1) / kBlk;
     const int qw = K <= 512 ? 3 : 4;
-    return 4u * (size_t)kWave * (size_t)(nblk + qw * kQCap + 1);
+    return 4u * (size_t)kWave * (size_t)(nblk + qw * kQCap);
 }
 
 }  // namespace same
