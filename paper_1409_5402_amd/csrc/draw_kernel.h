@@ -36,7 +36,7 @@ namespace same {
 #define SAME_QCAP 8
 #endif
 #ifndef SAME_WALK_STEPS
-#define SAME_WALK_STEPS 4
+#define SAME_WALK_STEPS 8
 #endif
 constexpr int kWave = 64;               // lanes per workgroup (one wave)
 constexpr int kBlk = 16;                // topics per checkpoint block
