@@ -171,9 +171,11 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
     const int lane = threadIdx.x;
     const int K = a.K;
     const int nblk = (K + kBlk - 1) / kBlk;
-    const int qw = K <= 512 ? 3 : 4;                               // words per queue entry
+    constexpr int qw = 3;                                          // words per queue entry
     uint32_t* chk = lds;                                           // [nblk][64] checkpoints (binary32 bits)
     uint32_t* que = lds + (size_t)nblk * kWave;                    // [kQCap][qw][64], a ring per lane
+    static_assert(kQCap <= 16, "two bits per ring slot in one register");
+    uint32_t khi = 0;       // bits 9 and 10 of the topic queued in each ring slot (the entry holds the low nine)
     // [64] piece totals by owner lane: they take the place of the last block's checkpoint, which pass 2
     // reads first and never again (it is cleared right after that read, before any trip can run)
     uint32_t* acc = lds + (size_t)(nblk - 1) * kWave;
@@ -326,7 +328,7 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
                 wq = __uint_as_float(que[(qh * qw + 0) * kWave + lane]);
                 Mq = __uint_as_float(que[(qh * qw + 1) * kWave + lane]);
                 const uint32_t xk = que[(qh * qw + 2) * kWave + lane];
-                kk = qw == 3 ? (int)(xk & 511u) : (int)que[(qh * qw + 3) * kWave + lane];
+                kk = (int)((xk & 511u) | (((khi >> (2 * qh)) & 3u) << 9));
                 u = uniform_from_word(xk);
                 qh = (qh + 1 == kQCap) ? 0 : qh + 1;
                 --cnt;
@@ -439,12 +441,8 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
                         e = e >= kQCap ? e - kQCap : e;
                         que[(e * qw + 0) * kWave + lane] = __float_as_uint(wk);
                         que[(e * qw + 1) * kWave + lane] = __float_as_uint(Mk);
-                        if (qw == 3) {
-                            que[(e * qw + 2) * kWave + lane] = (x[j] & ~511u) | (uint32_t)k;   // the uniform uses the top 23 bits
-                        } else {
-                            que[(e * qw + 2) * kWave + lane] = x[j];
-                            que[(e * qw + 3) * kWave + lane] = (uint32_t)k;
-                        }
+                        que[(e * qw + 2) * kWave + lane] = (x[j] & ~511u) | ((uint32_t)k & 511u);   // the uniform uses the top 23 bits
+                        khi = (khi & ~(3u << (2 * e))) | (((uint32_t)k >> 9) << (2 * e));
                         cnt += 1;
                         SAME_COUNT(a, 1, 1);                       // queued topics
                     }
@@ -516,8 +514,7 @@ inline int reduce_rows(int K) { const int r = 16384 / K; return r < 1 ? 1 : (r >
 inline size_t draw_lds_bytes(int K)
 {
     const int nblk = (K + kBlk - 1) / kBlk;
-    const int qw = K <= 512 ? 3 : 4;
-    return 4u * (size_t)kWave * (size_t)(nblk + qw * kQCap);
+    return 4u * (size_t)kWave * (size_t)(nblk + 3 * kQCap);
 }
 
 }  // namespace same

@@ -260,8 +260,8 @@ def test_empty_matrix():
 
 @pytest.mark.parametrize("K", [1024, 2048])
 def test_many_topics_news_shape(K):
-    """K=1024 (the many-topics workload) and the largest supported K: queue entries switch to four
-    words above K=512 and the checkpoint area grows; news-shaped slice, m=100."""
+    """K=1024 (the many-topics workload) and the largest supported K: above K=512 the high bits of a queued
+    topic live in a register beside the queue, and the checkpoint area grows; news-shaped slice, m=100."""
     X = corpus_to_csc(synth.preset("news_k1024", scale=0.0004))
     alpha = 50.0 / K
     o = oracle.OracleLDA(X, K, alpha, 0.01, seed=11, m0=1, G=32)
