@@ -372,8 +372,7 @@ class OracleLDA:
         self.X = X
         self.ndk, _, _ = run_pass(X, self.K, self.G, m_init, self.seed, pass_word(self.t), None, None,
                                   want_nwk=False)
-        self.nwk = None
-        self.theta = theta_update(self.ndk, m_init, self.alpha)
+        self.theta = theta_update(self.ndk, m_init, self.alpha)      # phi and n_wk stay as the last sweep left them
         self.t += 1
 
     def loglik(self, Xtest: CSC, foldin_sweeps: int, m_eval: int) -> float:

@@ -1,11 +1,11 @@
-"""Mutation check of the oracle's pins (CPU only, run by hand: `python tests/oracle_mutation_check.py`, ~10 min).
+"""Mutation check of the oracle's pins (CPU only, about ten minutes: marked `slow` and skipped unless
+SAME_LDA_SLOW=1 is set; `python tests/test_oracle_mutants.py` runs it by hand and prints every mutant).
 
 One plausible mistake at a time (a dropped term, a wrong sign, index or operand) is planted in a COPY of
-oracle/same_lda_oracle.c under a temporary directory; the pins of tests/test_oracle_pins.py are run against
-the copy, and the mutants that no pin notices are listed.  Two of the mutants below change only which
-integers come out, not their distribution (which of two equally heavy topics keeps the remainder; the
-length of a binomial piece): they are build decisions that no mathematical pin can see and are expected
-to survive; every other one must be caught.  Not collected by pytest.
+the oracle (oracle/same_lda_oracle.c or oracle/__init__.py) under a temporary directory; the pins of
+tests/test_oracle_pins.py are run against the copy, and the mutants that no pin notices are listed.  The
+mutants named in EXPECTED_SURVIVORS change only which integers come out, not their distribution: they are
+build decisions that no mathematical pin can see and are expected to survive; every other one must be caught.
 """
 import os
 import re
@@ -14,10 +14,37 @@ import subprocess
 import sys
 import tempfile
 
+import pytest
+
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 EXPECTED_SURVIVORS = {"chain: heaviest = lowest index among ties", "binom: piece length wrong"}
 
-# (name, text in the oracle's source, its replacement); the first occurrence is replaced
+C_FILE, PY_FILE = "same_lda_oracle.c", "__init__.py"
+
+# mistakes in the Python class that strings the steps together: (name, text in oracle/__init__.py, replacement)
+PY_MUTS = [
+ ("set_batch: phi recomputed from the uniform pass",
+  "        self.ndk, _, _ = run_pass(X, self.K, self.G, m_init, self.seed, pass_word(self.t), None, None,\n                                  want_nwk=False)\n        self.theta = theta_update(self.ndk, m_init, self.alpha)",
+  "        self.ndk, self.nwk, _ = run_pass(X, self.K, self.G, m_init, self.seed, pass_word(self.t), None, None)\n        self.phi = phi_update(self.nwk, m_init, self.beta, 1.0, None)\n        self.theta = theta_update(self.ndk, m_init, self.alpha)"),
+ ("set_batch: pass index not advanced",
+  "        self.theta = theta_update(self.ndk, m_init, self.alpha)      # phi and n_wk stay as the last sweep left them\n        self.t += 1",
+  "        self.theta = theta_update(self.ndk, m_init, self.alpha)      # phi and n_wk stay as the last sweep left them"),
+ ("set_batch: theta divided by the wrong m",
+  "        self.theta = theta_update(self.ndk, m_init, self.alpha)      # phi",
+  "        self.theta = theta_update(self.ndk, 1, self.alpha)      # phi"),
+ ("set_batch: initial pass weighted by the old model",
+  "pass_word(self.t), None, None,\n                                  want_nwk=False)\n        self.theta = theta_update(self.ndk, m_init",
+  "pass_word(self.t), np.ones((X.D, self.K), np.float32), self.phi,\n                                  want_nwk=False)\n        self.theta = theta_update(self.ndk, m_init"),
+ ("set_batch: the old minibatch stays resident", "        self.X = X\n        self.ndk, _, _ = run_pass(X,", "        self.ndk, _, _ = run_pass(X,"),
+ ("sweep: blend ignored", "self.phi = phi_update(self.nwk, m, self.beta, rho, self.phi)\n        self.t += 1\n\n    def sweep_sampled",
+  "self.phi = phi_update(self.nwk, m, self.beta, 1.0, self.phi)\n        self.t += 1\n\n    def sweep_sampled"),
+ ("sweep: pass index not advanced", "self.phi = phi_update(self.nwk, m, self.beta, rho, self.phi)\n        self.t += 1\n\n    def sweep_sampled",
+  "self.phi = phi_update(self.nwk, m, self.beta, rho, self.phi)\n\n    def sweep_sampled"),
+ ("loglik: fold-in never updates theta", "                                 theta, self.phi, want_nwk=False)\n            theta = theta_update(ndk, m_eval, self.alpha)",
+  "                                 theta, self.phi, want_nwk=False)"),
+]
+
+# (name, text in the oracle's C source, its replacement); the first occurrence is replaced
 MUTS = [
  ("chain: drop heaviest weight below h", "float M = (k > h) ? P[k] : P[k] + w[h];", "float M = P[k];"),
  ("chain: heaviest = lowest index among ties", "if (w[k] >= w[h]) h = k;", "if (w[k] > w[h]) h = k;"),
@@ -71,7 +98,7 @@ MUTS = [
 ]
 
 
-def run_mutant(src: str, work: str, old: str, new: str):
+def run_mutant(fname: str, src: str, work: str, old: str, new: str):
     """Builds a tree with the mutated oracle under work/ and runs the pins there; returns (caught, first failure)."""
     shutil.rmtree(work, ignore_errors=True)
     os.makedirs(work)
@@ -79,7 +106,7 @@ def run_mutant(src: str, work: str, old: str, new: str):
                     ignore=shutil.ignore_patterns("*.so", "__pycache__"))
     shutil.copytree(os.path.join(ROOT, "tests"), os.path.join(work, "tests"), ignore=shutil.ignore_patterns("__pycache__"))
     os.symlink(os.path.join(ROOT, "paper_1409_5402_amd"), os.path.join(work, "paper_1409_5402_amd"))
-    with open(os.path.join(work, "oracle", "same_lda_oracle.c"), "w") as f:
+    with open(os.path.join(work, "oracle", fname), "w") as f:
         f.write(src.replace(old, new, 1))
     r = subprocess.run([sys.executable, "-m", "pytest", "tests/test_oracle_pins.py", "-x", "-q", "-p", "no:cacheprovider"],
                        cwd=work, capture_output=True, text=True)
@@ -87,23 +114,44 @@ def run_mutant(src: str, work: str, old: str, new: str):
     return r.returncode != 0, (m.group(1) if m else "")
 
 
-def main():
-    src = open(os.path.join(ROOT, "oracle", "same_lda_oracle.c")).read()
+def check(verbose: bool):
+    """Returns (survivors, stale): mutants no pin notices, and mutants whose text is no longer in the oracle."""
     base = tempfile.mkdtemp(prefix="oracle_mutants_")
-    survivors = []
-    for name, old, new in MUTS:
-        if old not in src:
-            sys.exit(f"the text of mutant '{name}' is no longer in the oracle: update this list")
-        caught, first = run_mutant(src, os.path.join(base, "w"), old, new)
-        print(("caught   " if caught else "SURVIVED ") + name + (f"  [{first}]" if first else ""), flush=True)
-        if not caught:
-            survivors.append(name)
+    survivors, stale = [], []
+    for fname, muts in ((C_FILE, MUTS), (PY_FILE, PY_MUTS)):
+        src = open(os.path.join(ROOT, "oracle", fname)).read()
+        for name, old, new in muts:
+            if old not in src:
+                stale.append(name)
+                continue
+            caught, first = run_mutant(fname, src, os.path.join(base, "w"), old, new)
+            if verbose:
+                print(("caught   " if caught else "SURVIVED ") + name + (f"  [{first}]" if first else ""), flush=True)
+            if not caught:
+                survivors.append(name)
     shutil.rmtree(base, ignore_errors=True)
-    print("survivors:", survivors)
-    unexpected = sorted(set(survivors) - EXPECTED_SURVIVORS)
-    if unexpected:
-        sys.exit(f"no pin notices: {unexpected}")
+    return survivors, stale
+
+
+@pytest.mark.slow
+@pytest.mark.skipif(os.environ.get("SAME_LDA_SLOW") != "1", reason="about ten minutes: set SAME_LDA_SLOW=1 to run")
+def test_every_planted_mistake_is_noticed_by_a_pin():
+    survivors, stale = check(verbose=False)
+    assert not stale, f"the text of these mutants is no longer in the oracle: {stale}"
+    assert sorted(set(survivors) - EXPECTED_SURVIVORS) == []
+
+
+def test_mutant_texts_are_current():
+    """Cheap guard, always run: every mutant still names text that is in the oracle's sources."""
+    for fname, muts in ((C_FILE, MUTS), (PY_FILE, PY_MUTS)):
+        src = open(os.path.join(ROOT, "oracle", fname)).read()
+        missing = [name for name, old, _ in muts if old not in src]
+        assert not missing, (fname, missing)
 
 
 if __name__ == "__main__":
-    main()
+    survivors, stale = check(verbose=True)
+    print("survivors:", survivors, "stale:", stale)
+    unexpected = sorted(set(survivors) - EXPECTED_SURVIVORS)
+    if unexpected or stale:
+        sys.exit(f"no pin notices: {unexpected}; stale: {stale}")

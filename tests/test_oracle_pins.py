@@ -343,6 +343,56 @@ def test_large_topic_totals_convert_correctly():
 
 
 # --------------------------------------------------------------------------- #
+# a new minibatch (Section 5.2: the model is kept, the data changes)
+def test_set_batch_keeps_the_model_and_initialises_the_new_documents():
+    """After set_batch: phi and n_wk are bit-identical to before, the pass index has advanced by one, every new
+    document holds m_init copies per token (Eq. 7: its counts total m_init * N_d) spread by a uniform-weight
+    pass, theta = n_dk / m_init + alpha; and the next sweep draws from the new documents with the kept phi."""
+    ca, Xa = _toy(seed=21, D=9, V=14, density=0.5)
+    cb, Xb = _toy(seed=22, D=6, V=14, density=0.6)
+    K, alpha, beta = 5, 0.1, 0.01
+    o = oracle.OracleLDA(Xa, K, alpha, beta, seed=3, m0=4)
+    o.sweep(6)
+    phi0, nwk0, t0 = o.phi.copy(), o.nwk.copy(), o.t
+    o.set_batch(Xb, 8)
+    assert o.t == t0 + 1
+    assert np.array_equal(o.phi, phi0) and np.array_equal(o.nwk, nwk0)
+    assert o.X is Xb and o.ndk.shape == (Xb.D, K) and o.theta.shape == (Xb.D, K)
+    assert np.array_equal(o.ndk.sum(axis=1), 8 * cb.sum(axis=1))
+    assert np.allclose(o.theta, o.ndk / 8.0 + alpha, rtol=1e-6)
+    assert o.theta[3, 0] == np.float32(alpha)                        # the empty document of the new minibatch
+    # the uniform pass ignores phi: topic shares of the new documents are flat (chi-square over all copies)
+    tot = o.ndk.sum(axis=0).astype(np.float64)
+    assert stats.chisquare(tot).pvalue > 1e-4
+    # its stream is the training stream at the pass index it took: the same pass drawn directly
+    ndk_ref, _, _ = oracle.run_pass(Xb, K, o.G, 8, 3, PW(t0), None, None, want_nwk=False)
+    assert np.array_equal(o.ndk, ndk_ref)
+    # the following sweep uses the kept phi: word w of the new minibatch goes where phi0[w] is large
+    o.sweep(5, 1.0)
+    assert o.t == t0 + 2
+    assert np.array_equal(o.ndk.sum(axis=1), 5 * cb.sum(axis=1))
+    assert np.array_equal(o.nwk.sum(axis=1), 5 * cb.sum(axis=0))
+
+
+def test_set_batch_then_blend_closed_form_K1():
+    """K = 1 after a new minibatch: phi_hat_w = (tok_B(w) + beta) / (tokens_B + V beta) and the blend of
+    Algorithm 3's last line gives phi = (1 - rho) phi_A + rho phi_hat, with phi_A from the first minibatch."""
+    ca, Xa = _toy(seed=23, D=8, V=11, density=0.5)
+    cb, Xb = _toy(seed=24, D=5, V=11, density=0.7)
+    alpha, beta, rho = 0.1, 0.01, float(np.float32(0.25))
+    o = oracle.OracleLDA(Xa, 1, alpha, beta, seed=1, m0=3)
+    phi_a = (ca.sum(axis=0) + beta) / (ca.sum() + Xa.V * beta)
+    assert np.allclose(o.phi[:, 0], phi_a, rtol=1e-6)
+    o.set_batch(Xb, 2)
+    assert np.allclose(o.phi[:, 0], phi_a, rtol=1e-6)
+    assert np.allclose(o.theta[:, 0], cb.sum(axis=1) + alpha, rtol=1e-6)
+    o.sweep(7, rho)
+    phi_hat = (cb.sum(axis=0) + beta) / (cb.sum() + Xb.V * beta)
+    assert np.allclose(o.phi[:, 0], (1 - rho) * phi_a + rho * phi_hat, rtol=1e-5)
+    assert np.allclose(o.theta[:, 0], cb.sum(axis=1) + alpha, rtol=1e-6)
+
+
+# --------------------------------------------------------------------------- #
 # held-out log-likelihood (Section 6.1.1)
 def test_loglik_closed_forms():
     counts, X = _toy(seed=8)
