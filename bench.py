@@ -36,26 +36,36 @@ def draw_kernel_bytes(nnz: int, D: int, K: int) -> float:
 
 
 def measured_traffic(workload: str, form: str = "multinomial"):
-    """HBM bytes per draw-kernel launch from the committed rocprofv3 counter summary (None if absent)."""
+    """HBM bytes per draw-kernel launch and where the figure comes from.  It is not measured in this run: it is
+    read from the committed summary of the two rocprofv3 counter runs of this same command (None if absent)."""
     tag = "" if form == "multinomial" else f"_{form}"
-    path = os.path.join(ROOT, "profiles", f"draw_kernel{tag}_{workload}_pmc.md")
+    rel = os.path.join("profiles", f"draw_kernel{tag}_{workload}_pmc.md")
     try:
-        for line in open(path):
+        for line in open(os.path.join(ROOT, rel)):
             if line.startswith("hbm_bytes_per_launch"):
-                return float(line.split("=")[1].split()[0])
+                return (float(line.split("=")[1].split()[0]),
+                        f"{rel}: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command, not measured in this run")
     except OSError:
         pass
-    return None
+    return None, None
 
 
-def cpu_baseline(X_np, K, alpha, beta, m, m0, G, target_s=12.0, poisson=False, sampled=False):
-    """Times one sweep of the oracle (as it stands) on a leading slice of documents sized for ~target_s."""
+def cpu_baseline(X_np, K, alpha, beta, m, m0, G, zipf_s, target_s=12.0, poisson=False, sampled=False):
+    """Times one sweep of the oracle (as it stands) on a leading slice of documents sized for ~target_s.  The
+    sweep starts from a seeded concentrated state (synth.state: document-topic rows and topic-word columns drawn
+    from their Dirichlet priors, as after training), the regime of the GPU figures beside it; nothing the GPU
+    computed is given to the oracle."""
     import oracle
+    import torch
+    from paper_1409_5402_amd import synth
     cores = len(os.sched_getaffinity(0))
     docs = min(X_np.D, 512)
     while True:
         sl = X_np.slice_docs(0, docs)
         o = oracle.OracleLDA(sl, K, alpha, beta, seed=1, m0=m0, G=G)
+        c = synth.Corpus(sl.D, sl.V, torch.from_numpy(sl.colptr), torch.from_numpy(sl.rowidx), torch.from_numpy(sl.val))
+        theta, phi = synth.state(c, K, alpha, beta, seed=123, zipf_s=zipf_s)
+        o.theta, o.phi = theta.numpy(), phi.numpy()
         t0 = time.perf_counter()
         o.sweep_poisson(float(m)) if poisson else (o.sweep_sampled(m) if sampled else o.sweep(m))
         dt = max(time.perf_counter() - t0, 1e-4)
@@ -64,7 +74,8 @@ def cpu_baseline(X_np, K, alpha, beta, m, m0, G, target_s=12.0, poisson=False, s
         docs = int(min(X_np.D, max(2 * docs, docs * target_s / dt)))
     return {"value": sl.tokens / dt, "unit": "tokens/s", "cores": cores, "kind": "oracle",
             "sample": f"one sweep over the first {docs} documents ({sl.nnz} nonzeros, {int(sl.tokens)} tokens) "
-                      f"of the same corpus, K={K}, m={m}, after the oracle's own initialisation; {dt:.2f} s"}
+                      f"of the same corpus, K={K}, m={m}, from a seeded concentrated state (synth.state, seed 123); "
+                      f"{dt:.2f} s"}
 
 
 def stream_bench(args):
@@ -208,6 +219,9 @@ def main():
                     help="resident: sweeps over one matrix held in HBM (the headline); stream: one sweep per "
                          "minibatch of a stream of host-resident minibatches; sddmm: the normaliser alone")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-spec-run", action="store_true",
+                    help="skip the legs beside the headline: the workload's specified run from the random start "
+                         "(first_sweep_ms, runN_mean_ms) and the sweep from the seeded synthetic state")
     ap.add_argument("--no-loglik", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -244,18 +258,51 @@ def main():
     test = corpus.slice_docs(n_train, corpus.D) if n_train < corpus.D else None
     st = train.stats()
 
-    t0 = time.perf_counter()
     m0 = 1      # random initialisation: one topic per token
-    g = binding.SameLDA(train.D, train.V, train.colptr, train.rowidx, train.val, K, alpha, beta,
-                        seed=2, m0=m0, tokens_per_draw=G)
-    t_init = time.perf_counter() - t0
-
     poisson = args.form == "poisson"
     sampled = args.update == "sampled"
     if poisson and sampled:
         sys.exit("bench.py: --update sampled goes with the multinomial form")
-    sweep = ((lambda mm: g.sweep_poisson(float(mm))) if poisson else
-             (lambda mm: g.sweep_sampled(mm)) if sampled else (lambda mm: g.sweep(mm)))
+
+    def make():
+        return binding.SameLDA(train.D, train.V, train.colptr, train.rowidx, train.val, K, alpha, beta,
+                               seed=2, m0=m0, tokens_per_draw=G)
+
+    def sweeper(h):
+        return ((lambda mm: h.sweep_poisson(float(mm))) if poisson else
+                (lambda mm: h.sweep_sampled(mm)) if sampled else (lambda mm: h.sweep(mm)))
+
+    # The run the workload specifies, from the library's own random start and without any burn-in: p["sweeps"]
+    # sweeps at m; every sweep is timed on its own (wall clock around a synchronised call).
+    spec = {}
+    if not args.no_spec_run:
+        g = make()
+        sw = sweeper(g)
+        per = []
+        for _ in range(p["sweeps"]):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            sw(m)
+            g.synchronize()
+            per.append(1e3 * (time.perf_counter() - t0))
+        spec = {"first_sweep_ms": per[0], f"run{len(per)}_mean_ms": sum(per) / len(per), f"run{len(per)}_last_ms": per[-1],
+                "spec_run": f"{len(per)} sweeps at m={m} right after same_lda_init (one random topic per token), no burn-in"}
+        # one sweep from the seeded concentrated state the oracle's cpu_baseline leg is timed on
+        theta_s, phi_s = synth.state(train, K, alpha, beta, seed=123, zipf_s=p["gen"].get("zipf_s", 0.0))
+        g.set(binding.THETA, theta_s)
+        g.set(binding.PHI, phi_s)
+        del theta_s, phi_s
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        sw(m)
+        g.synchronize()
+        spec["synth_state_sweep_ms"] = 1e3 * (time.perf_counter() - t0)
+        g.close()
+
+    t0 = time.perf_counter()
+    g = make()
+    t_init = time.perf_counter() - t0
+    sweep = sweeper(g)
     for _ in range(args.burn_in[0]):        # state preparation: the sampler is timed where a run spends its time,
         sweep(1)                            # with topics formed, not in the first sweeps after a random start
     for _ in range(args.burn_in[1]):
@@ -281,6 +328,7 @@ def main():
     draw_ms_avg = draw_ms / launches
     achieved = bytes_per_launch / (draw_ms_avg * 1e-3) / 1e9
 
+    traffic, traffic_source = measured_traffic(args.workload, args.form)
     out = {
         "metric": ("tokens/sec per SAME sweep in the Poisson form (K=256, m=100) + achieved HBM GB/s vs 8 TB/s" if poisson else
                    "tokens/sec per SAME sweep with sampled theta and phi (K=256, m=100) + achieved HBM GB/s vs 8 TB/s" if sampled else
@@ -293,9 +341,9 @@ def main():
                    "form": args.form, "update": args.update, "tokens_per_draw": G, "draw_tasks": g.task_count, "alpha": alpha, "beta": beta,
                    "m_init": m0,
                    "state": f"untimed before the warm-up: {args.burn_in[0]} sweeps at m=1 then {args.burn_in[1]} at m={m}",
-                   "generate_s": round(t_gen, 2), "init_s": round(t_init, 2)},
+                   **spec, "generate_s": round(t_gen, 2), "init_s": round(t_init, 2)},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(args.workload, args.form),
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": traffic_source,
                      "kernel": "draw_kernel", "kernel_ms": draw_ms_avg, "bytes_per_launch": bytes_per_launch,
                      "compulsory_bytes_per_launch": draw_kernel_compulsory_bytes(st["nnz"], st["D"], st["V"], K)},
     }
@@ -306,7 +354,8 @@ def main():
     if not args.no_cpu_baseline:
         X_np = oracle.CSC(train.D, train.V, train.colptr.cpu().numpy(), train.rowidx.cpu().numpy(),
                           train.val.cpu().numpy())
-        out["cpu_baseline"] = cpu_baseline(X_np, K, alpha, beta, m, m0, G, poisson=poisson, sampled=sampled)
+        out["cpu_baseline"] = cpu_baseline(X_np, K, alpha, beta, m, m0, G, p["gen"].get("zipf_s", 0.0),
+                                           poisson=poisson, sampled=sampled)
     print(json.dumps(out))
 
 

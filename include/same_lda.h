@@ -39,7 +39,8 @@ extern "C" {
 #define SAME_LDA_OK       0
 #define SAME_LDA_EINVAL  (-1)  /* null pointer, bad shape, K < 1, m < 1, alpha <= 0, beta <= 0, bad selector */
 #define SAME_LDA_ECSC    (-2)  /* malformed matrix: column pointers not ascending, word id out of range,
-                                  count not a positive integer, m * count too large                       */
+                                  count not a positive integer, m * count too large, or m times the tokens
+                                  of one document or word beyond the 32-bit count matrices                  */
 #define SAME_LDA_ENOMEM  (-3)  /* host or device allocation failed                                         */
 #define SAME_LDA_EHIP    (-4)  /* HIP runtime error (text in same_lda_last_error)                          */
 
@@ -82,7 +83,8 @@ int same_lda_init(same_lda_t** out, const same_lda_csc* X, int32_t K, float alph
  * matrices, draw and scatter for every nonzero with m_t copies per token, then
  * theta = n_dk/m_t + alpha, phi_hat = (n_wk/m_t + beta) / (n_k/m_t + V*beta),
  * phi = (1-rho_t)*phi + rho_t*phi_hat (rho_t = 1 replaces phi).  Asynchronous.
- *   m_t    >= 1, and m_t * (largest group size) < 2^24
+ *   m_t    >= 1, m_t * (largest group size) < 2^24, and m_t * (tokens of any one document or word) < 2^32
+ *          (the count matrices are 32-bit; the error text names the document or word)
  *   rho_t  in (0, 1]                                                                           */
 int same_lda_sweep(same_lda_t* h, int32_t m_t, float rho_t);
 
@@ -104,8 +106,8 @@ int same_lda_sweep_poisson(same_lda_t* h, float m_t, float rho_t);
  * whose means are the update of Eq. 6 and whose spread shrinks as m_t grows.  The Gamma variables
  * come from the handle's seed on streams of their own (Marsaglia-Tsang on Philox blocks, one per
  * attempt), so the result is a function of (seed, pass index, counts).  Takes the next pass index
- * like same_lda_sweep; the sweep forms may alternate on one handle.  Allocates (V/64 + 1) * K
- * doubles of device memory on its first call.  Asynchronous.
+ * like same_lda_sweep; the sweep forms may alternate on one handle.  Allocates nothing (its
+ * (V/64 + 1) * K doubles of scratch belong to the handle from same_lda_init on).  Asynchronous.
  *   m_t    >= 1, and m_t * (largest group size) < 2^24                                         */
 int same_lda_sweep_sampled(same_lda_t* h, int32_t m_t);
 

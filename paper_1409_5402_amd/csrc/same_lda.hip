@@ -23,12 +23,16 @@ namespace {
 thread_local std::string g_init_error;
 
 constexpr int32_t kTileDocs = 16;   // documents per tile of the processing order
+constexpr int kGammaRows = 64;      // rows of n_wk per workgroup of the sampled phi step
 
 // Device copy of one sparse matrix plus its draw work list.
 struct Matrix {
     int32_t D = 0;
     int64_t nnz = 0, n_tasks = 0;
     uint32_t max_group = 0;        // largest number of tokens in one task
+    uint64_t max_doc_tokens = 0, max_word_tokens = 0;   // largest token total of one document / of one word
+    int32_t max_doc = -1, max_word = -1;                // and where they occur
+    bool with_words = false;       // its draws also accumulate word counts (a training matrix)
     double tokens = 0.0;
     int32_t*  t_doc = nullptr;     // [n_tasks]
     int32_t*  t_word = nullptr;    // [n_tasks]
@@ -113,7 +117,7 @@ struct same_lda {
     float* phi = nullptr;          // [V][K]
     uint32_t* nwk = nullptr;       // [V][K]
     unsigned long long* nk = nullptr;  // [K]
-    double* gamma_partial = nullptr;   // [blocks][K] block sums of the sampled phi step (allocated on first use)
+    double* gamma_partial = nullptr;   // [ceil(V / kGammaRows)][K] block sums of the sampled phi step
     float* gamma_total = nullptr;      // [K]
     bool timing = false;
     std::vector<std::pair<hipEvent_t, hipEvent_t>> events;   // recorded, not yet read
@@ -237,6 +241,19 @@ int build_matrix(same_lda* h, const same_lda_csc* X, int32_t V, int32_t K, int32
     if (D > 0) hipLaunchKernelGGL(same::wl_check_cols, dim3((unsigned)((D + 255) / 256)), dim3(256), 0, st, M.colptr, D, d_stats);
     hipLaunchKernelGGL(same::wl_scan_nonzeros, dim3(grid_for((size_t)nnz + 1)), dim3(256), 0, st, M.colptr, M.rowidx,
                        M.val, D, nnz, V, (uint32_t)G, M.nz_doc, ntask, d_stats);
+    // token totals per document and per word: they bound what the 32-bit count matrices must hold
+    unsigned long long *doc_tok = nullptr, *word_tok = nullptr;
+    HIP_TRY(h, tmp.get(&doc_tok, (size_t)D));
+    HIP_TRY(h, tmp.get(&word_tok, (size_t)V));
+    hipLaunchKernelGGL(same::zero_u64_kernel, dim3(grid_for((size_t)V)), dim3(256), 0, st, word_tok, (size_t)V);
+    if (D > 0) {
+        hipLaunchKernelGGL(same::wl_token_totals, dim3((unsigned)((D + 255) / 256)), dim3(256), 0, st, M.colptr, M.rowidx,
+                           M.val, D, V, doc_tok, word_tok, d_stats);
+        hipLaunchKernelGGL(same::wl_word_max, dim3((unsigned)((V + 255) / 256)), dim3(256), 0, st, word_tok, V, d_stats);
+        const int32_t most = D > V ? D : V;
+        hipLaunchKernelGGL(same::wl_token_argmax, dim3((unsigned)((most + 255) / 256)), dim3(256), 0, st, doc_tok, D,
+                           word_tok, V, d_stats);
+    }
     HIP_TRY(h, hipGetLastError());
     same::BuildStats stats;
     HIP_TRY(h, hipMemcpyAsync(&stats, d_stats, sizeof(stats), hipMemcpyDeviceToHost, st));
@@ -253,6 +270,9 @@ int build_matrix(same_lda* h, const same_lda_csc* X, int32_t V, int32_t K, int32
         return fail(h, SAME_LDA_ECSC, "too many draw tasks (%llu); raise tokens_per_draw", stats.n_tasks);
     const size_t n = (size_t)stats.n_tasks;
     M.n_tasks = (int64_t)n; M.max_group = stats.max_group; M.tokens = (double)stats.tokens;
+    M.max_doc_tokens = stats.max_doc_tokens; M.max_word_tokens = stats.max_word_tokens;
+    M.max_doc = (int32_t)stats.max_doc; M.max_word = (int32_t)stats.max_word;
+    M.with_words = with_pairs;
 
     // Processing order: documents are taken in tiles of kTileDocs (the theta rows a wave touches stay
     // within one small tile); inside a tile the order starts as storage order and is re-sorted before
@@ -340,12 +360,29 @@ struct Copies {
     static Copies real(float mf) { Copies c; c.m = 0; c.mf = mf; c.poisson = true; return c; }
 };
 
+// The count matrices are 32-bit: n_dk[d][k] can reach m * (tokens of document d) and n_wk[w][k]
+// m * (tokens of word w) when one topic takes them all.  A pass places at most most * tokens + extra copies
+// of a document or word (most = m, extra = 0 in the multinomial form; margins above the mean in the
+// Poisson form, whose totals are random).
+int check_accumulators(same_lda* h, double most, double extra, const Matrix& M)
+{
+    const double limit = 4294967296.0;
+    if (most * (double)M.max_doc_tokens + extra >= limit)
+        return fail(h, SAME_LDA_ECSC, "m * tokens of document %d = %g * %llu does not fit the 32-bit counts", M.max_doc,
+                    most, (unsigned long long)M.max_doc_tokens);
+    if (M.with_words && most * (double)M.max_word_tokens + extra >= limit)
+        return fail(h, SAME_LDA_ECSC, "m * tokens of word %d = %g * %llu does not fit the 32-bit counts", M.max_word,
+                    most, (unsigned long long)M.max_word_tokens);
+    return SAME_LDA_OK;
+}
+
 int check_mf(same_lda* h, float m, const Matrix& M)
 {
     if (!(m > 0.0f) || !std::isfinite(m)) return fail(h, SAME_LDA_EINVAL, "m must be a positive number (got %g)", (double)m);
     if ((double)m * (double)(M.max_group ? M.max_group : 1u) >= 4194304.0)
         return fail(h, SAME_LDA_ECSC, "m * largest token group = %g * %u must stay below 2^22", (double)m, M.max_group);
-    return SAME_LDA_OK;
+    // a Poisson total exceeds its mean: one percent and 2^16 copies above it are beyond any total that occurs
+    return check_accumulators(h, 1.01 * (double)m, 65536.0, M);
 }
 
 int check_m(same_lda* h, int32_t m, const Matrix& M)
@@ -353,7 +390,7 @@ int check_m(same_lda* h, int32_t m, const Matrix& M)
     if (m < 1) return fail(h, SAME_LDA_EINVAL, "m must be >= 1 (got %d)", m);
     if ((uint64_t)m * (uint64_t)(M.max_group ? M.max_group : 1u) >= (1ull << 24))
         return fail(h, SAME_LDA_ECSC, "m * largest token group = %d * %u must stay below 2^24", m, M.max_group);
-    return SAME_LDA_OK;
+    return check_accumulators(h, (double)m, 0.0, M);
 }
 
 template <bool DEBUG>
@@ -432,8 +469,6 @@ int update_phi(same_lda* h, float m, float rho, hipStream_t st)
     return SAME_LDA_OK;
 }
 
-constexpr int kGammaRows = 64;     // rows of n_wk per workgroup of the sampled phi step
-
 // theta of M drawn from its Dirichlet conditional (unnormalised, mean n_dk/m + alpha).
 int sample_theta(same_lda* h, Matrix& M, float m, uint32_t pword, hipStream_t st)
 {
@@ -450,9 +485,6 @@ int sample_phi(same_lda* h, float m, uint32_t pword, hipStream_t st)
 {
     const size_t n = (size_t)h->V * h->K;
     const int blocks = (h->V + kGammaRows - 1) / kGammaRows;
-    int rc;
-    if (!h->gamma_partial && (rc = dev_alloc(h, &h->gamma_partial, (size_t)blocks * h->K))) return rc;
-    if (!h->gamma_total && (rc = dev_alloc(h, &h->gamma_total, (size_t)h->K))) return rc;
     // the topic totals are part of the readable state, kept current as after a collapsed update
     hipLaunchKernelGGL(same::zero_u64_kernel, dim3(1), dim3(256), 0, st, h->nk, (size_t)h->K);
     hipLaunchKernelGGL(same::topic_totals_kernel, dim3(blocks), dim3(256), 0, st, h->nwk, h->V, h->K, h->nk, kGammaRows);
@@ -553,6 +585,8 @@ int same_lda_init(same_lda_t** out, const same_lda_csc* X, int32_t K, float alph
     if (!rc) rc = dev_alloc(h, &h->phi, (size_t)h->V * K);
     if (!rc) rc = dev_alloc(h, &h->nwk, (size_t)h->V * K);
     if (!rc) rc = dev_alloc(h, &h->nk, (size_t)K);
+    if (!rc) rc = dev_alloc(h, &h->gamma_partial, (size_t)((h->V + kGammaRows - 1) / kGammaRows) * K);
+    if (!rc) rc = dev_alloc(h, &h->gamma_total, (size_t)K);
     if (!rc) rc = run_pass(h, h->X, Copies::whole((uint32_t)m0), pass_word(0, 0), true, true, false, h->stream);
     if (!rc) rc = update_theta(h, h->X, (float)m0, h->stream);
     if (!rc) rc = update_phi(h, (float)m0, 1.0f, h->stream);

@@ -19,6 +19,9 @@ struct BuildStats {
     unsigned long long tokens;
     unsigned long long n_tasks;
     unsigned long long first_bad;
+    unsigned long long max_doc_tokens;     // largest number of tokens in one document, and that document
+    unsigned long long max_word_tokens;    // largest number of tokens of one word, and that word
+    uint32_t max_doc, max_word;
     uint32_t max_group;
     uint32_t n_slots;
 };
@@ -26,6 +29,43 @@ struct BuildStats {
 __global__ void wl_init_stats(BuildStats* s)
 {
     s->tokens = 0ull; s->n_tasks = 0ull; s->first_bad = ~0ull; s->max_group = 0u; s->n_slots = 0u;
+    s->max_doc_tokens = 0ull; s->max_word_tokens = 0ull; s->max_doc = ~0u; s->max_word = ~0u;
+}
+
+// Token totals per document and per word (the largest values the count matrices can reach are m times
+// these).  Only entries that passed validation are counted; word_tok must be zero on entry.
+__global__ void wl_token_totals(const int32_t* __restrict__ colptr, const int32_t* __restrict__ rowidx,
+                                const float* __restrict__ val, int32_t D, int32_t V,
+                                unsigned long long* __restrict__ doc_tok, unsigned long long* __restrict__ word_tok,
+                                BuildStats* s)
+{
+    const int32_t d = (int32_t)(blockIdx.x * blockDim.x + threadIdx.x);
+    if (d >= D) return;
+    unsigned long long tot = 0ull;
+    for (int64_t i = colptr[d]; i < (int64_t)colptr[d + 1]; ++i) {
+        const int32_t w = rowidx[i];
+        const float c = val[i];
+        if (w < 0 || w >= V || !(c >= 1.0f) || c >= 16777216.0f) continue;
+        tot += (unsigned long long)c;
+        atomicAdd(word_tok + w, (unsigned long long)c);
+    }
+    doc_tok[d] = tot;
+    if (tot) atomicMax(&s->max_doc_tokens, tot);
+}
+
+__global__ void wl_word_max(const unsigned long long* __restrict__ word_tok, int32_t V, BuildStats* s)
+{
+    const int32_t w = (int32_t)(blockIdx.x * blockDim.x + threadIdx.x);
+    if (w < V && word_tok[w]) atomicMax(&s->max_word_tokens, word_tok[w]);
+}
+
+// The lowest document and word ids that attain the two maxima (for the error message).
+__global__ void wl_token_argmax(const unsigned long long* __restrict__ doc_tok, int32_t D,
+                                const unsigned long long* __restrict__ word_tok, int32_t V, BuildStats* s)
+{
+    const int32_t i = (int32_t)(blockIdx.x * blockDim.x + threadIdx.x);
+    if (i < D && doc_tok[i] == s->max_doc_tokens) atomicMin(&s->max_doc, (uint32_t)i);
+    if (i < V && word_tok[i] == s->max_word_tokens) atomicMin(&s->max_word, (uint32_t)i);
 }
 
 __global__ void wl_check_cols(const int32_t* __restrict__ colptr, int32_t D, BuildStats* s)

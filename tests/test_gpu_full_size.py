@@ -7,7 +7,7 @@ import pytest
 import torch
 
 import oracle
-from paper_1409_5402_amd import binding, synth
+from paper_1409_5402_amd import binding, schedule, synth
 
 pytestmark = pytest.mark.gpu
 
@@ -17,6 +17,7 @@ def test_device_selftest():
     assert binding.selftest() == 0
 
 
+@pytest.mark.timeout(900)
 def test_news_full_size_properties_and_sampled_parity():
     dev = torch.device("cuda:0")
     p = synth.PRESETS["news"]
@@ -108,4 +109,170 @@ def test_news_full_size_properties_and_sampled_parity():
         np.testing.assert_allclose(th[d], want, rtol=1e-5)
     assert np.all(np.isfinite(ph)) and ph.min() > 0
     np.testing.assert_allclose(ph.astype(np.float64).sum(axis=0), 1.0, atol=1e-4)
+    g.close()
+
+
+def _csc(c):
+    return oracle.CSC(c.D, c.V, c.colptr.cpu().numpy(), c.rowidx.cpu().numpy(), c.val.cpu().numpy())
+
+
+def _assert_counts_equal(g, o, what):
+    ndk = g.get(binding.NDK)
+    bad = np.flatnonzero((ndk != o.ndk).any(axis=1))
+    assert bad.size == 0, f"{what}: n_dk differs in {bad.size} of {ndk.shape[0]} documents, first {bad[:5]}"
+    nwk = g.get(binding.NWK)
+    badw = np.flatnonzero((nwk != o.nwk).any(axis=1))
+    assert badw.size == 0, f"{what}: n_wk differs in {badw.size} words, first {badw[:5]}"
+    assert np.array_equal(g.get(binding.NK), o.nwk.sum(axis=0, dtype=np.uint64)), f"{what}: n_k differs"
+
+
+@pytest.mark.timeout(900)
+def test_medium_full_size_all_twenty_annealed_sweeps():
+    """The medium workload at its real size (D=50,000, V=20,000, K=64; Zipf-skewed words) through all twenty
+    sweeps of the linear schedule m = 1..20 (Section 6.1.3): the whole state against the oracle after every
+    sweep, counts bit for bit, theta and phi to 1e-5."""
+    p = synth.PRESETS["medium"]
+    X = _csc(synth.preset("medium"))
+    ms = schedule.linear(10.5, p["sweeps"])
+    assert ms == list(range(1, 21)) and X.D == 50_000
+    G = 32
+    o = oracle.OracleLDA(X, p["K"], p["alpha"], p["beta"], seed=1, m0=ms[0], G=G)
+    g = binding.SameLDA(X.D, X.V, X.colptr, X.rowidx, X.val, p["K"], p["alpha"], p["beta"], seed=1, m0=ms[0],
+                        tokens_per_draw=G)
+    _assert_counts_equal(g, o, "init")
+    for s, m in enumerate(ms):
+        o.sweep(m)
+        g.sweep(m)
+        print(f"medium sweep {s + 1} m={m}", flush=True)
+        _assert_counts_equal(g, o, f"sweep {s + 1} m={m}")
+    np.testing.assert_allclose(g.get(binding.THETA), o.theta, rtol=1e-5, atol=0)
+    np.testing.assert_allclose(g.get(binding.PHI), o.phi, rtol=1e-5, atol=0)
+    assert g.pass_index == o.t == 21
+    g.close()
+
+
+@pytest.mark.timeout(900)
+def test_news_k1024_full_size_sampled_parity_and_conservation():
+    """The many-topics workload at its real size (the news-shaped corpus, K=1024, m=100): sampled tasks
+    recomputed one by one by the oracle, among them tasks of the most frequent words and the largest groups;
+    one full-size sweep with per-document and per-word conservation and whole sampled documents and words."""
+    dev = torch.device("cuda:0")
+    p = synth.PRESETS["news_k1024"]
+    K, m, alpha, beta, G = p["K"], p["m"], p["alpha"], p["beta"], binding.DEFAULT_TOKENS_PER_DRAW
+    corpus = synth.preset("news_k1024", device=dev)
+    train = corpus.slice_docs(0, corpus.D - corpus.D // 10)
+    theta_t, phi_t = synth.state(train, K, alpha, beta, seed=223, zipf_s=1.1)
+    g = binding.SameLDA(train.D, train.V, train.colptr, train.rowidx, train.val, K, alpha, beta,
+                        seed=6, m0=1, tokens_per_draw=G)
+    g.set(binding.THETA, theta_t)
+    g.set(binding.PHI, phi_t)
+    X = _csc(train)
+    theta, phi = theta_t.cpu().numpy(), phi_t.cpu().numpy()
+    del theta_t, phi_t
+    pword = oracle.pass_word(g.pass_index)
+    base = oracle.task_base(X, G)
+    n_tasks = g.task_count
+    assert n_tasks == int(base[-1])
+
+    rng = np.random.default_rng(4)
+    word_tokens = np.bincount(X.rowidx, weights=X.val.astype(np.float64), minlength=X.V).astype(np.int64)
+    top_words = np.argsort(-word_tokens)[:3]
+    nz_top = np.concatenate([np.flatnonzero(X.rowidx == w)[:150] for w in top_words])     # tasks of the most frequent words
+    nz_big = np.argsort(-X.val)[:100]                                                     # the largest groups
+    ids = np.unique(np.concatenate([rng.choice(n_tasks, 1500, replace=False), base[nz_top], base[nz_big],
+                                    np.arange(0, 100), np.arange(n_tasks - 100, n_tasks)]))
+    got = g.debug_draw(m, ids)
+    ref = oracle.draw_tasks(X, K, G, m, 6, pword, theta, phi, ids)
+    bad = np.flatnonzero((got != ref).any(axis=1))
+    assert bad.size == 0, f"{bad.size} of {ids.size} sampled tasks differ, first task ids {ids[bad[:5]]}"
+
+    g.sweep(m)
+    print("news_k1024 sweep done", flush=True)
+    ndk, nwk, nk = g.get(binding.NDK), g.get(binding.NWK), g.get(binding.NK)
+    doc_tokens = np.add.reduceat(X.val.astype(np.int64), X.colptr[:-1].astype(np.int64)) * (np.diff(X.colptr) > 0)
+    assert np.array_equal(ndk.sum(axis=1, dtype=np.int64), m * doc_tokens)
+    assert np.array_equal(nwk.sum(axis=1, dtype=np.int64), m * word_tokens)
+    assert np.array_equal(nk.astype(np.int64), nwk.sum(axis=0, dtype=np.int64))
+    for d in [0, 5, 1234, X.D // 3, X.D - 1]:                    # whole documents
+        t0, t1 = int(base[X.colptr[d]]), int(base[X.colptr[d + 1]])
+        vec = oracle.draw_tasks(X, K, G, m, 6, pword, theta, phi, np.arange(t0, t1))
+        assert np.array_equal(vec.sum(axis=0, dtype=np.int64), ndk[d].astype(np.int64)), d
+    # whole words (rows of n_wk, which reach the matrix through the pair list and the reduce kernel): a frequent
+    # word would need millions of draws, so words with a few hundred nonzeros are taken
+    per_word = np.bincount(X.rowidx, minlength=X.V)
+    for w in np.flatnonzero((per_word > 100) & (per_word < 400))[[0, 7, -1]]:
+        nz = np.flatnonzero(X.rowidx == w)
+        tids = np.concatenate([np.arange(base[i], base[i + 1]) for i in nz])
+        vec = oracle.draw_tasks(X, K, G, m, 6, pword, theta, phi, tids)
+        assert np.array_equal(vec.sum(axis=0, dtype=np.int64), nwk[w].astype(np.int64)), int(w)
+    th = g.get(binding.THETA)
+    rows = rng.choice(X.D, 100, replace=False)
+    np.testing.assert_allclose(th[rows], ndk[rows] / m + alpha, rtol=1e-6)
+    g.close()
+
+
+@pytest.mark.timeout(900)
+def test_abstract_stream_two_full_size_minibatches():
+    """The streamed workload at its real minibatch size (100,000 documents, V=140,000, K=256): two minibatches,
+    the second one staged on the library's second stream while the first is swept and then committed
+    (Section 5.2), m from the geometric schedule and rho_t blending; the whole state against the oracle's
+    set_batch / sweep sequence, counts bit for bit."""
+    p = synth.PRESETS["abstracts_batch"]
+    K, alpha, beta, G = p["K"], p["alpha"], p["beta"], 64
+    batches = []
+    for i in range(2):
+        gen = dict(p["gen"]); gen["seed"] = 50 + i
+        batches.append(_csc(synth.generate(**gen)))
+    assert batches[0].D == 100_000 and batches[0].V == 140_000
+    sched = schedule.geometric(1, 100, 80)
+    steps = [(30, sched[30]), (70, sched[70])]                   # (minibatch number, m): m = 6 and m = 59
+    o = oracle.OracleLDA(batches[0], K, alpha, beta, seed=17, m0=1, G=G)
+    g = binding.SameLDA(batches[0].D, batches[0].V, batches[0].colptr, batches[0].rowidx, batches[0].val, K, alpha,
+                        beta, seed=17, m0=1, tokens_per_draw=G)
+    _assert_counts_equal(g, o, "init")
+    t, m = steps[0]
+    rho = float(np.float32(schedule.rho(t)))
+    o.sweep(m, rho)
+    g.sweep(m, rho)                                              # asynchronous: runs while the next minibatch is staged
+    B = batches[1]
+    pinned = [torch.from_numpy(a).pin_memory() for a in (B.colptr, B.rowidx, B.val)]
+    g.stage_batch(B.D, *pinned, 1, 0)
+    _assert_counts_equal(g, o, f"minibatch 0 m={m}")
+    print("stream minibatch 0 done", flush=True)
+    g.commit_batch()
+    o.set_batch(B, 1)
+    assert np.array_equal(g.get(binding.NDK), o.ndk)
+    np.testing.assert_allclose(g.get(binding.PHI), o.phi, rtol=1e-5, atol=0)
+    t, m = steps[1]
+    rho = float(np.float32(schedule.rho(t)))
+    o.sweep(m, rho)
+    g.sweep(m, rho)
+    _assert_counts_equal(g, o, f"minibatch 1 m={m}")
+    np.testing.assert_allclose(g.get(binding.THETA), o.theta, rtol=1e-5, atol=0)
+    np.testing.assert_allclose(g.get(binding.PHI), o.phi, rtol=1e-5, atol=0)
+    assert g.pass_index == o.t
+    g.close()
+
+
+@pytest.mark.timeout(900)
+def test_news_heldout_loglik_full_size():
+    """Held-out per-word log-likelihood (Section 6.1.1) on the news workload's held-out tenth (30,000 documents,
+    K=256, m=100, three fold-in sweeps) under a seeded topic-word matrix: within 1e-4 of the oracle's."""
+    p = synth.PRESETS["news"]
+    K, m, alpha, beta, G = p["K"], p["m"], p["alpha"], p["beta"], binding.DEFAULT_TOKENS_PER_DRAW
+    corpus = synth.preset("news")
+    test = _csc(corpus.slice_docs(corpus.D - corpus.D // 10, corpus.D))
+    seedX = _csc(corpus.slice_docs(0, 50))                       # a handle needs a resident matrix: fifty documents
+    _, phi_t = synth.state(corpus.slice_docs(0, 50), K, alpha, beta, seed=323, zipf_s=1.1)
+    phi = phi_t.numpy()
+    o = oracle.OracleLDA(seedX, K, alpha, beta, seed=8, m0=1, G=G)
+    g = binding.SameLDA(seedX.D, seedX.V, seedX.colptr, seedX.rowidx, seedX.val, K, alpha, beta, seed=8, m0=1,
+                        tokens_per_draw=G)
+    o.phi = phi
+    g.set(binding.PHI, phi)
+    ll_g = g.loglik(test.D, test.colptr, test.rowidx, test.val, 3, m)
+    ll_o = o.loglik(test, 3, m)
+    print(f"held-out ll gpu {ll_g:.6f} oracle {ll_o:.6f}", flush=True)
+    assert abs(ll_g - ll_o) <= 1e-4
+    assert -12.0 < ll_o < -5.0
     g.close()

@@ -248,6 +248,35 @@ def test_errors_are_reported_not_crashes():
     g.close()
 
 
+def test_accumulator_range_guard():
+    """The count matrices are 32-bit: a sweep whose m times the tokens of one word or one document would not fit is
+    refused, and the message names the word or document; one copy less per token is accepted and conserved."""
+    X = oracle.CSC(2, 1, np.array([0, 1, 2], np.int32), np.zeros(2, np.int32), np.array([8e6, 8e6], np.float32))
+    g = make_gpu(X, 2, 0.1, 0.01, 1, 1, 1000)              # the word holds 1.6e7 tokens: m = 268 fits, 269 does not
+    g.sweep(268)
+    assert int(g.get(binding.NWK).sum(dtype=np.int64)) == 268 * 16_000_000
+    assert np.array_equal(g.get(binding.NDK).sum(axis=1, dtype=np.int64), [268 * 8_000_000] * 2)
+    with pytest.raises(binding.SameLdaError) as e:
+        g.sweep(269)
+    assert e.value.code == -2 and "word 0" in str(e.value)
+    with pytest.raises(binding.SameLdaError) as e:
+        g.sweep_poisson(268.0)                              # a Poisson total may exceed its mean
+    assert e.value.code == -2
+    g.sweep_poisson(250.0)
+    g.synchronize()
+    g.close()
+    # one document of two words: the document is the first to overflow
+    X = oracle.CSC(1, 2, np.array([0, 2], np.int32), np.array([0, 1], np.int32), np.array([8e6, 8e6], np.float32))
+    g = make_gpu(X, 2, 0.1, 0.01, 1, 1, 1000)
+    with pytest.raises(binding.SameLdaError) as e:
+        g.sweep(269)
+    assert e.value.code == -2 and "document 0" in str(e.value)
+    with pytest.raises(binding.SameLdaError) as e:
+        g.loglik(X.D, X.colptr, X.rowidx, X.val, 1, 300)   # held-out matrices are checked too
+    assert e.value.code == -2
+    g.close()
+
+
 def test_empty_matrix():
     X = oracle.CSC(3, 10, np.zeros(4, np.int32), np.zeros(0, np.int32), np.zeros(0, np.float32))
     g = make_gpu(X, 4, 0.1, 0.01, 1, 5, 8)
