@@ -47,8 +47,16 @@ def lib() -> ctypes.CDLL:
         L.oracle_uniform_from_word.restype = c_float
         L.oracle_stream_uniform.argtypes = [c_uint64, c_uint64, c_uint32, c_uint32, c_uint32]
         L.oracle_stream_uniform.restype = c_float
-        L.oracle_ipow.argtypes = [c_float, c_uint32]
-        L.oracle_ipow.restype = c_float
+        L.oracle_chain_uniform.argtypes = [c_uint64, c_uint64, c_uint32, c_uint32, c_uint32]
+        L.oracle_chain_uniform.restype = c_float
+        L.oracle_block_len.argtypes = [c_int32]
+        L.oracle_block_len.restype = c_int32
+        L.oracle_prefix.argtypes = [c_int32, f32p, f32p]
+        L.oracle_prefix.restype = c_float
+        L.oracle_top_position.argtypes = [c_float, c_uint32, c_float]
+        L.oracle_top_position.restype = c_float
+        L.oracle_log1m.argtypes = [c_float]
+        L.oracle_log1m.restype = c_float
         L.oracle_binom_walk.argtypes = [c_uint32, c_float, c_float, c_float]
         L.oracle_binom_walk.restype = c_uint32
         L.oracle_binom.argtypes = [c_uint32, c_float, c_uint64, c_uint64, c_uint32, c_uint32]
@@ -136,19 +144,44 @@ def uniform_from_word(x: int) -> float:
 
 
 def stream_uniform(seed: int, tau: int, k: int, piece: int, pword: int) -> float:
+    """Uniform of piece `piece` of topic k (stream layout of the Poisson form)."""
     return float(lib().oracle_stream_uniform(seed, tau, k, piece, pword))
 
 
-def ipow(s: float, n: int) -> float:
-    return float(lib().oracle_ipow(c_float(s), n))
+def chain_uniform(seed: int, tau: int, step: int, slot: int, pword: int) -> float:
+    """Uniform of step `step` of the multinomial draw: slot 0 places the highest copy, slot 1 + j decides
+    piece j of the step's binomial."""
+    return float(lib().oracle_chain_uniform(seed, tau, step, slot, pword))
+
+
+def block_len(K: int) -> int:
+    return int(lib().oracle_block_len(K))
+
+
+def prefix(w):
+    """Two-level running sums of the weights: returns (P[K], mu)."""
+    w = np.ascontiguousarray(w, dtype=np.float32)
+    P = np.zeros(w.shape[0], dtype=np.float32)
+    mu = lib().oracle_prefix(w.shape[0], _p(w, c_float), _p(P, c_float))
+    return P, float(mu)
+
+
+def top_position(U: float, R: int, u: float) -> float:
+    """Position of the highest of R copies uniform on (0, U), from one uniform u."""
+    return float(lib().oracle_top_position(c_float(U), R, c_float(u)))
+
+
+def log1m(x: float) -> float:
+    """-log(1 - x) for 0 < x <= 1/2."""
+    return float(lib().oracle_log1m(c_float(x)))
 
 
 def binom_walk(n: int, pm0: float, r: float, u: float) -> int:
     return int(lib().oracle_binom_walk(n, c_float(pm0), c_float(r), c_float(u)))
 
 
-def binom(R: int, q: float, seed: int, tau: int, k: int, pword: int) -> int:
-    return int(lib().oracle_binom(R, c_float(q), seed, tau, k, pword))
+def binom(R: int, q: float, seed: int, tau: int, step: int, pword: int) -> int:
+    return int(lib().oracle_binom(R, c_float(q), seed, tau, step, pword))
 
 
 def draw(w, N: int, seed: int, tau: int, pword: int):

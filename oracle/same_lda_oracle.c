@@ -14,10 +14,11 @@
  * implementation following the same steps obtains the same integers.
  *
  * Parts the paper does not fix (build decisions; "parity unpinned" by the paper,
- * pinned only in distribution): the order of the conditional-binomial chain, the
- * binomial sampler, the random number generator and its keying, the summation
- * order, the grouping of a nonzero's tokens into draws, the initialisation and
- * the held-out fold-in.
+ * pinned only in distribution): how the multinomial count vector is drawn (here:
+ * topic by topic from the top, each step placing the highest remaining copy and
+ * the copies that share its topic), the binomial sampler, the random number
+ * generator and its keying, the summation order, the grouping of a nonzero's
+ * tokens into draws, the initialisation and the held-out fold-in.
  */
 #include <math.h>
 #include <stddef.h>
@@ -55,12 +56,43 @@ float oracle_uniform_from_word(uint32_t x)
     return (float)(2u * (x >> 9) + 1u) * 5.9604644775390625e-8f; /* 2^-24 */
 }
 
-/* Stream layout.  One draw task (see oracle_pass) has a 40-bit id tau.  The
- * uniform that decides topic k's first binomial piece is word (k mod 4) of the
- * block with counter (tau_lo, tau_hi, k/4, pass).  Piece j >= 1 of topic k uses
- * word ((j-1) mod 4) of the block (tau_lo, tau_hi | ((j-1)/4) << 8,
- * 2^31 | k, pass).  The key is the 64-bit seed.  "pass" carries the pass index
- * in its low 28 bits and a stream domain (0 training, 1 held-out fold-in) above. */
+/* Stream layouts.  One draw task (see oracle_pass) has a 40-bit id tau; the key
+ * is the 64-bit seed; "pass" carries the pass index in its low 28 bits and a
+ * stream domain (0 training, 1 held-out fold-in) above.
+ *
+ * Multinomial form (oracle_draw): the draw proceeds in steps 0, 1, 2, ... (one per
+ * topic that receives copies).  Step s takes two uniforms from the block with
+ * counter (tau_lo, tau_hi, s/2, pass): slot 0, word 2*(s mod 2), places the highest
+ * remaining copy; slot 1, word 2*(s mod 2)+1, decides the first piece of the
+ * step's binomial.  Slot j >= 2 (piece j-1 of that binomial) is word ((j-2) mod 4)
+ * of the block (tau_lo, tau_hi | ((j-2)/4) << 8, 2^31 | s, pass).               */
+static float chain_uniform(uint64_t seed, uint64_t tau, uint32_t step, uint32_t slot, uint32_t pass)
+{
+    uint32_t key[2] = { (uint32_t)seed, (uint32_t)(seed >> 32) };
+    uint32_t ctr[4], out[4];
+    ctr[0] = (uint32_t)tau;
+    ctr[1] = (uint32_t)(tau >> 32) & 0xFFu;
+    ctr[3] = pass;
+    if (slot < 2u) {
+        ctr[2] = step >> 1;
+        oracle_philox4x32_10(ctr, key, out);
+        return oracle_uniform_from_word(out[2u * (step & 1u) + slot]);
+    }
+    ctr[1] |= ((slot - 2u) >> 2) << 8;
+    ctr[2] = 0x80000000u | step;
+    oracle_philox4x32_10(ctr, key, out);
+    return oracle_uniform_from_word(out[(slot - 2u) & 3u]);
+}
+
+float oracle_chain_uniform(uint64_t seed, uint64_t tau, uint32_t step, uint32_t slot, uint32_t pass)
+{
+    return chain_uniform(seed, tau, step, slot, pass);
+}
+
+/* Poisson form (oracle_draw_poisson): the uniform that decides topic k's first
+ * piece is word (k mod 4) of the block with counter (tau_lo, tau_hi, k/4, pass).
+ * Piece j >= 1 of topic k uses word ((j-1) mod 4) of the block
+ * (tau_lo, tau_hi | ((j-1)/4) << 8, 2^31 | k, pass).                            */
 static float stream_uniform(uint64_t seed, uint64_t tau, uint32_t k, uint32_t piece, uint32_t pass)
 {
     uint32_t key[2] = { (uint32_t)seed, (uint32_t)(seed >> 32) };
@@ -85,110 +117,11 @@ float oracle_stream_uniform(uint64_t seed, uint64_t tau, uint32_t k, uint32_t pi
 }
 
 /* ------------------------------------------------------------------------- */
-/* s^n by binary square-and-multiply, least significant bit first.            */
-float oracle_ipow(float s, uint32_t n)
-{
-    float result = 1.0f, base = s;
-    uint32_t e = n;
-    while (e > 0) {
-        if (e & 1u) result = result * base;
-        e >>= 1;
-        if (e > 0) base = base * base;
-    }
-    return result;
-}
-
-/* Binomial(n, qq) for one piece by inversion: walk the pmf upward from 0,
- * pm(x) = pm(x-1) * r * (n-x+1) / x with r = qq/(1-qq), until the cdf reaches
- * u.  The walk also ends when the pmf has fallen below the resolution of the
- * running cdf (the tail is numerically exhausted).                            */
-uint32_t oracle_binom_walk(uint32_t n, float pm0, float r, float u)
-{
-    uint32_t x = 0;
-    float pm = pm0, cdf = pm0;
-    while (u > cdf && x < n) {
-        x += 1;
-        float inv_x = 1.0f / (float)x;
-        pm = pm * r;
-        pm = pm * (float)(n - x + 1u);
-        pm = pm * inv_x;
-        float next = cdf + pm;
-        if (next == cdf) break;
-        cdf = next;
-    }
-    return x;
-}
-
-/* n ~ Binomial(R, q) for topic k of task tau.  The smaller of q and 1-q is
- * sampled (the result is complemented for q > 1/2); when R*qq exceeds 32, R is cut
- * into pieces of floor(32/qq) trials so that (1-qq)^piece never underflows; each
- * piece has its own uniform.                                                        */
-uint32_t oracle_binom(uint32_t R, float q, uint64_t seed, uint64_t tau, uint32_t k, uint32_t pass)
-{
-    if (R == 0 || !(q > 0.0f)) return 0;
-    if (q >= 1.0f) return R;
-    int flip = q > 0.5f;
-    float qq = flip ? 1.0f - q : q;
-    float s = 1.0f - qq;
-    float r = qq / s;
-    int single = ((float)R * qq) <= 32.0f;
-    uint32_t L = single ? R : (uint32_t)(32.0f / qq);
-    float pmL = oracle_ipow(s, L);
-    uint32_t rem = R, piece = 0, total = 0;
-    while (rem > 0) {
-        uint32_t n = rem < L ? rem : L;
-        float pm0 = (n == L) ? pmL : oracle_ipow(s, n);
-        float u = stream_uniform(seed, tau, k, piece, pass);
-        total += oracle_binom_walk(n, pm0, r, u);
-        rem -= n;
-        piece += 1;
-    }
-    return flip ? R - total : total;
-}
-
-/* The factored draw (Section 4): the N = m*g copies of a latent topic variable
- * with conditional weights w[0..K) are one Multinomial(N, w/sum w) count
- * vector, drawn as a chain of conditional binomials.  The heaviest topic h (the
- * highest index among equal maxima) is never drawn: it keeps what is left.  The
- * others are visited from the last topic down, n_k ~ Bin(R, w_k / M_k), R -= n_k,
- * where M_k is the weight not yet decided when k is visited: the topics
- * 0..k and, if it is not among them, topic h.  P[k] is the running sum
- * w_0+...+w_k accumulated left to right, so M_k = P[k] for k > h and
- * M_k = P[k] + w_h for k < h.  Returns P[K-1] (the normaliser mu of Algorithm 3).
- * scratch holds K floats.                                                      */
-float oracle_draw(int32_t K, const float* w, uint32_t N, uint64_t seed, uint64_t tau,
-                  uint32_t pass, uint32_t* counts, float* scratch)
-{
-    float* P = scratch;
-    P[0] = w[0];
-    for (int32_t k = 1; k < K; ++k) P[k] = P[k - 1] + w[k];
-    int32_t h = 0;
-    for (int32_t k = 1; k < K; ++k) if (w[k] >= w[h]) h = k;
-    for (int32_t k = 0; k < K; ++k) counts[k] = 0;
-    uint32_t R = N;
-    for (int32_t k = K - 1; k >= 0 && R > 0; --k) {
-        if (k == h || !(w[k] > 0.0f)) continue;
-        float M = (k > h) ? P[k] : P[k] + w[h];
-        float q = w[k] / M;
-        uint32_t n = oracle_binom(R, q, seed, tau, (uint32_t)k, pass);
-        counts[k] = n;
-        R -= n;
-    }
-    counts[h] = R;
-    return P[K - 1];
-}
-
-/* ------------------------------------------------------------------------- */
-/* Poisson form of the factored draw (Section 4, second part; Algorithm 3, the
- * sampling line): the count of topic k among the copies of a latent variable is
- * an independent Poisson variable with rate (number of copies) * P(topic k).
- * The number of copies may be any positive real.
- *
- * exp(-y) for 0 <= y <= 32 from + - * only, so that a second implementation
+/* exp(-y) for 0 <= y <= 48 from + - * only, so that a second implementation
  * obtains the same bits: t = y*log2(e), n = trunc(t), f = t-n in [0,1),
  * g = f - 1/2, 2^-(g+1/2) by the degree-7 Taylor polynomial of
  * 2^-1/2 * exp(-g ln 2) in Horner form (every product and sum rounded once),
- * scaled by 2^-n.  Relative error below 2e-6, below 2e-7 for y <= 2 (tests).                          */
+ * scaled by 2^-n.  Relative error below 3e-6, below 2e-7 for y <= 2 (tests).   */
 float oracle_expneg(float y)
 {
     static const float c[8] = {
@@ -212,6 +145,203 @@ float oracle_expneg(float y)
     }
     return ldexpf(p, -n);
 }
+
+/* log x for a positive normal x: x = 2^e * f with f in [sqrt(1/2), sqrt(2)),
+ * log f = 2 atanh(s), s = (f-1)/(f+1), by the odd series up to s^11.         */
+float oracle_flog(float x)
+{
+    uint32_t bits;
+    memcpy(&bits, &x, sizeof bits);
+    int32_t e = (int32_t)(bits >> 23) - 127;
+    uint32_t fb = (bits & 0x007FFFFFu) | 0x3F800000u;
+    float f;
+    memcpy(&f, &fb, sizeof f);
+    if (f > 1.41421354f) { f = f * 0.5f; e += 1; }
+    float num = f - 1.0f, den = f + 1.0f;
+    float s = num / den;
+    float z = s * s;
+    float p = 0.0909090936f;
+    p = p * z; p = p + 0.111111112f;
+    p = p * z; p = p + 0.142857149f;
+    p = p * z; p = p + 0.2f;
+    p = p * z; p = p + 0.333333343f;
+    p = p * z; p = p + 1.0f;
+    float lf = 2.0f * s;
+    lf = lf * p;
+    float le = (float)e * 0.693147182f;
+    return le + lf;
+}
+
+/* -log(1 - x) for 0 < x <= 1/2 without ever rounding 1 - x (which would lose x
+ * below 2^-24): log((1+t)/(1-t)) = 2 atanh(t) with t = x / (2 - x), by the odd
+ * series through t^17 in Horner form.  Relative error below 3e-7 (tests).      */
+float oracle_log1m(float x)
+{
+    float den = 2.0f - x;
+    float t = x / den;
+    float z = t * t;
+    float p = 0.0588235296f;                 /* 1/17 */
+    p = p * z; p = p + 0.0666666701f;        /* 1/15 */
+    p = p * z; p = p + 0.0769230798f;        /* 1/13 */
+    p = p * z; p = p + 0.0909090936f;        /* 1/11 */
+    p = p * z; p = p + 0.111111112f;         /* 1/9  */
+    p = p * z; p = p + 0.142857149f;         /* 1/7  */
+    p = p * z; p = p + 0.2f;
+    p = p * z; p = p + 0.333333343f;
+    p = p * z; p = p + 1.0f;
+    float two_t = 2.0f * t;
+    return two_t * p;
+}
+
+/* Binomial(n, qq) for one piece by inversion: walk the pmf upward from 0,
+ * pm(x) = pm(x-1) * r * (n-x+1) / x with r = qq/(1-qq), until the cdf reaches
+ * u.  The walk also ends when the pmf has fallen below the resolution of the
+ * running cdf (the tail is numerically exhausted).                            */
+uint32_t oracle_binom_walk(uint32_t n, float pm0, float r, float u)
+{
+    uint32_t x = 0;
+    float pm = pm0, cdf = pm0;
+    while (u > cdf && x < n) {
+        x += 1;
+        float inv_x = 1.0f / (float)x;
+        pm = pm * r;
+        pm = pm * (float)(n - x + 1u);
+        pm = pm * inv_x;
+        float next = cdf + pm;
+        if (next == cdf) break;
+        cdf = next;
+    }
+    return x;
+}
+
+/* n ~ Binomial(R, q), the binomial of step `step` of task tau.  The smaller of q
+ * and 1-q is sampled (the result is complemented for q > 1/2).  One piece of R
+ * trials serves when R*qq <= 32; otherwise R is cut into pieces of floor(32/qq)
+ * trials and a shorter last one, each with its own uniform, so that the
+ * probability of zero successes never underflows.  That probability, (1-qq)^n,
+ * is exp(-n * (-log(1-qq))) with the two functions above: forming 1-qq first
+ * would round qq to a multiple of 2^-24 and the pmf would no longer sum to one
+ * (for millions of trials the missing mass exceeds the law's own).            */
+uint32_t oracle_binom(uint32_t R, float q, uint64_t seed, uint64_t tau, uint32_t step, uint32_t pass)
+{
+    if (R == 0 || !(q > 0.0f)) return 0;
+    if (q >= 1.0f) return R;
+    int flip = q > 0.5f;
+    float qq = flip ? 1.0f - q : q;
+    float s = 1.0f - qq;
+    float r = qq / s;
+    float lq = oracle_log1m(qq);
+    int single = ((float)R * qq) <= 32.0f;
+    uint32_t L = single ? R : (uint32_t)(32.0f / qq);
+    uint32_t rem = R, piece = 0, total = 0;
+    while (rem > 0) {
+        uint32_t n = rem < L ? rem : L;
+        float pm0 = oracle_expneg((float)n * lq);
+        float u = chain_uniform(seed, tau, step, 1u + piece, pass);
+        total += oracle_binom_walk(n, pm0, r, u);
+        rem -= n;
+        piece += 1;
+    }
+    return flip ? R - total : total;
+}
+
+/* Running sums of the weights in two levels.  The K topics are taken in blocks
+ * of T = 4*ceil(K/128) consecutive topics (at most 32 blocks; T = 8 at K = 256).
+ * Inside a block the weights are added left to right starting from zero
+ * (r_0 = w_0, r_j = r_{j-1} + w_j); the sums S of whole blocks are added left to
+ * right (S = 0 before the first block); P[k] = S + r.  P is non-decreasing, the
+ * last P of a block is the S of the next, and the return value P[K-1] is the
+ * normaliser mu of Algorithm 3.                                                */
+int32_t oracle_block_len(int32_t K)
+{
+    return 4 * ((K + 127) / 128);
+}
+
+float oracle_prefix(int32_t K, const float* w, float* P)
+{
+    int32_t T = oracle_block_len(K);
+    float S = 0.0f;
+    for (int32_t b0 = 0; b0 < K; b0 += T) {
+        float r = 0.0f;
+        int32_t b1 = b0 + T < K ? b0 + T : K;
+        for (int32_t k = b0; k < b1; ++k) {
+            r = r + w[k];
+            P[k] = S + r;
+        }
+        S = S + r;
+    }
+    return S;
+}
+
+/* Position of the highest of R copies spread uniformly over (0, U): the largest of
+ * R independent uniforms has distribution function (y/U)^R, so y = U * u^(1/R)
+ * for one uniform u; u^(1/R) = exp(log(u)/R) with the logarithm and exponential
+ * above.  One copy needs neither.                                              */
+float oracle_top_position(float U, uint32_t R, float u)
+{
+    float y;
+    if (R == 1u) {
+        y = U * u;
+    } else {
+        float a = -oracle_flog(u);
+        float z = a / (float)R;
+        float e = oracle_expneg(z);
+        if (e > 1.0f) e = 1.0f;
+        y = U * e;
+    }
+    if (!(y > 0.0f)) y = U;
+    return y;
+}
+
+/* The factored draw (Section 4): the N = m*g copies of a latent topic variable
+ * with conditional weights w[0..K) are one Multinomial(N, w/sum w) count
+ * vector.  Picture every copy as a point uniform on (0, mu), topic k owning the
+ * interval (P[k-1], P[k]].  The draw walks down from the top, one step per topic
+ * that receives copies.  With R copies left, all of them below U:
+ *   - the highest copy sits at y = oracle_top_position(U, R, u); its topic is the
+ *     first k with P[k] >= y;
+ *   - given y, the other R-1 copies are uniform on (0, y), so each of them falls
+ *     into the same topic, i.e. above P[k-1], with probability q = (y - P[k-1]) / y:
+ *     that topic receives 1 + Binomial(R-1, q) copies;
+ *   - the copies left are all below P[k-1], the next step's U.
+ * Returns mu.  scratch holds K floats.                                         */
+float oracle_draw(int32_t K, const float* w, uint32_t N, uint64_t seed, uint64_t tau,
+                  uint32_t pass, uint32_t* counts, float* scratch)
+{
+    float* P = scratch;
+    float mu = oracle_prefix(K, w, P);
+    for (int32_t k = 0; k < K; ++k) counts[k] = 0;
+    uint32_t R = N, step = 0;
+    float U = mu;
+    int32_t top = K;                    /* the copies left belong to topics below top */
+    while (R > 0) {
+        if (!(U > 0.0f)) { counts[top - 1] += R; break; }       /* no weight left: a degenerate input */
+        float u = chain_uniform(seed, tau, step, 0, pass);
+        float y = oracle_top_position(U, R, u);
+        int32_t k = 0;
+        while (k < top - 1 && !(P[k] >= y)) ++k;                 /* P[top-1] == U >= y */
+        float prev = k > 0 ? P[k - 1] : 0.0f;
+        uint32_t n = 1;
+        if (R > 1u) {
+            float width = y - prev;
+            float q = width / y;
+            n += oracle_binom(R - 1u, q, seed, tau, step, pass);
+        }
+        counts[k] += n;
+        R -= n;
+        U = prev;
+        top = k;
+        step += 1;
+        if (top == 0 && R > 0) { counts[0] += R; break; }       /* k = 0 gives q = 1: nothing can be left */
+    }
+    return mu;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Poisson form of the factored draw (Section 4, second part; Algorithm 3, the
+ * sampling line): the count of topic k among the copies of a latent variable is
+ * an independent Poisson variable with rate (number of copies) * P(topic k).
+ * The number of copies may be any positive real.  exp(-rate) is oracle_expneg.  */
 
 /* Poisson(rate) for one piece by inversion: walk the pmf upward from 0,
  * pm(x) = pm(x-1) * rate / x, until the cdf reaches u or the pmf has fallen
@@ -545,32 +675,6 @@ void oracle_phi_update(int32_t V, int32_t K, const uint32_t* nwk, uint32_t m, fl
  *
  * Logarithm, cosine and exponential are evaluated from + - * / only, one
  * rounding each, so that a second implementation takes the same decisions.   */
-
-/* log x for a positive normal x: x = 2^e * f with f in [sqrt(1/2), sqrt(2)),
- * log f = 2 atanh(s), s = (f-1)/(f+1), by the odd series up to s^11.         */
-float oracle_flog(float x)
-{
-    uint32_t bits;
-    memcpy(&bits, &x, sizeof bits);
-    int32_t e = (int32_t)(bits >> 23) - 127;
-    uint32_t fb = (bits & 0x007FFFFFu) | 0x3F800000u;
-    float f;
-    memcpy(&f, &fb, sizeof f);
-    if (f > 1.41421354f) { f = f * 0.5f; e += 1; }
-    float num = f - 1.0f, den = f + 1.0f;
-    float s = num / den;
-    float z = s * s;
-    float p = 0.0909090936f;
-    p = p * z; p = p + 0.111111112f;
-    p = p * z; p = p + 0.142857149f;
-    p = p * z; p = p + 0.2f;
-    p = p * z; p = p + 0.333333343f;
-    p = p * z; p = p + 1.0f;
-    float lf = 2.0f * s;
-    lf = lf * p;
-    float le = (float)e * 0.693147182f;
-    return le + lf;
-}
 
 /* cos(2 pi u) for u in (0,1): the quarter turn and the angle inside it, then the
  * Taylor polynomial of sine or cosine on [0, pi/2).                           */

@@ -4,8 +4,9 @@ SAME_LDA_SLOW=1 is set; `python tests/test_oracle_mutants.py` runs it by hand an
 One plausible mistake at a time (a dropped term, a wrong sign, index or operand) is planted in a COPY of
 the oracle (oracle/same_lda_oracle.c or oracle/__init__.py) under a temporary directory; the pins of
 tests/test_oracle_pins.py are run against the copy, and the mutants that no pin notices are listed.  The
-mutants named in EXPECTED_SURVIVORS change only which integers come out, not their distribution: they are
-build decisions that no mathematical pin can see and are expected to survive; every other one must be caught.
+mutant named in EXPECTED_SURVIVORS changes only which integers come out, not their distribution (the length
+of a binomial piece): a build decision that no mathematical pin can see, expected to survive; every other
+one must be caught.
 """
 import os
 import re
@@ -17,7 +18,7 @@ import tempfile
 import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-EXPECTED_SURVIVORS = {"chain: heaviest = lowest index among ties", "binom: piece length wrong"}
+EXPECTED_SURVIVORS = {"binom: piece length wrong"}
 
 C_FILE, PY_FILE = "same_lda_oracle.c", "__init__.py"
 
@@ -46,18 +47,32 @@ PY_MUTS = [
 
 # (name, text in the oracle's C source, its replacement); the first occurrence is replaced
 MUTS = [
- ("chain: drop heaviest weight below h", "float M = (k > h) ? P[k] : P[k] + w[h];", "float M = P[k];"),
- ("chain: heaviest = lowest index among ties", "if (w[k] >= w[h]) h = k;", "if (w[k] > w[h]) h = k;"),
- ("chain: ascending order", "for (int32_t k = K - 1; k >= 0 && R > 0; --k) {", "for (int32_t k = 0; k < K && R > 0; ++k) {"),
- ("chain: remainder not given to h", "counts[h] = R;", "counts[h] = 0;"),
- ("chain: R not reduced", "        counts[k] = n;\n        R -= n;", "        counts[k] = n;"),
+ ("chain: the step's topic keeps only the top copy", "n += oracle_binom(R - 1u, q, seed, tau, step, pass);", "n += 0u * oracle_binom(R - 1u, q, seed, tau, step, pass);"),
+ ("chain: binomial over all R copies", "n += oracle_binom(R - 1u, q, seed, tau, step, pass);", "n += oracle_binom(R, q, seed, tau, step, pass); if (n > R) n = R;"),
+ ("chain: width over the whole range", "float q = width / y;", "float q = width / U;"),
+ ("chain: width from the topic's upper end", "float width = y - prev;", "float width = P[k] - prev;"),
+ ("chain: next range keeps the topic", "        U = prev;\n        top = k;", "        U = P[k];\n        top = k + 1;"),
+ ("chain: R not reduced", "        counts[k] += n;\n        R -= n;", "        counts[k] += n;\n        R -= 1;"),
+ ("chain: topic above the position", "while (k < top - 1 && !(P[k] >= y)) ++k;", "while (k < top - 1 && !(P[k] >= y)) ++k;\n        if (k < top - 1) ++k;"),
+ ("chain: every step reuses step 0's uniforms", "float u = chain_uniform(seed, tau, step, 0, pass);", "float u = chain_uniform(seed, tau, 0, 0, pass);"),
+ ("top: root of order R+1", "float z = a / (float)R;", "float z = a / (float)(R + 1u);"),
+ ("top: no root taken", "float e = oracle_expneg(z);\n        if (e > 1.0f) e = 1.0f;", "float e = oracle_expneg(a);\n        if (e > 1.0f) e = 1.0f;"),
+ ("top: single copy at the top end", "        y = U * u;\n    } else {", "        y = U;\n    } else {"),
+ ("prefix: block sums restart", "        S = S + r;\n    }\n    return S;", "        S = r;\n    }\n    return S;"),
+ ("prefix: running sum skips the block's first weight", "            r = r + w[k];\n            P[k] = S + r;", "            P[k] = S + r;\n            r = r + w[k];"),
+ ("prefix: block length off", "return 4 * ((K + 127) / 128);", "return 4 * ((K + 127) / 128) + 4;"),
  ("binom: complement not undone", "return flip ? R - total : total;", "return total;"),
  ("binom: r = qq instead of qq/s", "float r = qq / s;", "float r = qq;"),
  ("binom: piece length wrong", "uint32_t L = single ? R : (uint32_t)(32.0f / qq);", "uint32_t L = single ? R : (uint32_t)(16.0f / qq) + 7u;"),
- ("binom: pieces share one uniform", "float u = stream_uniform(seed, tau, k, piece, pass);\n        total += oracle_binom_walk", "float u = stream_uniform(seed, tau, k, 0, pass);\n        total += oracle_binom_walk"),
+ ("binom: pieces share one uniform", "float u = chain_uniform(seed, tau, step, 1u + piece, pass);", "float u = chain_uniform(seed, tau, step, 1u, pass);"),
+ ("binom: binomial reuses the position's uniform", "float u = chain_uniform(seed, tau, step, 1u + piece, pass);", "float u = chain_uniform(seed, tau, step, piece == 0 ? 0u : 1u + piece, pass);"),
+ ("binom: zero-success probability from the rounded 1-qq", "float pm0 = oracle_expneg((float)n * lq);", "float pm0 = oracle_expneg((float)n * -oracle_flog(s));"),
+ ("binom: zero-success probability ignores n", "float pm0 = oracle_expneg((float)n * lq);", "float pm0 = oracle_expneg(lq);"),
+ ("log1m: denominator 1 - x", "float den = 2.0f - x;", "float den = 1.0f - x;"),
+ ("log1m: series cut after t^3", "    p = p * z; p = p + 0.2f;\n", "    p = 0.2f;\n"),
  ("walk: n-x instead of n-x+1", "pm = pm * (float)(n - x + 1u);", "pm = pm * (float)(n - x);"),
  ("walk: starts cdf at 0", "float pm = pm0, cdf = pm0;\n    while (u > cdf && x < n) {", "float pm = pm0, cdf = 0.0f;\n    while (u > cdf && x < n) {"),
- ("ipow: exponent off by one", "uint32_t e = n;\n    while (e > 0) {", "uint32_t e = n + 1u;\n    while (e > 0) {"),
+ ("chain stream: slot ignored", "return oracle_uniform_from_word(out[2u * (step & 1u) + slot]);", "return oracle_uniform_from_word(out[2u * (step & 1u)]);"),
  ("uniform: can be 0", "(2u * (x >> 9) + 1u)", "(2u * (x >> 9))"),
  ("stream: topic word index ignores k", "return oracle_uniform_from_word(out[k & 3u]);", "return oracle_uniform_from_word(out[0]);"),
  ("weights: phi row of wrong word", "phi ? phi + (size_t)word * K : NULL, w);\n                uint32_t ntask", "phi ? phi + (size_t)((word + 1) % V) * K : NULL, w);\n                uint32_t ntask"),

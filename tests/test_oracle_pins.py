@@ -60,18 +60,55 @@ def test_stream_uniforms_are_uniform_and_keyed():
     assert len(set(later)) == len(later)
 
 
+def test_chain_uniforms_are_uniform_keyed_and_laid_out_as_stated():
+    """Uniforms of the multinomial draw: two per step from the block of the step pair, further binomial pieces
+    from blocks of their own; every coordinate of the key changes the value; checked against the block function."""
+    us = np.array([oracle.chain_uniform(7, tau, s, slot, PW(3)) for tau in range(1250) for s in range(16) for slot in (0, 1)])
+    obs = np.histogram(us, bins=20, range=(0, 1))[0]
+    assert stats.chisquare(obs).pvalue > 1e-4
+    assert abs(us.mean() - 0.5) < 0.01
+    pairs = us.reshape(-1, 2)                              # the two uniforms of a step are independent
+    assert abs(np.corrcoef(pairs[:, 0], pairs[:, 1])[0, 1]) < 0.02
+    base = oracle.chain_uniform(7, 5, 3, 0, PW(3))
+    others = [oracle.chain_uniform(8, 5, 3, 0, PW(3)), oracle.chain_uniform(7, 6, 3, 0, PW(3)),
+              oracle.chain_uniform(7, 5, 2, 0, PW(3)), oracle.chain_uniform(7, 5, 3, 1, PW(3)),
+              oracle.chain_uniform(7, 5, 3, 0, PW(4)), oracle.chain_uniform(7, 5, 3, 0, PW(3, oracle.DOMAIN_HELDOUT)),
+              oracle.chain_uniform(7, 5 + (1 << 32), 3, 0, PW(3))]
+    assert all(base != o for o in others)
+    seed, tau, pw = (0x1234 << 32) | 0x9abc, (3 << 32) | 77, PW(9)
+    key = [seed & 0xFFFFFFFF, seed >> 32]
+    for step in (0, 1, 6, 7):
+        blk = oracle.philox([tau & 0xFFFFFFFF, tau >> 32, step >> 1, pw], key)
+        for slot in (0, 1):
+            assert oracle.chain_uniform(seed, tau, step, slot, pw) == oracle.uniform_from_word(int(blk[2 * (step & 1) + slot]))
+        for j in (2, 3, 5, 6, 9, 10):
+            blk = oracle.philox([tau & 0xFFFFFFFF, (tau >> 32) | (((j - 2) >> 2) << 8), 0x80000000 | step, pw], key)
+            assert oracle.chain_uniform(seed, tau, step, j, pw) == oracle.uniform_from_word(int(blk[(j - 2) & 3]))
+    allu = [oracle.chain_uniform(7, 5, s, j, PW(3)) for s in range(4) for j in range(12)]
+    assert len(set(allu)) == len(allu)
+
+
 # --------------------------------------------------------------------------- #
 # binomial sampler
-def test_ipow_against_double_pow():
+def test_log1m_against_the_library_function():
+    """-log(1-x) on (0, 1/2], down to arguments far below 2^-24 where 1-x is no longer representable."""
     rng = np.random.default_rng(0)
-    for _ in range(300):
-        s = float(np.float32(rng.uniform(0.5, 1.0)))
-        n = int(rng.integers(0, 5000))
-        ref = s ** n
-        got = oracle.ipow(s, n)
-        assert got == pytest.approx(ref, rel=2e-7 * (n + 2), abs=1e-44)
-    assert oracle.ipow(0.3, 0) == 1.0
-    assert oracle.ipow(np.float32(0.7), 1) == float(np.float32(0.7))
+    xs = np.concatenate([10.0 ** rng.uniform(-12, np.log10(0.5), size=3000), [0.5, 0.25, 1e-30, 2.0 ** -24, 2.0 ** -25]])
+    for x in xs.astype(np.float32):
+        assert oracle.log1m(float(x)) == pytest.approx(-math.log1p(-float(x)), rel=3e-7)
+
+
+def test_zero_success_probability_is_accurate_for_any_number_of_trials():
+    """(1-q)^n as the sampler forms it, exp(-n * -log(1-q)), against double arithmetic: relative error 1e-5 at
+    most for n*q up to 45, whatever n (ten trials or sixteen million)."""
+    rng = np.random.default_rng(1)
+    for _ in range(2000):
+        n = int(10 ** rng.uniform(0, 7.2))
+        q = float(np.float32(min(0.5, 10 ** rng.uniform(-9, -0.3))))
+        if n * q > 45:
+            continue
+        got = oracle.expneg(float(np.float32(n) * np.float32(oracle.log1m(q))))
+        assert got == pytest.approx(math.exp(n * math.log1p(-q)), rel=1e-5)
 
 
 def test_binom_walk_matches_library_quantile():
@@ -85,7 +122,7 @@ def test_binom_walk_matches_library_quantile():
             continue
         s = float(np.float32(1.0) - np.float32(q))
         r = float(np.float32(q) / np.float32(s))
-        pm0 = oracle.ipow(s, n)
+        pm0 = oracle.expneg(float(np.float32(n) * np.float32(oracle.log1m(q))))
         for u in rng.uniform(0.001, 0.999, size=8):
             u = float(np.float32(u))
             cdf = stats.binom.cdf(np.arange(n + 1), n, q)
@@ -120,6 +157,75 @@ def test_binom_degenerate_cases():
     assert oracle.binom(0, 0.3, 1, 1, 1, PW(1)) == 0
     assert oracle.binom(9, 0.0, 1, 1, 1, PW(1)) == 0
     assert oracle.binom(9, 1.0, 1, 1, 1, PW(1)) == 9
+
+
+@pytest.mark.parametrize("R,q", [(1_000_000, 1.7e-6), (16_000_000, 1.3e-6), (8_000_000, 1.7e-7), (3_000_000, 0.9999993)])
+def test_binom_keeps_its_mass_for_millions_of_trials(R, q):
+    """Very many trials with a tiny success probability: the rounding of 1-q must not eat the mass of the
+    law.  Mean and P(0) against the binomial law."""
+    n_draws = 6000
+    xs = np.array([oracle.binom(R, q, 23, tau, 2, PW(1)) for tau in range(n_draws)], np.int64)
+    qf = float(np.float32(q))
+    if qf > 0.5:
+        xs, qf = R - xs, 1.0 - qf
+    mean = R * qf
+    assert abs(xs.mean() - mean) < 4.5 * math.sqrt(mean / n_draws) + 2e-4 * mean
+    p0 = math.exp(R * math.log1p(-qf))
+    assert abs(np.mean(xs == 0) - p0) < 4.5 * math.sqrt(p0 * (1 - p0) / n_draws) + 2e-4
+
+
+# --------------------------------------------------------------------------- #
+# the normaliser and its running sums
+@pytest.mark.parametrize("K", [1, 2, 3, 4, 5, 16, 100, 127, 128, 129, 256, 300, 1024, 2048])
+def test_prefix_sums_against_double_and_their_structure(K):
+    """P[k] against the cumulative sum in double; non-decreasing; P[K-1] is the returned normaliser; blocks of
+    4*ceil(K/128) topics, at most 32 of them; integer weights give exact sums whatever the blocking."""
+    T = oracle.block_len(K)
+    assert T % 4 == 0 and T * 32 >= K and (T - 4) * 32 < K
+    assert {1: 4, 128: 4, 129: 8, 256: 8, 1024: 32, 2048: 64}.get(K, T) == T
+    rng = np.random.default_rng(K)
+    w = (rng.gamma(0.3, size=K) + 1e-7).astype(np.float32)
+    w[rng.integers(0, K)] = 0.0                           # a topic without weight repeats the sum before it
+    P, mu = oracle.prefix(w)
+    ref = np.cumsum(w.astype(np.float64))
+    assert np.allclose(P, ref, rtol=(T + K // T + 2) * 2.0 ** -24, atol=0)
+    assert np.all(np.diff(P) >= 0) and mu == float(P[-1])
+    z = np.flatnonzero(w == 0)
+    assert all(P[k] == (P[k - 1] if k else 0.0) for k in z)
+    wi = rng.integers(0, 1000, size=K).astype(np.float32)
+    Pi, mui = oracle.prefix(wi)
+    assert np.array_equal(Pi, np.cumsum(wi.astype(np.int64)).astype(np.float32)) and mui == float(wi.sum(dtype=np.float64))
+
+
+# --------------------------------------------------------------------------- #
+# the highest of R copies
+def test_top_position_is_the_Rth_root():
+    """y = U * u^(1/R) against double arithmetic; one copy is U*u exactly; y never exceeds U and stays positive."""
+    rng = np.random.default_rng(3)
+    for R in [1, 2, 3, 7, 100, 5000, 1_000_000, (1 << 24) - 1]:
+        for _ in range(200):
+            u = oracle.uniform_from_word(int(rng.integers(0, 1 << 32)))
+            U = float(np.float32(rng.gamma(1.0) + 1e-3))
+            y = oracle.top_position(U, R, u)
+            assert 0.0 < y <= U
+            if R == 1:
+                assert y == float(np.float32(U) * np.float32(u))
+            else:
+                assert y == pytest.approx(U * u ** (1.0 / R), rel=3e-6)
+    assert oracle.top_position(1.0, 5, 1.0 - 2.0 ** -24) == 1.0 or oracle.top_position(1.0, 5, 1.0 - 2.0 ** -24) > 0.9999998
+    assert oracle.top_position(1e-44, 3, 2.0 ** -24) > 0.0           # an underflowing product falls back to U
+
+
+@pytest.mark.parametrize("R", [1, 2, 5, 40, 1000])
+def test_top_position_has_the_law_of_the_largest_of_R_uniforms(R):
+    """Distribution function (y/U)^R (Kolmogorov-Smirnov over stream uniforms), and for small R a two-sample
+    test against the maximum of R library uniforms (brute force)."""
+    n = 40000
+    ys = np.array([oracle.top_position(2.5, R, oracle.chain_uniform(5, tau, 0, 0, PW(1))) for tau in range(n)]) / 2.5
+    assert stats.kstest(ys, lambda x: np.clip(x, 0, 1) ** R).pvalue > 1e-4
+    if R <= 40:
+        brute = np.random.default_rng(R).uniform(size=(n, R)).max(axis=1)
+        assert stats.ks_2samp(ys, brute).pvalue > 1e-4
 
 
 # --------------------------------------------------------------------------- #
