@@ -20,28 +20,6 @@
 
 namespace same {
 
-// log x, x a positive normal number: x = 2^e f, f in [sqrt(1/2), sqrt(2)); log f = 2 atanh((f-1)/(f+1))
-// by the odd series through the eleventh power.
-__device__ __forceinline__ float flog(float x)
-{
-    const uint32_t bits = __float_as_uint(x);
-    int e = (int)(bits >> 23) - 127;
-    float f = __uint_as_float((bits & 0x007FFFFFu) | 0x3F800000u);
-    if (f > 1.41421354f) { f = f * 0.5f; e += 1; }
-    const float s = (f - 1.0f) / (f + 1.0f);
-    const float z = s * s;
-    float p = 0.0909090936f;
-    p = p * z; p = p + 0.111111112f;
-    p = p * z; p = p + 0.142857149f;
-    p = p * z; p = p + 0.2f;
-    p = p * z; p = p + 0.333333343f;
-    p = p * z; p = p + 1.0f;
-    float lf = 2.0f * s;
-    lf = lf * p;
-    const float le = (float)e * 0.693147182f;
-    return le + lf;
-}
-
 // cos(2 pi u), u in (0,1): quarter turn, then the Taylor polynomial of sine or cosine on [0, pi/2).
 __device__ __forceinline__ float cos2pi(float u)
 {

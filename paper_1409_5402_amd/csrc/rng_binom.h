@@ -1,4 +1,4 @@
-// Device-side random stream and power helper of the SAME LDA draw (gfx950).
+// Device-side random stream and elementary functions of the SAME LDA draw (gfx950).
 //
 // Every floating-point step here is a single IEEE binary32 operation with one rounding
 // (the file is compiled with -ffp-contract=off); the integer results therefore depend only
@@ -108,22 +108,58 @@ __device__ __forceinline__ void piece_block(const StreamKey& s, uint32_t k, uint
     philox4x32_10(s.tau_lo, s.tau_hi | (pb << 8), 0x80000000u | k, s.pass, s.seed_lo, s.seed_hi, out);
 }
 
-// s^n by binary square-and-multiply, least significant bit first.  The loop runs for the longest
-// exponent among the active lanes without per-lane branches; squarings past a lane's last set
-// bit are never multiplied into its result.
-__device__ __forceinline__ float ipow(float s, uint32_t n)
+// 1/x for an integer-valued x in [1, 2^24): the hardware reciprocal followed by one Newton step
+// equals the correctly rounded quotient for every such x (checked exhaustively by the library's
+// self-test), at a third of the cost of a full division.
+__device__ __forceinline__ float inv_int(float x)
 {
-    float result = 1.0f, base = s;
-    uint32_t e = n;
-    while (__any(e > 0)) {
-        result = (e & 1u) ? result * base : result;
-        base = base * base;
-        e >>= 1;
-    }
-    return result;
+    const float y = __builtin_amdgcn_rcpf(x);
+    const float e = __builtin_fmaf(-x, y, 1.0f);
+    return __builtin_fmaf(y, e, y);
 }
 
-// exp(-y) for 0 <= y <= 32 from + - * only (Poisson form of the draw): t = y*log2(e), n = trunc(t),
+// log x, x a positive normal number: x = 2^e f, f in [sqrt(1/2), sqrt(2)); log f = 2 atanh((f-1)/(f+1))
+// by the odd series through the eleventh power.
+__device__ __forceinline__ float flog(float x)
+{
+    const uint32_t bits = __float_as_uint(x);
+    int e = (int)(bits >> 23) - 127;
+    float f = __uint_as_float((bits & 0x007FFFFFu) | 0x3F800000u);
+    if (f > 1.41421354f) { f = f * 0.5f; e += 1; }
+    const float s = (f - 1.0f) / (f + 1.0f);
+    const float z = s * s;
+    float p = 0.0909090936f;
+    p = p * z; p = p + 0.111111112f;
+    p = p * z; p = p + 0.142857149f;
+    p = p * z; p = p + 0.2f;
+    p = p * z; p = p + 0.333333343f;
+    p = p * z; p = p + 1.0f;
+    float lf = 2.0f * s;
+    lf = lf * p;
+    const float le = (float)e * 0.693147182f;
+    return le + lf;
+}
+
+// -log(1 - x) for 0 < x <= 1/2 without rounding 1 - x (which would lose x below 2^-24):
+// 2 atanh(t) with t = x / (2 - x), by the odd series through the seventeenth power.
+__device__ __forceinline__ float log1m(float x)
+{
+    const float t = x / (2.0f - x);
+    const float z = t * t;
+    float p = 0.0588235296f;
+    p = p * z; p = p + 0.0666666701f;
+    p = p * z; p = p + 0.0769230798f;
+    p = p * z; p = p + 0.0909090936f;
+    p = p * z; p = p + 0.111111112f;
+    p = p * z; p = p + 0.142857149f;
+    p = p * z; p = p + 0.2f;
+    p = p * z; p = p + 0.333333343f;
+    p = p * z; p = p + 1.0f;
+    const float two_t = 2.0f * t;
+    return two_t * p;
+}
+
+// exp(-y) for 0 <= y <= 48 from + - * only: t = y*log2(e), n = trunc(t),
 // f = t-n in [0,1), g = f - 1/2, 2^-(g+1/2) by the degree-7 Taylor polynomial of
 // 2^-1/2 * exp(-g ln 2) in Horner form, every product and sum rounded once, scaled by 2^-n.
 __device__ __forceinline__ float expneg(float y)

@@ -14,7 +14,9 @@
 #include <unordered_map>
 #include <vector>
 
+#include "draw_kernel.h"
 #include "gamma_kernels.h"
+#include "poisson_kernel.h"
 #include "update_kernels.h"
 #include "worklist_kernels.h"
 
@@ -398,16 +400,24 @@ int launch_draw(same_lda* h, const same::DrawArgs& a, bool uniform, bool poisson
 {
     if (a.n <= 0) return SAME_LDA_OK;
     const int T = same::kWave;
-    const size_t lds = same::draw_lds_bytes(a.K);
     const int64_t blocks = (a.n + T - 1) / T;
     if (blocks >= (int64_t)1 << 31) return fail(h, SAME_LDA_EINVAL, "too many draw tasks for one launch");
-    const bool vec = (a.K % same::kBlk) == 0;
     dim3 grid((unsigned)blocks), block((unsigned)T);
-    if (uniform)      hipLaunchKernelGGL((same::draw_kernel<true, false, DEBUG, false>), grid, block, lds, st, a);
-    else if (poisson && vec) hipLaunchKernelGGL((same::draw_kernel<false, true, DEBUG, true>), grid, block, lds, st, a);
-    else if (poisson) hipLaunchKernelGGL((same::draw_kernel<false, false, DEBUG, true>), grid, block, lds, st, a);
-    else if (vec)     hipLaunchKernelGGL((same::draw_kernel<false, true, DEBUG, false>), grid, block, lds, st, a);
-    else              hipLaunchKernelGGL((same::draw_kernel<false, false, DEBUG, false>), grid, block, lds, st, a);
+    if (poisson) {
+        const size_t lds = same::poisson_lds_bytes();
+        if (a.K % same::kBlk == 0) hipLaunchKernelGGL((same::poisson_draw_kernel<true, DEBUG>), grid, block, lds, st, a);
+        else                       hipLaunchKernelGGL((same::poisson_draw_kernel<false, DEBUG>), grid, block, lds, st, a);
+    } else {
+        // blocks of 4 * ceil(K / 128) topics: one or two 16-byte loads per block and matrix up to K = 256
+        const size_t lds = same::draw_lds_bytes();
+        const bool vec = a.K % 4 == 0;
+        const int tb = same::block_len(a.K) / 4;
+        if (uniform)             hipLaunchKernelGGL((same::draw_kernel<true, false, DEBUG, 0>), grid, block, lds, st, a);
+        else if (!vec)           hipLaunchKernelGGL((same::draw_kernel<false, false, DEBUG, 0>), grid, block, lds, st, a);
+        else if (tb == 1)        hipLaunchKernelGGL((same::draw_kernel<false, true, DEBUG, 1>), grid, block, lds, st, a);
+        else if (tb == 2)        hipLaunchKernelGGL((same::draw_kernel<false, true, DEBUG, 2>), grid, block, lds, st, a);
+        else                     hipLaunchKernelGGL((same::draw_kernel<false, true, DEBUG, 0>), grid, block, lds, st, a);
+    }
     HIP_TRY(h, hipGetLastError());
     return SAME_LDA_OK;
 }

@@ -1,0 +1,143 @@
+// What the two draw kernels (multinomial form: draw_kernel.h, Poisson form: poisson_kernel.h) share:
+// the launch arguments, the scatter of a task's counts (Algorithm 3, the two accumulation lines) and
+// the kernel that adds the recorded (topic, count) pairs to the word rows.
+#pragma once
+#include "rng_binom.h"
+
+namespace same {
+
+#ifndef SAME_WALK_STEPS
+#define SAME_WALK_STEPS 8
+#endif
+#ifndef SAME_POOL_MIN
+#define SAME_POOL_MIN 8
+#endif
+constexpr int kWave = 64;               // lanes per workgroup (one wave)
+constexpr int kPairWords = 16;          // words of a pair-list slot: a count and up to 15 (topic, count) pairs
+constexpr int kPairShift = 11;          // a pair is topic | count << 11 (topics < 2048, counts < 2^21)
+constexpr int kWalkSteps = SAME_WALK_STEPS;   // pmf steps per trip of a draw machine
+constexpr float kPieceMean = 32.0f;     // a binomial / Poisson variable whose mean exceeds this is cut into pieces
+constexpr int kPoolMin = SAME_POOL_MIN; // waiting multi-piece variables that trigger a pass shared by the wave
+
+struct DrawArgs {
+    int64_t         n;          // tasks in this launch
+    const int32_t*  t_doc;      // [n_tasks] document of the task
+    const int32_t*  t_word;     // [n_tasks] word of the task
+    const uint32_t* t_g;        // [n_tasks] tokens in the task's group
+    const int32_t*  order;      // [n_tasks] task id handled at each launch position
+    uint32_t*       cost;       // [n_tasks] out: trips this task was busy for (null: not recorded)
+    const int64_t*  ids;        // debug launches: task ids to draw instead (else null)
+    const float*    theta;      // [D][K]   (unused when weights are uniform)
+    const float*    phi;        // [V][K]
+    uint32_t*       ndk;        // [D][K]   (debug launches: [n][K] output rows)
+    uint32_t*       nwk;        // [V][K] or null
+    uint32_t*       pairs;      // [n_slots][kPairWords] pair list in word order, or null (update nwk directly)
+    const int32_t*  t_slot;     // [n_tasks] slot of each task in the pair list, -1 for a task without one
+    int32_t         K;
+    uint32_t        m;          // copies per token (multinomial form)
+    float           mf;         // copies per token (Poisson form: any positive real)
+    uint32_t        seed_lo, seed_hi, pass;
+#ifdef SAME_STATS
+    unsigned long long* stats;  // profiling builds only: event counters
+#endif
+};
+
+#ifdef SAME_STATS
+#define SAME_COUNT(a, i, v) do { if ((a).stats) atomicAdd((a).stats + (i), (unsigned long long)(v)); } while (0)
+#else
+#define SAME_COUNT(a, i, v) do { } while (0)
+#endif
+
+// Where the counts of one task go.  Every placed count goes to the document's row at once.  The word's
+// row is updated either the same way or, when the launch has a pair list, later by word_reduce_kernel:
+// the task records (topic, count) in its slot of the list (slots are in word order), so that the
+// scattered updates of [V][K] become one streaming pass with all updates of a row close together.
+struct Scatter {
+    uint32_t* __restrict__ out_d;     // the document's row (debug launches: the task's output row)
+    uint32_t* __restrict__ out_w;     // the word's row, or null
+    uint32_t* __restrict__ pslot;     // the task's slot in the pair list, or null
+    uint32_t npairs;
+
+    __device__ __forceinline__ void emit(int k, uint32_t n)
+    {
+        atomicAdd(out_d + k, n);
+        if (pslot) {
+            if (npairs < (uint32_t)(kPairWords - 1)) pslot[1u + npairs] = (uint32_t)k | (n << kPairShift);
+            else atomicAdd(out_w + k, n);                          // slot full: straight to the row
+            npairs += 1;
+        } else if (out_w) {
+            atomicAdd(out_w + k, n);
+        }
+    }
+    // the slot's first word: how many pairs it holds
+    __device__ __forceinline__ void close(bool live)
+    {
+        if (pslot && live) pslot[0] = npairs < (uint32_t)(kPairWords - 1) ? npairs : (uint32_t)(kPairWords - 1);
+    }
+};
+
+template <bool DEBUG>
+__device__ __forceinline__ Scatter make_scatter(const DrawArgs& a, int64_t row, int64_t tau, int32_t d, int32_t w)
+{
+    Scatter s;
+    const int K = a.K;
+    s.out_d = DEBUG ? a.ndk + (size_t)row * K : a.ndk + (size_t)d * K;
+    s.out_w = (DEBUG || a.nwk == nullptr) ? nullptr : a.nwk + (size_t)w * K;
+    s.pslot = nullptr;
+    if (!DEBUG && a.pairs != nullptr && s.out_w != nullptr) {
+        const int32_t slot_id = a.t_slot[tau];
+        if (slot_id >= 0) s.pslot = a.pairs + (size_t)slot_id * kPairWords;
+    }
+    s.npairs = 0;
+    return s;
+}
+
+// Adds the recorded pairs to the word rows.  Slots are in word order and exist only for words with
+// at least kSlotMinTasks tasks: a workgroup takes kReduceChunk consecutive slots, sums the pairs of
+// the first `rows` words it meets in an LDS table and sends the rest straight to [V][K]; the table is
+// then added to the rows it stands for.  Threads start at different pairs of their slots: tasks of
+// one word have their large counts at the same topics, and aligned walks would meet at one address.
+constexpr int kReduceChunk = 2048;
+constexpr int kSlotMinTasks = 32;
+constexpr int kReduceThreads = 1024;    // two slots per thread: the kernel waits on its loads, many waves hide that
+
+__global__ __launch_bounds__(kReduceThreads) void word_reduce_kernel(const uint32_t* __restrict__ pairs,
+                                                          const int32_t* __restrict__ slot_word, int64_t n, int K,
+                                                          int rows, uint32_t* __restrict__ nwk)
+{
+    extern __shared__ uint32_t tab[];                              // [rows][K]
+    const int64_t s0 = (int64_t)blockIdx.x * kReduceChunk;
+    const int64_t s1 = s0 + kReduceChunk < n ? s0 + kReduceChunk : n;
+    const int32_t w0 = slot_word[s0];
+    for (int i = threadIdx.x; i < rows * K; i += blockDim.x) tab[i] = 0u;
+    __syncthreads();
+    for (int64_t s = s0 + threadIdx.x; s < s1; s += blockDim.x) {
+        const uint32_t* __restrict__ src = pairs + (size_t)s * kPairWords;
+        const int32_t w = slot_word[s];
+        const bool in_tab = w - w0 < rows;
+        uint32_t* dst = in_tab ? tab + (size_t)(w - w0) * K : nwk + (size_t)w * K;
+        const uint32_t cnt = src[0];
+        uint32_t idx = ((threadIdx.x & 255u) * cnt) >> 8;          // start somewhere in [0, cnt)
+        for (uint32_t i = 0; i < cnt; i += 4u) {                   // four loads in flight, then their updates
+            uint32_t p[4];
+#pragma unroll
+            for (uint32_t j = 0; j < 4u; ++j) {
+                p[j] = (i + j < cnt) ? src[1u + idx] : 0u;
+                idx = idx + 1u >= cnt ? 0u : idx + 1u;
+            }
+#pragma unroll
+            for (uint32_t j = 0; j < 4u; ++j)
+                if (i + j < cnt) atomicAdd(dst + (p[j] & ((1u << kPairShift) - 1u)), p[j] >> kPairShift);
+        }
+    }
+    __syncthreads();
+    uint32_t* base = nwk + (size_t)w0 * K;                         // row w0 + r, topic k is at base[r*K + k]
+    for (int i = threadIdx.x; i < rows * K; i += blockDim.x) {
+        const uint32_t v = tab[i];
+        if (v != 0u) atomicAdd(base + i, v);                       // only rows of real words hold counts
+    }
+}
+
+inline int reduce_rows(int K) { const int r = 16384 / K; return r < 1 ? 1 : (r > 64 ? 64 : r); }
+
+}  // namespace same

@@ -6,7 +6,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-#include "draw_kernel.h"
+#include "rng_binom.h"
 
 namespace same {
 
