@@ -149,6 +149,75 @@ def stream_bench(args):
     print(json.dumps(out))
 
 
+def stats_bench(args):
+    """Event counts of the draw kernel (an event-counting build of the library, paper_1409_5402_amd/build.py
+    --stats): steps, trips, pmf terms and shared passes per task at three states of the news-shaped workload -
+    the first sweep at m after the random start (flat posteriors), the last burn-in sweep at m=1, and the
+    converged state the headline is timed at."""
+    import ctypes
+    import torch
+    from paper_1409_5402_amd import binding, build, synth
+
+    if not os.path.exists(build.STATS_LIB):
+        build.build(stats=True)
+    L = binding.load(build.STATS_LIB)
+    L.same_lda_stats_buffer.argtypes = [ctypes.c_void_p]
+    L.same_lda_stats_buffer.restype = None
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    p = synth.PRESETS[args.workload]
+    K, m, alpha, beta, G = p["K"], p["m"], p["alpha"], p["beta"], args.tokens_per_draw
+    corpus = synth.preset(args.workload, device=dev, scale=args.scale)
+    n_train = corpus.D - corpus.D // 10 if corpus.D >= 10 else corpus.D
+    train = corpus.slice_docs(0, n_train)
+    stats = torch.zeros(48, dtype=torch.int64, device=dev)
+
+    def measured(g, mm, what):
+        stats.zero_()
+        L.same_lda_stats_buffer(stats.data_ptr())
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        g.sweep(mm)
+        g.synchronize()
+        ms = 1e3 * (time.perf_counter() - t0)
+        L.same_lda_stats_buffer(None)
+        v = stats.cpu().numpy()
+        nt = g.task_count
+        nw = (nt + 63) // 64
+        return {"state": what, "m": mm, "sweep_ms_with_counters": round(ms, 2),
+                "steps_per_task": round(v[1] / nt, 3), "trips_per_64_tasks": round(v[2] / nw, 2),
+                "block_reloads_per_task": round(v[3] / nt, 3),
+                "pmf_terms_per_task": round(v[4] / nt, 3), "binomials_per_task": round(v[5] / nt, 3),
+                "shared_passes_per_64_tasks": round(v[6] / nw, 4), "shared_pieces_per_64_tasks": round(v[7] / nw, 3),
+                "lanes_per_trip": {"stepping": round(v[8] / max(v[2], 1), 2), "walking_on": round(v[9] / max(v[2], 1), 2),
+                                   "waiting_for_a_shared_pass": round(v[10] / max(v[2], 1), 2),
+                                   "idle": round(v[11] / max(v[2], 1), 2)},
+                "pmf_rounds_per_trip": round(v[12] / max(v[2], 1), 3), "refills_per_64_tasks": round(v[13] / nw, 3),
+                "counts_past_a_full_slot_per_task": round(sum(v[16:22]) / nt, 4),
+                "of_them_by_group_size_1_2_4_8_16_32up": [int(x) for x in v[16:22]],
+                "of_them_by_word_id_below_16_256_4096_rest": [int(x) for x in v[22:26]]}
+
+    out = []
+    g = binding.SameLDA(train.D, train.V, train.colptr, train.rowidx, train.val, K, alpha, beta, seed=2, m0=1,
+                        tokens_per_draw=G)
+    out.append(measured(g, m, f"first sweep at m={m} after the random start"))
+    g.close()
+    g = binding.SameLDA(train.D, train.V, train.colptr, train.rowidx, train.val, K, alpha, beta, seed=2, m0=1,
+                        tokens_per_draw=G)
+    for _ in range(args.burn_in[0] - 1):
+        g.sweep(1)
+    out.append(measured(g, 1, f"sweep {args.burn_in[0]} of the burn-in at m=1"))
+    for _ in range(args.burn_in[1] + args.warmup):
+        g.sweep(m)
+    out.append(measured(g, m, f"converged state: {args.burn_in[0]} sweeps at m=1, {args.burn_in[1] + args.warmup} at m={m}"))
+    theta_s, phi_s = synth.state(train, K, alpha, beta, seed=123, zipf_s=p["gen"].get("zipf_s", 0.0))
+    g.set(binding.THETA, theta_s)
+    g.set(binding.PHI, phi_s)
+    out.append(measured(g, m, "seeded concentrated state (synth.state, seed 123)"))
+    g.close()
+    print(json.dumps({"workload": f"{args.workload} (scale {args.scale})", "K": K, "tokens_per_draw": G, "states": out}))
+
+
 def sddmm_bench(args):
     """The normaliser of Algorithm 3 alone (SDDMM, Section 5.3) over the news-shaped matrix at full size."""
     import torch
@@ -215,9 +284,10 @@ def main():
     ap.add_argument("--update", choices=["collapsed", "sampled"], default="collapsed",
                     help="parameter step: the posterior means of Eq. 6 (what the paper runs, the headline) or "
                          "Dirichlet draws of theta and phi (Algorithm 2, third step; multinomial form only)")
-    ap.add_argument("--mode", choices=["resident", "stream", "sddmm"], default="resident",
+    ap.add_argument("--mode", choices=["resident", "stream", "sddmm", "stats"], default="resident",
                     help="resident: sweeps over one matrix held in HBM (the headline); stream: one sweep per "
-                         "minibatch of a stream of host-resident minibatches; sddmm: the normaliser alone")
+                         "minibatch of a stream of host-resident minibatches; sddmm: the normaliser alone; "
+                         "stats: event counts of the draw kernel from a counting build of the library")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-spec-run", action="store_true",
                     help="skip the legs beside the headline: the workload's specified run from the random start "
@@ -241,6 +311,8 @@ def main():
         args.warmup = 10
     if args.mode == "sddmm":
         return sddmm_bench(args)
+    if args.mode == "stats":
+        return stats_bench(args)
     import oracle
     from paper_1409_5402_amd import binding, synth
 

@@ -43,17 +43,20 @@ class _Csc(Structure):
 _lib = None
 
 
-def load() -> ctypes.CDLL:
-    """Loads the built library; raises if it is missing (build it with paper_1409_5402_amd.build)."""
+def load(path: str | None = None) -> ctypes.CDLL:
+    """Loads the built library; raises if it is missing (build it with paper_1409_5402_amd.build).  `path` (or the
+    environment variable SAME_LDA_LIB) names another build of the same library, e.g. the event-counting build of
+    bench.py --mode stats; the first load of a process decides."""
     global _lib
     if _lib is None:
-        if not os.path.exists(LIB_PATH):
-            raise FileNotFoundError(f"{LIB_PATH} is missing: run paper_1409_5402_amd.build.build() first")
+        path = path or os.environ.get("SAME_LDA_LIB") or LIB_PATH
+        if not os.path.exists(path):
+            raise FileNotFoundError(f"{path} is missing: run paper_1409_5402_amd.build.build() first")
         try:
             import torch  # noqa: F401  (where torch is installed, its HIP runtime must be the one loaded first:
         except ImportError:             # the library then binds to the same runtime as the tensors it is given)
             pass
-        L = ctypes.CDLL(LIB_PATH)
+        L = ctypes.CDLL(path)
         L.same_lda_init.argtypes = [POINTER(c_void_p), POINTER(_Csc), c_int32, c_float, c_float, c_uint64,
                                     c_int32, c_int32, c_void_p]
         L.same_lda_sweep.argtypes = [c_void_p, c_int32, c_float]

@@ -15,18 +15,24 @@ FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-ffp-contract=off",
          "-fPIC", "-shared", "-Wall", "-Wextra", "-Wno-unused-value"]
 
 
-def build(verbose: bool = False) -> str:
+STATS_LIB = os.path.join(HERE, "libsame_lda_stats.so")
+
+
+def build(verbose: bool = False, stats: bool = False) -> str:
+    """stats=True builds a second library whose draw kernel counts its own events (steps, trips, pmf terms,
+    shared passes) into a device buffer given through same_lda_stats_buffer: for `bench.py --mode stats` only."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *FLAGS, "-o", LIB, *SRC]
+    cmd = [hipcc, *FLAGS, *(["-DSAME_STATS"] if stats else []), "-o", STATS_LIB if stats else LIB, *SRC]
     res = subprocess.run(cmd, capture_output=True, text=True)
     if verbose or res.returncode != 0:
         print(" ".join(cmd))
         print(res.stdout)
         print(res.stderr)
     if res.returncode != 0:
-        raise RuntimeError("hipcc failed building libsame_lda.so")
-    return LIB
+        raise RuntimeError("hipcc failed building the library")
+    return STATS_LIB if stats else LIB
 
 
 if __name__ == "__main__":
-    print(build(verbose=True))
+    import sys
+    print(build(verbose=True, stats="--stats" in sys.argv))

@@ -53,122 +53,60 @@ __device__ __forceinline__ float top_position(float U, uint32_t R, float u)
     return y;
 }
 
+#ifndef SAME_REFILL_MIN
+#define SAME_REFILL_MIN 24
+#endif
+#ifndef SAME_WALK_ROUNDS
+#define SAME_WALK_ROUNDS 4
+#endif
+constexpr int kRefillMin = SAME_REFILL_MIN;     // idle lanes that make the wave fetch new tasks
+constexpr int kWalkRounds = SAME_WALK_ROUNDS;   // rounds of kWalkSteps pmf terms per trip, while some lane needs them
+
 // TB: float4 loads per block and matrix when known at compile time (1 for K <= 128, 2 for K <= 256),
 // 0: taken from K at run time.  VEC: K is a multiple of 4 (16-byte loads), else element-wise loads.
+//
+// The launch positions are handed out in segments of kSegment consecutive positions through a counter in
+// device memory (a.counter, zero at launch): a workgroup (one wave) takes a segment, its lanes take the
+// segment's tasks as they become free, and when the segment is used up the wave takes the next one.  Tasks
+// differ widely in the number of steps they need (one for most, a hundred for a few): a lane that waited
+// for the slowest of 64 fixed tasks would idle most of the time, and a wave with a fixed share of the matrix
+// would end with one lane busy.  Whenever kRefillMin lanes are idle the wave stops stepping, gives each idle
+// lane the next position, scans the new tasks (two per instruction) and goes on.
+constexpr int kSegment = 256;
+
 template <bool UNIFORM, bool VEC, bool DEBUG, int TB>
 __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
 {
     extern __shared__ uint32_t lds[];
-    float* sums = reinterpret_cast<float*>(lds);                   // [64 tasks][kSumStride]
+    float* sums = reinterpret_cast<float*>(lds);                   // [64 lanes][kSumStride]: block sums, then running sums
     uint32_t* acc = lds + (size_t)kWave * kSumStride;              // [64] piece totals by owner lane
     const int lane = threadIdx.x;
     const int K = a.K;
     const int T = TB > 0 ? 4 * TB : block_len(K);                  // topics per block
     const int nblk = (K + T - 1) / T;                              // blocks in use (<= 32)
-
-    // lanes past the end take the last task with zero copies: all loads stay valid, nothing is emitted
-    const int64_t slot = (int64_t)blockIdx.x * kWave + lane;
-    const bool live = slot < a.n;
-    const int64_t row = live ? slot : a.n - 1;
-    // order holds non-negative 32-bit ids: the high byte of tau is then a constant zero for the whole launch
-    const int64_t tau = DEBUG ? a.ids[row] : (int64_t)(uint32_t)a.order[row];
-    const int32_t d = a.t_doc[tau];
-    const int32_t w = a.t_word[tau];
-    const uint32_t N = live ? a.m * a.t_g[tau] : 0u;
-    const float* __restrict__ th = UNIFORM ? nullptr : a.theta + (size_t)d * K;
-    const float* __restrict__ ph = UNIFORM ? nullptr : a.phi + (size_t)w * K;
-    Scatter sc = make_scatter<DEBUG>(a, row, tau, d, w);
+    const int half = lane >> 5, hl = lane & 31;
+    int32_t next = 0, end = 0;                                     // the wave's segment: positions not yet handed out
+    bool drained = false;                                          // the counter has passed the last position
     acc[lane] = 0u;
 
-    // ---- scan: the block sums of the wave's 64 tasks, two tasks at a time
-    if (UNIFORM) {
-        // all weights are 1: block l holds min(T, K - l*T) topics
-        for (int l = 0; l < nblk; ++l) sums[lane * kSumStride + l] = (float)(min(K, (l + 1) * T) - l * T);
-    } else {
-        const int half = lane >> 5, hl = lane & 31;
-        const int k0 = hl * T;
-        if (VEC && TB > 0) {
-            // all loads of a task pair are issued before the previous pair is summed
-            float4 pv[TB > 0 ? TB : 1], tv[TB > 0 ? TB : 1];
-            auto issue = [&](int p) {
-                const int src = 2 * p + half;
-                const int32_t pd = __shfl(d, src), pw = __shfl(w, src);
-                const float* __restrict__ tp = a.theta + (size_t)pd * K + k0;
-                const float* __restrict__ pp = a.phi + (size_t)pw * K + k0;
-#pragma unroll
-                for (int c = 0; c < TB; ++c) {
-                    if (k0 + 4 * c < K) {
-                        pv[c] = *reinterpret_cast<const float4*>(pp + 4 * c);
-                        tv[c] = *reinterpret_cast<const float4*>(tp + 4 * c);
-                    } else {
-                        pv[c] = make_float4(0.f, 0.f, 0.f, 0.f);
-                        tv[c] = make_float4(0.f, 0.f, 0.f, 0.f);
-                    }
-                }
-            };
-            issue(0);
-            for (int p = 0; p < kWave / 2; ++p) {
-                float4 cp[TB > 0 ? TB : 1], ct[TB > 0 ? TB : 1];
-#pragma unroll
-                for (int c = 0; c < TB; ++c) { cp[c] = pv[c]; ct[c] = tv[c]; }
-                if (p + 1 < kWave / 2) issue(p + 1);
-                float r = 0.0f;
-#pragma unroll
-                for (int c = 0; c < TB; ++c) {
-                    r = r + ct[c].x * cp[c].x;
-                    r = r + ct[c].y * cp[c].y;
-                    r = r + ct[c].z * cp[c].z;
-                    r = r + ct[c].w * cp[c].w;
-                }
-                sums[(2 * p + half) * kSumStride + hl] = r;
-            }
-        } else {
-            for (int p = 0; p < kWave / 2; ++p) {
-                const int src = 2 * p + half;
-                const int32_t pd = __shfl(d, src), pw = __shfl(w, src);
-                const float* __restrict__ tp = a.theta + (size_t)pd * K;
-                const float* __restrict__ pp = a.phi + (size_t)pw * K;
-                float r = 0.0f;
-                if (VEC) {
-                    for (int c = 0; c < T / 4; ++c) {
-                        const int k = k0 + 4 * c;
-                        if (k < K) {
-                            const float4 x = *reinterpret_cast<const float4*>(pp + k);
-                            const float4 t = *reinterpret_cast<const float4*>(tp + k);
-                            r = r + t.x * x.x;
-                            r = r + t.y * x.y;
-                            r = r + t.z * x.z;
-                            r = r + t.w * x.w;
-                        }
-                    }
-                } else {
-                    for (int j = 0; j < T; ++j) {
-                        const int k = k0 + j;
-                        if (k < K) r = r + tp[k] * pp[k];
-                    }
-                }
-                sums[src * kSumStride + hl] = r;
-            }
-        }
-    }
-    __syncthreads();
-
-    // ---- the lane's own task: running sums over its blocks, S_l in place of the block sums
-    float U = 0.0f;
-    for (int l = 0; l < nblk; ++l) {
-        U = U + sums[lane * kSumStride + l];
-        sums[lane * kSumStride + l] = U;
-    }
-
+    // ---- the lane's current task
+#ifdef SAME_STATS
+    uint32_t R_task_g = 0;
+#endif
+    bool open = false;      // a task was taken and its slot of the pair list is not yet closed
+    int32_t d = 0, w = 0;
+    const float* __restrict__ th = nullptr;
+    const float* __restrict__ ph = nullptr;
+    Scatter sc;
+    sc.out_d = nullptr; sc.out_w = nullptr; sc.pslot = nullptr; sc.npairs = 0;
     StreamKey key;
-    key.seed_lo = a.seed_lo; key.seed_hi = a.seed_hi;
-    key.tau_lo = (uint32_t)tau; key.tau_hi = (uint32_t)((uint64_t)tau >> 32) & 0xFFu;
-    key.pass = a.pass;
-    const PrimaryPre pre = primary_pre(key);
+    key.seed_lo = a.seed_lo; key.seed_hi = a.seed_hi; key.tau_lo = 0; key.tau_hi = 0; key.pass = a.pass;
+    PrimaryPre pre = primary_pre(key);
 
-    // ---- the draw: a per-lane state machine
-    uint32_t R = N;         // copies not yet placed, all of them below U
-    int lt = nblk - 1;      // block that holds U
+    // ---- the draw of that task: a per-lane state machine
+    uint32_t R = 0;         // copies not yet placed, all of them below U
+    float U = 0.0f;
+    int lt = 0;             // block that holds U
     int top = K;            // the copies left belong to topics below top
     uint32_t step = 0;      // steps taken: the next one uses words 2*(step & 1), +1 of block step >> 1
     uint32_t xs2 = 0, xs3 = 0;   // the second half of the last Philox block, for the odd step
@@ -178,22 +116,130 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
     float r = 0.f, lq = 0.f, pm = 0.f, cdf = 0.f, u = 0.f;
     bool flip = false, stalled = false;
     int kk = 0;
-    uint32_t busy = 0;      // trips in which this lane had work: its cost for the next ordering
 
-    // A finished binomial of bR trials with x successes of the sampled side: topic kk receives the step's
-    // top copy and the copies that share its topic.
-    auto finish = [&](uint32_t x) {
-        const uint32_t nk = flip ? bR - x : x;
-        sc.emit(kk, 1u + nk);
-        R -= nk;
-        st = 0;
-        SAME_COUNT(a, 5, 1);
+    // Idle lanes take the next positions, the wave scans the new tasks' block sums (two tasks at a time, one
+    // per half-wave: lane hl of a half owns block hl), each new lane turns its sums into running sums.
+    auto refill = [&](uint64_t idle_mask) {
+        const bool idle = (idle_mask >> lane) & 1ull;
+        if (idle && open) { sc.close(true); open = false; }
+        const int rank = (int)__popcll(idle_mask & ((1ull << lane) - 1ull));
+        const int avail = end - next;
+        const bool take = idle && rank < avail;
+        if (take) {
+            const int64_t pos = (int64_t)next + rank;
+            const int64_t tau = DEBUG ? a.ids[pos] : pos;
+            d = a.t_doc[tau];
+            w = a.t_word[tau];
+            R = a.m * a.t_g[tau];
+#ifdef SAME_STATS
+            R_task_g = a.t_g[tau];
+#endif
+            th = UNIFORM ? nullptr : a.theta + (size_t)d * K;
+            ph = UNIFORM ? nullptr : a.phi + (size_t)w * K;
+            sc = make_scatter<DEBUG>(a, pos, tau, d, w);
+            key.tau_lo = (uint32_t)tau; key.tau_hi = (uint32_t)((uint64_t)tau >> 32) & 0xFFu;
+            pre = primary_pre(key);
+            open = true;
+            lt = nblk - 1; top = K; step = 0; st = 0;
+        }
+        const int n_idle = (int)__popcll(idle_mask);
+        next += n_idle < avail ? n_idle : avail;
+        uint64_t fresh = __ballot(take);
+        if (UNIFORM) {
+            // all weights are 1: block l holds min(T, K - l*T) topics
+            if (take) for (int l = 0; l < nblk; ++l) sums[lane * kSumStride + l] = (float)(min(K, (l + 1) * T) - l * T);
+        } else {
+            const int k0 = hl * T;
+            // the next pair of new lanes: one for each half-wave (the last one twice if their number is odd)
+            auto pick = [&](uint64_t& rem) {
+                const int la = __ffsll((unsigned long long)rem) - 1;
+                rem &= rem - 1;
+                int lb = la;
+                if (rem) { lb = __ffsll((unsigned long long)rem) - 1; rem &= rem - 1; }
+                return half ? lb : la;
+            };
+            if (VEC && TB > 0) {
+                // the loads of a task pair are issued before the previous pair is summed
+                float4 pv[TB > 0 ? TB : 1], tv[TB > 0 ? TB : 1];
+                auto issue = [&](int src) {
+                    const int32_t pd = __shfl(d, src), pw = __shfl(w, src);
+                    const float* __restrict__ tp = a.theta + (size_t)pd * K + k0;
+                    const float* __restrict__ pp = a.phi + (size_t)pw * K + k0;
+#pragma unroll
+                    for (int c = 0; c < TB; ++c) {
+                        if (k0 + 4 * c < K) {
+                            pv[c] = *reinterpret_cast<const float4*>(pp + 4 * c);
+                            tv[c] = *reinterpret_cast<const float4*>(tp + 4 * c);
+                        } else {
+                            pv[c] = make_float4(0.f, 0.f, 0.f, 0.f);
+                            tv[c] = make_float4(0.f, 0.f, 0.f, 0.f);
+                        }
+                    }
+                };
+                int src = 0;
+                bool more = fresh != 0;
+                if (more) { src = pick(fresh); issue(src); }
+                while (more) {
+                    const int cur = src;
+                    float4 cp[TB > 0 ? TB : 1], ct[TB > 0 ? TB : 1];
+#pragma unroll
+                    for (int c = 0; c < TB; ++c) { cp[c] = pv[c]; ct[c] = tv[c]; }
+                    more = fresh != 0;
+                    if (more) { src = pick(fresh); issue(src); }
+                    float rs = 0.0f;
+#pragma unroll
+                    for (int c = 0; c < TB; ++c) {
+                        rs = rs + ct[c].x * cp[c].x;
+                        rs = rs + ct[c].y * cp[c].y;
+                        rs = rs + ct[c].z * cp[c].z;
+                        rs = rs + ct[c].w * cp[c].w;
+                    }
+                    sums[cur * kSumStride + hl] = rs;
+                }
+            } else {
+                while (fresh) {
+                    const int src = pick(fresh);
+                    const int32_t pd = __shfl(d, src), pw = __shfl(w, src);
+                    const float* __restrict__ tp = a.theta + (size_t)pd * K;
+                    const float* __restrict__ pp = a.phi + (size_t)pw * K;
+                    float rs = 0.0f;
+                    if (VEC) {
+                        for (int c = 0; c < T / 4; ++c) {
+                            const int k = k0 + 4 * c;
+                            if (k < K) {
+                                const float4 x = *reinterpret_cast<const float4*>(pp + k);
+                                const float4 t = *reinterpret_cast<const float4*>(tp + k);
+                                rs = rs + t.x * x.x;
+                                rs = rs + t.y * x.y;
+                                rs = rs + t.z * x.z;
+                                rs = rs + t.w * x.w;
+                            }
+                        }
+                    } else {
+                        for (int j = 0; j < T; ++j) {
+                            const int k = k0 + j;
+                            if (k < K) rs = rs + tp[k] * pp[k];
+                        }
+                    }
+                    sums[src * kSumStride + hl] = rs;
+                }
+            }
+        }
+        __syncthreads();
+        if (take) {
+            float run = 0.0f;
+            for (int l = 0; l < nblk; ++l) {
+                run = run + sums[lane * kSumStride + l];
+                sums[lane * kSumStride + l] = run;
+            }
+            U = run;
+        }
     };
 
     // Binomials cut into pieces.  The pieces are independent (own uniform each): those of all the
     // lanes in state 3 are numbered consecutively and dealt out over the 64 lanes; every owner
-    // receives the total of its pieces through an LDS counter.
-    auto pool = [&](uint64_t pend) {
+    // receives the total of its pieces through an LDS counter.  Returns the owner's successes.
+    auto pool = [&](uint64_t pend) -> uint32_t {
         const uint32_t np = (st == 3) ? (bR + L - 1u) / L : 0u;
         uint32_t total = 0;
         for (uint64_t p = pend; p != 0; p &= p - 1) total += __shfl(np, __ffsll((unsigned long long)p) - 1);
@@ -231,30 +277,39 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
                     pmj = pmj * orr;
                     pmj = pmj * (float)(nj - xj + 1u);
                     pmj = pmj * inv_int((float)xj);
-                    const float next = cdfj + pmj;
-                    if (next == cdfj) break;
-                    cdfj = next;
+                    const float next_cdf = cdfj + pmj;
+                    if (next_cdf == cdfj) break;
+                    cdfj = next_cdf;
                 }
                 if (xj > 0) atomicAdd(acc + owner, xj);
             }
         }
         __syncthreads();
-        if (st == 3) {
-            const uint32_t part = acc[lane];
-            acc[lane] = 0u;
-            finish(part);
-        }
+        uint32_t part = 0;
+        if (st == 3) { part = acc[lane]; acc[lane] = 0u; }
         __syncthreads();
+        return part;
     };
 
     // One trip of the machine for the whole wave.
     auto trip = [&]() {
         if (lane == 0) SAME_COUNT(a, 2, 1);
-        busy += (st != 0 || R > 0) ? 1u : 0u;
+#ifdef SAME_STATS
+        {   // lanes by what they do in this trip: step, walk on, wait for a shared pass, idle
+            const uint64_t b_step = __ballot(st == 0 && R > 0), b_walk = __ballot(st == 1), b_wait = __ballot(st == 3);
+            if (lane == 0) {
+                SAME_COUNT(a, 8, __popcll((unsigned long long)b_step)); SAME_COUNT(a, 9, __popcll((unsigned long long)b_walk));
+                SAME_COUNT(a, 10, __popcll((unsigned long long)b_wait));
+                SAME_COUNT(a, 11, 64 - __popcll((unsigned long long)(b_step | b_walk | b_wait)));
+            }
+        }
+#endif
+        int ek = 0;             // the count this trip settles for this lane: en copies to topic ek
+        uint32_t en = 0;
         if (st == 0 && R > 0) {
             SAME_COUNT(a, 1, 1);                                   // steps
             if (!(U > 0.0f)) {                                     // no weight left: a degenerate input
-                sc.emit(top > 0 ? top - 1 : 0, R);
+                ek = top > 0 ? top - 1 : 0; en = R;
                 R = 0;
             } else {
                 uint32_t xa, xb;
@@ -334,10 +389,10 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
                 bstep = step;
                 U = prev; lt = l; top = k; step += 1u;
                 if (Rm == 0u || !(q > 0.0f)) {
-                    sc.emit(k, 1u);
+                    ek = k; en = 1u;
                     R = Rm;
                 } else if (q >= 1.0f) {
-                    sc.emit(k, R);
+                    ek = k; en = R;
                     R = 0;
                 } else {
                     flip = q > 0.5f;
@@ -346,7 +401,7 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
                     r = qq / s1;
                     lq = log1m(qq);
                     bR = Rm;
-                    R = Rm;                                        // finish() takes the binomial's share off
+                    R = Rm;                                        // the binomial's share comes off when it is known
                     u = uniform_from_word(xb);
                     if (((float)Rm * qq) <= kPieceMean) {          // one piece of Rm trials
                         L = Rm;
@@ -362,35 +417,77 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
         }
         {
             const uint64_t pend = __ballot(st == 3);
-            if (pend != 0 && (__popcll((unsigned long long)pend) >= kPoolMin || !__any(st == 1 || (st == 0 && R > 0))))
-                pool(pend);
+            if (pend != 0 && (__popcll((unsigned long long)pend) >= kPoolMin || !__any(st == 1 || (st == 0 && R > 0)))) {
+                const uint32_t part = pool(pend);
+                if (st == 3) {
+                    const uint32_t nk = flip ? bR - part : part;
+                    ek = kk; en = 1u + nk;
+                    R -= nk;
+                    st = 0;
+                    SAME_COUNT(a, 5, 1);
+                }
+            }
         }
         if (__any(st == 1)) {
             const bool walking = st == 1;
+            bool more = walking && !stalled && u > cdf && xw < L;
+            for (int round = 0; round < kWalkRounds && __any(more); ++round) {
+                if (lane == 0) SAME_COUNT(a, 12, 1);               // rounds of pmf terms
 #pragma unroll
-            for (int i = 0; i < kWalkSteps; ++i) {
-                const bool go = walking && !stalled && u > cdf && xw < L;
-                const uint32_t xn = xw + 1u;
-                float pmn = pm * r;
-                pmn = pmn * (float)(L - xn + 1u);
-                pmn = pmn * inv_int((float)xn);
-                const float next = cdf + pmn;
-                const bool still = next == cdf;
-                if (go) SAME_COUNT(a, 4, 1);                       // walk steps
-                xw = go ? xn : xw;
-                pm = go ? pmn : pm;
-                cdf = (go && !still) ? next : cdf;
-                stalled = stalled || (go && still);
+                for (int i = 0; i < kWalkSteps; ++i) {
+                    const uint32_t xn = xw + 1u;
+                    float pmn = pm * r;
+                    pmn = pmn * (float)(L - xn + 1u);
+                    pmn = pmn * inv_int((float)xn);
+                    const float next_cdf = cdf + pmn;
+                    const bool still = next_cdf == cdf;
+                    if (more) SAME_COUNT(a, 4, 1);                 // pmf terms
+                    xw = more ? xn : xw;
+                    pm = more ? pmn : pm;
+                    cdf = (more && !still) ? next_cdf : cdf;
+                    stalled = stalled || (more && still);
+                    more = more && !still && u > cdf && xw < L;
+                }
             }
-            if (walking && (stalled || !(u > cdf && xw < L))) finish(xw);
+            if (walking && !more) {                                // the binomial is known
+                const uint32_t nk = flip ? bR - xw : xw;
+                ek = kk; en = 1u + nk;
+                R -= nk;
+                st = 0;
+                SAME_COUNT(a, 5, 1);
+            }
         }
+#ifdef SAME_STATS
+        if (en > 0u && sc.pslot && sc.npairs >= (uint32_t)(kPairWords - 1)) {   // a count that finds its slot full
+            const uint32_t g = R_task_g;
+            SAME_COUNT(a, 16 + min(5, 31 - __clz((int)max(g, 1u))), 1);
+            SAME_COUNT(a, 22 + (w < 16 ? 0 : w < 256 ? 1 : w < 4096 ? 2 : 3), 1);
+        }
+#endif
+        if (en > 0u) sc.emit(ek, en);
     };
 
-    while (__any(st != 0 || R > 0)) trip();
-    sc.close(live);
-    // The ordering key for the next pass: a running mean (weight 1/4 on this pass) predicts a task's next
-    // cost a little better than this pass's cost alone.
-    if (!DEBUG && live && a.cost) a.cost[tau] = (3u * a.cost[tau] + busy + 2u) >> 2;
+    for (;;) {
+        const uint64_t idle_mask = __ballot(st == 0 && R == 0);
+        if (!drained && (__popcll((unsigned long long)idle_mask) >= kRefillMin || idle_mask == ~0ull)) {
+            if (next >= end) {                                     // the next segment (all lanes obtain the same value)
+                uint32_t first = 0;
+                if (lane == 0) first = atomicAdd(a.counter, (uint32_t)kSegment);
+                first = (uint32_t)__builtin_amdgcn_readfirstlane((int)first);
+                drained = (int64_t)first >= a.n;
+                next = drained ? 0 : (int32_t)first;
+                end = drained ? 0 : (int32_t)((int64_t)first + kSegment < a.n ? (int64_t)first + kSegment : a.n);
+            }
+            if (next < end) {
+                if (lane == 0) SAME_COUNT(a, 13, 1);               // refills
+                refill(idle_mask);
+                continue;
+            }
+        }
+        if (idle_mask == ~0ull) break;                             // nothing in flight and nothing left to take
+        trip();
+    }
+    if (open) sc.close(true);
 }
 
 inline size_t draw_lds_bytes() { return 4u * (size_t)kWave * (size_t)(kSumStride + 1); }

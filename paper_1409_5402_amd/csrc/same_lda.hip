@@ -54,6 +54,10 @@ struct Matrix {
     int64_t   n_slots = 0;         // tasks of frequent words, each with a slot
     int32_t*  t_slot = nullptr;    // [n_tasks] slot of each task (rank in (word, task id) order), -1 if none
     int32_t*  slot_word = nullptr; // [n_slots] word of each slot
+    // hot words (training matrices only): their rows of the word-count matrix have private copies
+    int16_t*  hot_of = nullptr;    // [V] number of a hot word, -1 for the others
+    int32_t*  hot_word = nullptr;  // [kHotMax] the hot words by number
+    int32_t   n_hot = 0;
 };
 
 }  // namespace
@@ -119,6 +123,7 @@ struct same_lda {
     float* phi = nullptr;          // [V][K]
     uint32_t* nwk = nullptr;       // [V][K]
     unsigned long long* nk = nullptr;  // [K]
+    uint32_t* draw_counter = nullptr;  // [2] segment counters of the draw kernel: launches on the handle's stream, on the copy stream
     double* gamma_partial = nullptr;   // [ceil(V / kGammaRows)][K] block sums of the sampled phi step
     float* gamma_total = nullptr;      // [K]
     bool timing = false;
@@ -170,6 +175,7 @@ void free_matrix(same_lda* h, Matrix& M)
     dev_free(h, M.colptr); dev_free(h, M.t_doc); dev_free(h, M.t_word); dev_free(h, M.t_g); dev_free(h, M.order);
     dev_free(h, M.tile_start); dev_free(h, M.cost); dev_free(h, M.nz_doc); dev_free(h, M.rowidx); dev_free(h, M.val);
     dev_free(h, M.theta); dev_free(h, M.ndk); dev_free(h, M.pairs); dev_free(h, M.t_slot); dev_free(h, M.slot_word);
+    dev_free(h, M.hot_of); dev_free(h, M.hot_word);
     M = Matrix();
 }
 
@@ -255,6 +261,12 @@ int build_matrix(same_lda* h, const same_lda_csc* X, int32_t V, int32_t K, int32
         const int32_t most = D > V ? D : V;
         hipLaunchKernelGGL(same::wl_token_argmax, dim3((unsigned)((most + 255) / 256)), dim3(256), 0, st, doc_tok, D,
                            word_tok, V, d_stats);
+        if (with_pairs) {                                      // the words whose rows get private copies (scatter.h)
+            if ((rc = dev_alloc(h, &M.hot_of, (size_t)V))) return rc;
+            if ((rc = dev_alloc(h, &M.hot_word, (size_t)same::kHotMax))) return rc;
+            hipLaunchKernelGGL(same::wl_hot_words, dim3((unsigned)((V + 255) / 256)), dim3(256), 0, st, word_tok, V,
+                               (int32_t)same::kHotMax, M.hot_of, M.hot_word, d_stats);
+        }
     }
     HIP_TRY(h, hipGetLastError());
     same::BuildStats stats;
@@ -274,6 +286,7 @@ int build_matrix(same_lda* h, const same_lda_csc* X, int32_t V, int32_t K, int32
     M.n_tasks = (int64_t)n; M.max_group = stats.max_group; M.tokens = (double)stats.tokens;
     M.max_doc_tokens = stats.max_doc_tokens; M.max_word_tokens = stats.max_word_tokens;
     M.max_doc = (int32_t)stats.max_doc; M.max_word = (int32_t)stats.max_word;
+    M.n_hot = M.hot_of ? (int32_t)(stats.n_hot < (uint32_t)same::kHotMax ? stats.n_hot : (uint32_t)same::kHotMax) : 0;
     M.with_words = with_pairs;
 
     // Processing order: documents are taken in tiles of kTileDocs (the theta rows a wave touches stay
@@ -395,19 +408,34 @@ int check_m(same_lda* h, int32_t m, const Matrix& M)
     return check_accumulators(h, (double)m, 0.0, M);
 }
 
+// The multinomial kernel's segment counter for a launch on st, set to zero on st (a launch of its own, so
+// that the events around the draw kernel bracket that kernel alone).
+int prepare_counter(same_lda* h, same::DrawArgs& a, hipStream_t st)
+{
+    a.counter = (st == h->copy_stream && st != h->stream) ? h->draw_counter + 1 : h->draw_counter;
+    hipLaunchKernelGGL(same::zero_u32_kernel, dim3(1), dim3(64), 0, st, a.counter, (size_t)1);
+    HIP_TRY(h, hipGetLastError());
+    return SAME_LDA_OK;
+}
+
 template <bool DEBUG>
 int launch_draw(same_lda* h, const same::DrawArgs& a, bool uniform, bool poisson, hipStream_t st)
 {
     if (a.n <= 0) return SAME_LDA_OK;
     const int T = same::kWave;
-    const int64_t blocks = (a.n + T - 1) / T;
-    if (blocks >= (int64_t)1 << 31) return fail(h, SAME_LDA_EINVAL, "too many draw tasks for one launch");
-    dim3 grid((unsigned)blocks), block((unsigned)T);
+    dim3 block((unsigned)T);
     if (poisson) {
+        const int64_t blocks = (a.n + T - 1) / T;
+        if (blocks >= (int64_t)1 << 31) return fail(h, SAME_LDA_EINVAL, "too many draw tasks for one launch");
+        dim3 grid((unsigned)blocks);
         const size_t lds = same::poisson_lds_bytes();
         if (a.K % same::kBlk == 0) hipLaunchKernelGGL((same::poisson_draw_kernel<true, DEBUG>), grid, block, lds, st, a);
         else                       hipLaunchKernelGGL((same::poisson_draw_kernel<false, DEBUG>), grid, block, lds, st, a);
     } else {
+        // Workgroups take segments of launch positions from a counter until none is left: a few per compute
+        // unit more than fit at once, so that the chip is full from the first moment to the last.
+        const int64_t segments = (a.n + same::kSegment - 1) / same::kSegment;
+        dim3 grid((unsigned)(segments < 256 * 24 ? segments : 256 * 24));
         // blocks of 4 * ceil(K / 128) topics: one or two 16-byte loads per block and matrix up to K = 256
         const size_t lds = same::draw_lds_bytes();
         const bool vec = a.K % 4 == 0;
@@ -429,7 +457,7 @@ unsigned long long* g_stats = nullptr;   // profiling builds only
 same::DrawArgs draw_args(const same_lda* h, const Matrix& M, Copies c, uint32_t pass_word, bool with_words)
 {
     same::DrawArgs a;
-    a.n = M.n_tasks; a.t_doc = M.t_doc; a.t_word = M.t_word; a.t_g = M.t_g; a.order = M.order; a.cost = M.cost; a.ids = nullptr;
+    a.n = M.n_tasks; a.counter = nullptr; a.t_doc = M.t_doc; a.t_word = M.t_word; a.t_g = M.t_g; a.order = M.order; a.cost = M.cost; a.ids = nullptr;
     a.theta = M.theta; a.phi = h->phi; a.ndk = M.ndk; a.nwk = with_words ? h->nwk : nullptr;
     // a pair holds a count below 2^(32 - kPairShift): m * largest group must fit
     // (a Poisson count may exceed its rate: four times the rate plus 128 is beyond any count the walk can return)
@@ -439,6 +467,8 @@ same::DrawArgs draw_args(const same_lda* h, const Matrix& M, Copies c, uint32_t 
     a.t_slot = M.t_slot;
     a.K = h->K; a.m = c.m; a.mf = c.mf; a.seed_lo = (uint32_t)h->seed; a.seed_hi = (uint32_t)(h->seed >> 32);
     a.pass = pass_word;
+    a.V = h->V;
+    a.hot_of = (with_words && M.n_hot > 0) ? M.hot_of : nullptr;
 #ifdef SAME_STATS
     a.stats = g_stats;
 #endif
@@ -446,6 +476,9 @@ same::DrawArgs draw_args(const same_lda* h, const Matrix& M, Copies c, uint32_t 
 }
 
 uint32_t pass_word(int32_t pass_index, uint32_t domain) { return (domain << 28) | ((uint32_t)pass_index & 0x0FFFFFFFu); }
+
+// The word-count matrix is followed by the private copies of the hot words' rows.
+size_t nwk_elements(const same_lda* h) { return ((size_t)h->V + (size_t)same::kHotCopies * same::kHotMax) * h->K; }
 
 int zero_u32(same_lda* h, uint32_t* p, size_t n, hipStream_t st)
 {
@@ -514,12 +547,14 @@ int run_pass(same_lda* h, Matrix& M, Copies c, uint32_t pword, bool uniform, boo
 {
     int rc;
     if ((rc = zero_u32(h, M.ndk, (size_t)M.D * h->K, st))) return rc;
-    if (with_words && (rc = zero_u32(h, h->nwk, (size_t)h->V * h->K, st))) return rc;
-    if (!uniform && M.n_tiles > 0) {
+    if (with_words && (rc = zero_u32(h, h->nwk, nwk_elements(h), st))) return rc;   // the hot words' copies too
+    if (!uniform && c.poisson && M.n_tiles > 0) {               // the Poisson kernel takes its tasks in cost order
         hipLaunchKernelGGL(same::reorder_kernel, dim3((unsigned)M.n_tiles), dim3(256), 0, st, M.tile_start, M.cost,
                            M.order);
         HIP_TRY(h, hipGetLastError());
     }
+    same::DrawArgs a = draw_args(h, M, c, pword, with_words);
+    if (!c.poisson && (rc = prepare_counter(h, a, st))) return rc;
     // the events bracket the draw kernel alone
     std::pair<hipEvent_t, hipEvent_t> ev{nullptr, nullptr};
     if (timed) {
@@ -530,7 +565,6 @@ int run_pass(same_lda* h, Matrix& M, Copies c, uint32_t pword, bool uniform, boo
         }
         HIP_TRY(h, hipEventRecord(ev.first, st));
     }
-    const same::DrawArgs a = draw_args(h, M, c, pword, with_words);
     if ((rc = launch_draw<false>(h, a, uniform, c.poisson, st))) return rc;
     if (timed) {
         HIP_TRY(h, hipEventRecord(ev.second, st));
@@ -542,6 +576,11 @@ int run_pass(same_lda* h, Matrix& M, Copies c, uint32_t pword, bool uniform, boo
         hipLaunchKernelGGL(same::word_reduce_kernel, dim3((unsigned)blocks), dim3(same::kReduceThreads),
                            (size_t)rows * h->K * sizeof(uint32_t), st, a.pairs, M.slot_word, M.n_slots, h->K, rows,
                            h->nwk);
+        HIP_TRY(h, hipGetLastError());
+    }
+    if (a.hot_of) {
+        hipLaunchKernelGGL(same::hot_fold_kernel, dim3((unsigned)((M.n_hot * h->K + 255) / 256)), dim3(256), 0, st, h->nwk,
+                           M.hot_word, M.n_hot, h->V, h->K);
         HIP_TRY(h, hipGetLastError());
     }
     return SAME_LDA_OK;
@@ -593,10 +632,11 @@ int same_lda_init(same_lda_t** out, const same_lda_csc* X, int32_t K, float alph
     int rc = build_matrix(h, X, h->V, K, h->G, h->X, h->stream, true);
     if (!rc) rc = check_m(h, m0, h->X);
     if (!rc) rc = dev_alloc(h, &h->phi, (size_t)h->V * K);
-    if (!rc) rc = dev_alloc(h, &h->nwk, (size_t)h->V * K);
+    if (!rc) rc = dev_alloc(h, &h->nwk, nwk_elements(h));
     if (!rc) rc = dev_alloc(h, &h->nk, (size_t)K);
     if (!rc) rc = dev_alloc(h, &h->gamma_partial, (size_t)((h->V + kGammaRows - 1) / kGammaRows) * K);
     if (!rc) rc = dev_alloc(h, &h->gamma_total, (size_t)K);
+    if (!rc) rc = dev_alloc(h, &h->draw_counter, (size_t)2);
     if (!rc) rc = run_pass(h, h->X, Copies::whole((uint32_t)m0), pass_word(0, 0), true, true, false, h->stream);
     if (!rc) rc = update_theta(h, h->X, (float)m0, h->stream);
     if (!rc) rc = update_phi(h, (float)m0, 1.0f, h->stream);
@@ -737,7 +777,7 @@ void same_lda_free(same_lda_t* h)
     if (h->has_staged) free_matrix(h, h->staged);
     if (h->copy_stream) { hipStreamSynchronize(h->copy_stream); hipStreamDestroy(h->copy_stream); }
     dev_free(h, h->phi); dev_free(h, h->nwk); dev_free(h, h->nk);
-    dev_free(h, h->gamma_partial); dev_free(h, h->gamma_total);
+    dev_free(h, h->gamma_partial); dev_free(h, h->gamma_total); dev_free(h, h->draw_counter);
     h->cache.clear_spare();
     for (auto& e : h->events) { hipEventDestroy(e.first); hipEventDestroy(e.second); }
     for (auto& e : h->pool) { hipEventDestroy(e.first); hipEventDestroy(e.second); }
@@ -808,7 +848,8 @@ int debug_draw(same_lda_t* h, Copies c, const int64_t* task_ids, int32_t n, uint
     if (!rc) {
         same::DrawArgs a = draw_args(h, h->X, c, pass_word(h->pass, 0), false);
         a.n = n; a.ids = ids_d; a.ndk = out_d; a.nwk = nullptr; a.cost = nullptr;
-        rc = launch_draw<true>(h, a, false, c.poisson, h->stream);
+        if (!c.poisson) rc = prepare_counter(h, a, h->stream);
+        if (!rc) rc = launch_draw<true>(h, a, false, c.poisson, h->stream);
     }
     if (!rc) {
         hipError_t e = hipMemcpyAsync(counts_out, out_d, (size_t)n * h->K * 4, hipMemcpyDeviceToHost, h->stream);

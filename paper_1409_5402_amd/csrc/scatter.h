@@ -21,11 +21,12 @@ constexpr int kPoolMin = SAME_POOL_MIN; // waiting multi-piece variables that tr
 
 struct DrawArgs {
     int64_t         n;          // tasks in this launch
+    uint32_t*       counter;    // multinomial form: first launch position not yet taken by a workgroup (zero at launch)
     const int32_t*  t_doc;      // [n_tasks] document of the task
     const int32_t*  t_word;     // [n_tasks] word of the task
     const uint32_t* t_g;        // [n_tasks] tokens in the task's group
-    const int32_t*  order;      // [n_tasks] task id handled at each launch position
-    uint32_t*       cost;       // [n_tasks] out: trips this task was busy for (null: not recorded)
+    const int32_t*  order;      // Poisson form: [n_tasks] task id handled at each launch position
+    uint32_t*       cost;       // Poisson form: [n_tasks] out: trips this task was busy for (null: not recorded)
     const int64_t*  ids;        // debug launches: task ids to draw instead (else null)
     const float*    theta;      // [D][K]   (unused when weights are uniform)
     const float*    phi;        // [V][K]
@@ -37,6 +38,8 @@ struct DrawArgs {
     uint32_t        m;          // copies per token (multinomial form)
     float           mf;         // copies per token (Poisson form: any positive real)
     uint32_t        seed_lo, seed_hi, pass;
+    int32_t         V;          // rows of nwk that are words; the copies of the hot words' rows follow them
+    const int16_t*  hot_of;     // [V] index of a hot word among the hot words, -1 for the others (null: no hot words)
 #ifdef SAME_STATS
     unsigned long long* stats;  // profiling builds only: event counters
 #endif
@@ -48,13 +51,22 @@ struct DrawArgs {
 #define SAME_COUNT(a, i, v) do { } while (0)
 #endif
 
-// Where the counts of one task go.  Every placed count goes to the document's row at once.  The word's
-// row is updated either the same way or, when the launch has a pair list, later by word_reduce_kernel:
-// the task records (topic, count) in its slot of the list (slots are in word order), so that the
-// scattered updates of [V][K] become one streaming pass with all updates of a row close together.
+// Rows of [V][K] that very many tasks update at once (the most frequent words: their tasks spread copies
+// over many topics, fill their pair-list slot and send the rest straight to the row) are a bottleneck of
+// their own: atomics on a handful of lines are served by a handful of memory channels, one after the other.
+// Such a word therefore gets kHotCopies private copies of its row behind the matrix; a workgroup adds to the
+// copy picked by its index, and hot_fold_kernel adds the copies to the word's row afterwards.
+constexpr int kHotMax = 256;            // words that may be hot (those holding at least 1/256 of all tokens)
+constexpr int kHotCopies = 32;          // copies of a hot word's row
+
+// Where the counts of one task go.  Every placed count goes to the document's row at once (an atomic:
+// several waves may hold tasks of one document).  The word's row is updated either the same way or, when
+// the launch has a pair list, later by word_reduce_kernel: the task records (topic, count) in its slot of
+// the list (slots are in word order), so that the scattered updates of [V][K] become one streaming pass
+// with all updates of a row close together.
 struct Scatter {
     uint32_t* __restrict__ out_d;     // the document's row (debug launches: the task's output row)
-    uint32_t* __restrict__ out_w;     // the word's row, or null
+    uint32_t* __restrict__ out_w;     // the word's row (for a hot word: this workgroup's copy of it), or null
     uint32_t* __restrict__ pslot;     // the task's slot in the pair list, or null
     uint32_t npairs;
 
@@ -82,14 +94,35 @@ __device__ __forceinline__ Scatter make_scatter(const DrawArgs& a, int64_t row, 
     Scatter s;
     const int K = a.K;
     s.out_d = DEBUG ? a.ndk + (size_t)row * K : a.ndk + (size_t)d * K;
-    s.out_w = (DEBUG || a.nwk == nullptr) ? nullptr : a.nwk + (size_t)w * K;
+    s.out_w = nullptr;
     s.pslot = nullptr;
-    if (!DEBUG && a.pairs != nullptr && s.out_w != nullptr) {
-        const int32_t slot_id = a.t_slot[tau];
-        if (slot_id >= 0) s.pslot = a.pairs + (size_t)slot_id * kPairWords;
+    if (!DEBUG && a.nwk != nullptr) {
+        const int hot = a.hot_of ? (int)a.hot_of[w] : -1;
+        const size_t wrow = hot < 0 ? (size_t)w : (size_t)a.V + (size_t)(blockIdx.x % kHotCopies) * kHotMax + (size_t)hot;
+        s.out_w = a.nwk + wrow * K;
+        if (a.pairs != nullptr) {
+            const int32_t slot_id = a.t_slot[tau];
+            if (slot_id >= 0) s.pslot = a.pairs + (size_t)slot_id * kPairWords;
+        }
     }
     s.npairs = 0;
     return s;
+}
+
+// Adds the copies of the hot words' rows (rows V .. V + kHotCopies*kHotMax of the matrix) to the words' own
+// rows and clears them.  Runs alone on its stream after the draw and the pair-list reduction.
+__global__ void hot_fold_kernel(uint32_t* __restrict__ nwk, const int32_t* __restrict__ hot_word, int n_hot, int V, int K)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n_hot * K) return;
+    const int hw = i / K, k = i - hw * K;
+    uint32_t total = 0;
+    for (int c = 0; c < kHotCopies; ++c) {
+        uint32_t* p = nwk + ((size_t)V + (size_t)c * kHotMax + (size_t)hw) * K + k;
+        total += *p;
+        *p = 0u;
+    }
+    if (total) nwk[(size_t)hot_word[hw] * K + k] += total;
 }
 
 // Adds the recorded pairs to the word rows.  Slots are in word order and exist only for words with

@@ -24,12 +24,13 @@ struct BuildStats {
     uint32_t max_doc, max_word;
     uint32_t max_group;
     uint32_t n_slots;
+    uint32_t n_hot;                        // words holding at least 1/kHotMax of all tokens
 };
 
 __global__ void wl_init_stats(BuildStats* s)
 {
     s->tokens = 0ull; s->n_tasks = 0ull; s->first_bad = ~0ull; s->max_group = 0u; s->n_slots = 0u;
-    s->max_doc_tokens = 0ull; s->max_word_tokens = 0ull; s->max_doc = ~0u; s->max_word = ~0u;
+    s->max_doc_tokens = 0ull; s->max_word_tokens = 0ull; s->max_doc = ~0u; s->max_word = ~0u; s->n_hot = 0u;
 }
 
 // Token totals per document and per word (the largest values the count matrices can reach are m times
@@ -57,6 +58,22 @@ __global__ void wl_word_max(const unsigned long long* __restrict__ word_tok, int
 {
     const int32_t w = (int32_t)(blockIdx.x * blockDim.x + threadIdx.x);
     if (w < V && word_tok[w]) atomicMax(&s->max_word_tokens, word_tok[w]);
+}
+
+// Hot words: those that hold at least one part in hot_max of all tokens (so at most hot_max of them).  They are
+// numbered in the order the threads arrive; the numbering only names the copies of their rows, no result
+// depends on it.  hot_of[w] = number or -1; hot_word[number] = w.
+__global__ void wl_hot_words(const unsigned long long* __restrict__ word_tok, int32_t V, int32_t hot_max,
+                             int16_t* __restrict__ hot_of, int32_t* __restrict__ hot_word, BuildStats* s)
+{
+    const int32_t w = (int32_t)(blockIdx.x * blockDim.x + threadIdx.x);
+    if (w >= V) return;
+    int16_t idx = -1;
+    if (word_tok[w] > 0ull && word_tok[w] * (unsigned long long)hot_max >= s->tokens) {
+        const uint32_t at = atomicAdd(&s->n_hot, 1u);
+        if (at < (uint32_t)hot_max) { idx = (int16_t)at; hot_word[at] = w; }
+    }
+    hot_of[w] = idx;
 }
 
 // The lowest document and word ids that attain the two maxima (for the error message).
