@@ -164,7 +164,16 @@ int same_lda_task_count(const same_lda_t* h, int64_t* count);
  *   counts_out  host, [n][K] uint32                                                            */
 int same_lda_debug_draw(same_lda_t* h, int32_t m_t, const int64_t* task_ids, int32_t n,
                         uint32_t* counts_out);
-/* The same hook for the NEXT same_lda_sweep_poisson(h, m_t, .).                                  */
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid it): the same hook as same_lda_debug_draw, same arguments and same result, but it
+ * calls no hipMalloc / hipFree: the staged task ids, the count rows and the draw kernel's segment counter live
+ * in a device array that is part of the library (about 4.2 MB on every GPU the library runs on, held until the
+ * process ends).  At most 4096 tasks and 2^20 counts (n * K) per call; more is refused with SAME_LDA_EINVAL.
+ * Every call on a GPU uses that GPU's one array: calls that overlap on one GPU (two handles, two threads)
+ * race; the array keeps the last call's contents and the call clears what it needs.  Synchronises.         */
+int same_lda_debug_draw_noalloc(same_lda_t* h, int32_t m_t, const int64_t* task_ids, int32_t n,
+                                uint32_t* counts_out);
+/* The same hook as same_lda_debug_draw for the NEXT same_lda_sweep_poisson(h, m_t, .).           */
 int same_lda_debug_draw_poisson(same_lda_t* h, float m_t, const int64_t* task_ids, int32_t n,
                                 uint32_t* counts_out);
 

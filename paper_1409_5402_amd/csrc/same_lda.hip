@@ -9,6 +9,7 @@
 #include <cstdio>
 #include <cstring>
 #include <map>
+#include <mutex>
 #include <new>
 #include <string>
 #include <unordered_map>
@@ -830,6 +831,40 @@ int same_lda_task_count(const same_lda_t* h, int64_t* count)
 }
 
 namespace {
+// Device memory of same_lda_debug_draw_noalloc: the segment counter of the draw kernel, the staged task ids and
+// the count rows.  One copy per GPU (a file-scope device array), kept until the process ends.
+constexpr int32_t kNoAllocMaxTasks = 4096;
+constexpr size_t kNoAllocMaxCounts = (size_t)1 << 20;
+struct NoAllocScratch {
+    uint32_t counter[64];
+    int64_t  ids[kNoAllocMaxTasks];
+    uint32_t counts[kNoAllocMaxCounts];
+};
+}  // namespace
+
+static __device__ __align__(256) unsigned char scratch[sizeof(NoAllocScratch)];
+
+namespace {
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices];      // the array's address on each device, once asked for
+std::mutex g_scratch_mutex;
+
+// The address of the current device's copy of `scratch` (its name is a host-side stand-in, not a device address).
+int scratch_of_current_device(same_lda* h, NoAllocScratch** out)
+{
+    int dev = -1;
+    HIP_TRY(h, hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(h, SAME_LDA_EINVAL, "device %d is beyond the %d this library keeps scratch for", dev, kMaxDevices);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        HIP_TRY(h, hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        g_scratch_ptr[dev] = p;
+    }
+    *out = static_cast<NoAllocScratch*>(g_scratch_ptr[dev]);
+    return SAME_LDA_OK;
+}
+
 int debug_draw(same_lda_t* h, Copies c, const int64_t* task_ids, int32_t n, uint32_t* counts_out)
 {
     if (n < 0 || (n > 0 && (!task_ids || !counts_out))) return fail(h, SAME_LDA_EINVAL, "bad debug_draw arguments");
@@ -867,6 +902,33 @@ int same_lda_debug_draw(same_lda_t* h, int32_t m_t, const int64_t* task_ids, int
     if (!h) return SAME_LDA_EINVAL;
     if (m_t < 1) return fail(h, SAME_LDA_EINVAL, "m must be >= 1 (got %d)", m_t);
     return debug_draw(h, Copies::whole((uint32_t)m_t), task_ids, n, counts_out);
+}
+
+int same_lda_debug_draw_noalloc(same_lda_t* h, int32_t m_t, const int64_t* task_ids, int32_t n, uint32_t* counts_out)
+{
+    if (!h) return SAME_LDA_EINVAL;
+    if (m_t < 1) return fail(h, SAME_LDA_EINVAL, "m must be >= 1 (got %d)", m_t);
+    if (n < 0 || (n > 0 && (!task_ids || !counts_out))) return fail(h, SAME_LDA_EINVAL, "bad debug_draw arguments");
+    if (n > kNoAllocMaxTasks || (size_t)n * (size_t)h->K > kNoAllocMaxCounts)
+        return fail(h, SAME_LDA_EINVAL, "debug_draw_noalloc takes at most %d tasks and %zu counts (tasks * K) per call (got %d tasks, K = %d)",
+                    kNoAllocMaxTasks, kNoAllocMaxCounts, n, h->K);
+    int rc = check_m(h, m_t, h->X);
+    if (rc || n == 0) return rc;
+    for (int32_t i = 0; i < n; ++i)
+        if (task_ids[i] < 0 || task_ids[i] >= h->X.n_tasks) return fail(h, SAME_LDA_EINVAL, "task id %lld out of range", (long long)task_ids[i]);
+    NoAllocScratch* S = nullptr;
+    if ((rc = scratch_of_current_device(h, &S))) return rc;
+    const size_t counts = (size_t)n * h->K;
+    HIP_TRY(h, hipMemcpyAsync(S->ids, task_ids, (size_t)n * 8, hipMemcpyHostToDevice, h->stream));
+    if ((rc = zero_u32(h, S->counts, counts, h->stream))) return rc;             // the array keeps the last call's contents
+    same::DrawArgs a = draw_args(h, h->X, Copies::whole((uint32_t)m_t), pass_word(h->pass, 0), false);
+    a.n = n; a.ids = S->ids; a.ndk = S->counts; a.nwk = nullptr; a.cost = nullptr;
+    a.counter = S->counter;
+    if ((rc = zero_u32(h, S->counter, 1, h->stream))) return rc;
+    if ((rc = launch_draw<true>(h, a, false, false, h->stream))) return rc;
+    HIP_TRY(h, hipMemcpyAsync(counts_out, S->counts, counts * 4, hipMemcpyDeviceToHost, h->stream));
+    HIP_TRY(h, hipStreamSynchronize(h->stream));
+    return SAME_LDA_OK;
 }
 
 int same_lda_debug_draw_poisson(same_lda_t* h, float m_t, const int64_t* task_ids, int32_t n, uint32_t* counts_out)
