@@ -41,6 +41,9 @@ constexpr int kSumStride = kMaxBlocks + 1;      // words between the block sums 
 
 __host__ __device__ inline int block_len(int K) { return 4 * ((K + 127) / 128); }
 
+// Rows of document counts a wave keeps in LDS: two up to K = 256, one up to K = 512 (2 KB at most), none beyond.
+__host__ __device__ inline int doc_rows(int K) { return K <= 256 ? 2 : (K <= 512 ? 1 : 0); }
+
 // Position of the highest of R copies uniform on (0, U).
 __device__ __forceinline__ float top_position(float U, uint32_t R, float u)
 {
@@ -85,6 +88,15 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
     const int T = TB > 0 ? 4 * TB : block_len(K);                  // topics per block
     const int nblk = (K + T - 1) / T;                              // blocks in use (<= 32)
     const int half = lane >> 5, hl = lane & 31;
+    // Rows of the new document counts kept in LDS while the wave works on their documents (the launch positions are
+    // in storage order: the 64 lanes hold tasks of one or two documents at a time).  Counts are added here and
+    // reach the matrix in one pass over the row when the wave has left the document; tasks of a document that
+    // has no row here add to the matrix at once.
+    uint32_t* rows = acc + kWave;                                  // [n_rows][K]
+    const int n_rows = DEBUG ? 0 : doc_rows(K);
+    int tag0 = -1, tag1 = -1;                                      // the documents of rows 0 and 1 (wave-uniform), -1: free
+    int myrow = -1;                                                // the row of this lane's document, -1: none
+    for (int i = lane; i < n_rows * K; i += kWave) rows[i] = 0u;
     int32_t next = 0, end = 0;                                     // the wave's segment: positions not yet handed out
     bool drained = false;                                          // the counter has passed the last position
     acc[lane] = 0u;
@@ -117,6 +129,16 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
     bool flip = false, stalled = false;
     int kk = 0;
 
+    // Adds row i of the LDS counts to the matrix row of document doc and clears it (whole wave).
+    auto flush_row = [&](int i, int doc) {
+        __syncthreads();
+        for (int k = lane; k < K; k += kWave) {
+            const uint32_t v = rows[i * K + k];
+            if (v) { atomicAdd(a.ndk + (size_t)doc * K + k, v); rows[i * K + k] = 0u; }
+        }
+        __syncthreads();
+    };
+
     // Idle lanes take the next positions, the wave scans the new tasks' block sums (two tasks at a time, one
     // per half-wave: lane hl of a half owns block hl), each new lane turns its sums into running sums.
     auto refill = [&](uint64_t idle_mask) {
@@ -145,6 +167,23 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
         const int n_idle = (int)__popcll(idle_mask);
         next += n_idle < avail ? n_idle : avail;
         uint64_t fresh = __ballot(take);
+        if (n_rows > 0) {
+            // lanes that keep working keep their row; a new task joins the row of its document if there is one;
+            // documents that are new to the wave get the rows no lane uses any more, lowest document first
+            if (idle) myrow = -1;
+            if (take) myrow = d == tag0 ? 0 : ((n_rows > 1 && d == tag1) ? 1 : -1);
+            for (int round = 0; round < n_rows; ++round) {
+                const uint64_t used0 = __ballot(myrow == 0), used1 = __ballot(myrow == 1);
+                const int free_row = used0 == 0 ? 0 : ((n_rows > 1 && used1 == 0) ? 1 : -1);
+                int dn = (take && myrow < 0) ? d : 0x7FFFFFFF;         // the lowest new document without a row
+                for (int o = 32; o > 0; o >>= 1) dn = min(dn, __shfl_xor(dn, o));
+                if (free_row < 0 || dn == 0x7FFFFFFF) break;
+                const int old = free_row == 0 ? tag0 : tag1;
+                if (old >= 0) flush_row(free_row, old);
+                if (free_row == 0) tag0 = dn; else tag1 = dn;
+                if (take && d == dn) myrow = free_row;
+            }
+        }
         if (UNIFORM) {
             // all weights are 1: block l holds min(T, K - l*T) topics
             if (take) for (int l = 0; l < nblk; ++l) sums[lane * kSumStride + l] = (float)(min(K, (l + 1) * T) - l * T);
@@ -464,7 +503,10 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
             SAME_COUNT(a, 22 + (w < 16 ? 0 : w < 256 ? 1 : w < 4096 ? 2 : 3), 1);
         }
 #endif
-        if (en > 0u) sc.emit(ek, en);
+        if (en > 0u) {
+            if (myrow >= 0) { atomicAdd(rows + myrow * K + ek, en); sc.emit_word(ek, en); }
+            else sc.emit(ek, en);
+        }
     };
 
     for (;;) {
@@ -488,8 +530,10 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
         trip();
     }
     if (open) sc.close(true);
+    if (n_rows > 0 && tag0 >= 0) flush_row(0, tag0);
+    if (n_rows > 1 && tag1 >= 0) flush_row(1, tag1);
 }
 
-inline size_t draw_lds_bytes() { return 4u * (size_t)kWave * (size_t)(kSumStride + 1); }
+inline size_t draw_lds_bytes(int K) { return 4u * ((size_t)kWave * (size_t)(kSumStride + 1) + (size_t)doc_rows(K) * (size_t)K); }
 
 }  // namespace same

@@ -438,7 +438,7 @@ int launch_draw(same_lda* h, const same::DrawArgs& a, bool uniform, bool poisson
         const int64_t segments = (a.n + same::kSegment - 1) / same::kSegment;
         dim3 grid((unsigned)(segments < 256 * 24 ? segments : 256 * 24));
         // blocks of 4 * ceil(K / 128) topics: one or two 16-byte loads per block and matrix up to K = 256
-        const size_t lds = same::draw_lds_bytes();
+        const size_t lds = same::draw_lds_bytes(a.K);
         const bool vec = a.K % 4 == 0;
         const int tb = same::block_len(a.K) / 4;
         if (uniform)             hipLaunchKernelGGL((same::draw_kernel<true, false, DEBUG, 0>), grid, block, lds, st, a);

@@ -73,6 +73,11 @@ struct Scatter {
     __device__ __forceinline__ void emit(int k, uint32_t n)
     {
         atomicAdd(out_d + k, n);
+        emit_word(k, n);
+    }
+    // the word's half alone (the caller has added the count to the document's row itself)
+    __device__ __forceinline__ void emit_word(int k, uint32_t n)
+    {
         if (pslot) {
             if (npairs < (uint32_t)(kPairWords - 1)) pslot[1u + npairs] = (uint32_t)k | (n << kPairShift);
             else atomicAdd(out_w + k, n);                          // slot full: straight to the row
