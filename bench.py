@@ -158,7 +158,9 @@ def stats_bench(args):
     import torch
     from paper_1409_5402_amd import binding, build, synth
 
-    if not os.path.exists(build.STATS_LIB):
+    newest = max(os.path.getmtime(os.path.join(dp, f)) for dp, _, fs in os.walk(os.path.join(ROOT, "paper_1409_5402_amd", "csrc"))
+                 for f in fs)
+    if not os.path.exists(build.STATS_LIB) or os.path.getmtime(build.STATS_LIB) < newest:
         build.build(stats=True)
     L = binding.load(build.STATS_LIB)
     L.same_lda_stats_buffer.argtypes = [ctypes.c_void_p]

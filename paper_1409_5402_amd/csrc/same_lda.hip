@@ -251,14 +251,18 @@ int build_matrix(same_lda* h, const same_lda_csc* X, int32_t V, int32_t K, int32
     hipLaunchKernelGGL(same::wl_scan_nonzeros, dim3(grid_for((size_t)nnz + 1)), dim3(256), 0, st, M.colptr, M.rowidx,
                        M.val, D, nnz, V, (uint32_t)G, M.nz_doc, ntask, d_stats);
     // token totals per document and per word: they bound what the 32-bit count matrices must hold
-    unsigned long long *doc_tok = nullptr, *word_tok = nullptr;
+    unsigned long long *doc_tok = nullptr, *word_tok = nullptr, *stripes = nullptr;
     HIP_TRY(h, tmp.get(&doc_tok, (size_t)D));
     HIP_TRY(h, tmp.get(&word_tok, (size_t)V));
-    hipLaunchKernelGGL(same::zero_u64_kernel, dim3(grid_for((size_t)V)), dim3(256), 0, st, word_tok, (size_t)V);
+    HIP_TRY(h, tmp.get(&stripes, (size_t)V * same::kTokenStripes));
+    hipLaunchKernelGGL(same::zero_u64_kernel, dim3(grid_for((size_t)V * same::kTokenStripes)), dim3(256), 0, st, stripes,
+                       (size_t)V * same::kTokenStripes);
+    if (nnz > 0)
+        hipLaunchKernelGGL(same::wl_word_tokens, dim3(grid_for((size_t)nnz)), dim3(256), 0, st, M.rowidx, M.val, nnz, V, stripes);
+    hipLaunchKernelGGL(same::wl_word_totals, dim3((unsigned)((V + 255) / 256)), dim3(256), 0, st, stripes, V, word_tok, d_stats);
     if (D > 0) {
-        hipLaunchKernelGGL(same::wl_token_totals, dim3((unsigned)((D + 255) / 256)), dim3(256), 0, st, M.colptr, M.rowidx,
-                           M.val, D, V, doc_tok, word_tok, d_stats);
-        hipLaunchKernelGGL(same::wl_word_max, dim3((unsigned)((V + 255) / 256)), dim3(256), 0, st, word_tok, V, d_stats);
+        hipLaunchKernelGGL(same::wl_doc_tokens, dim3((unsigned)((D + 255) / 256)), dim3(256), 0, st, M.colptr, M.rowidx,
+                           M.val, D, V, doc_tok, d_stats);
         const int32_t most = D > V ? D : V;
         hipLaunchKernelGGL(same::wl_token_argmax, dim3((unsigned)((most + 255) / 256)), dim3(256), 0, st, doc_tok, D,
                            word_tok, V, d_stats);

@@ -34,30 +34,67 @@ __global__ void wl_init_stats(BuildStats* s)
 }
 
 // Token totals per document and per word (the largest values the count matrices can reach are m times
-// these).  Only entries that passed validation are counted; word_tok must be zero on entry.
-__global__ void wl_token_totals(const int32_t* __restrict__ colptr, const int32_t* __restrict__ rowidx,
-                                const float* __restrict__ val, int32_t D, int32_t V,
-                                unsigned long long* __restrict__ doc_tok, unsigned long long* __restrict__ word_tok,
-                                BuildStats* s)
+// these).  Only entries that passed validation are counted.  Words: one thread per nonzero adds to one of
+// kTokenStripes copies of the per-word array (the most frequent words would otherwise receive one atomic per
+// document on a single address); wl_word_totals then adds the copies.  Documents: one thread per document.
+constexpr int kTokenStripes = 32;
+
+__global__ __launch_bounds__(256) void wl_word_tokens(const int32_t* __restrict__ rowidx, const float* __restrict__ val,
+                                                      int64_t nnz, int32_t V, unsigned long long* __restrict__ stripes)
 {
-    const int32_t d = (int32_t)(blockIdx.x * blockDim.x + threadIdx.x);
-    if (d >= D) return;
-    unsigned long long tot = 0ull;
-    for (int64_t i = colptr[d]; i < (int64_t)colptr[d + 1]; ++i) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    unsigned long long* mine = stripes + (size_t)(blockIdx.x % kTokenStripes) * V;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < nnz; i += stride) {
         const int32_t w = rowidx[i];
         const float c = val[i];
         if (w < 0 || w >= V || !(c >= 1.0f) || c >= 16777216.0f) continue;
-        tot += (unsigned long long)c;
-        atomicAdd(word_tok + w, (unsigned long long)c);
+        atomicAdd(mine + w, (unsigned long long)c);
     }
-    doc_tok[d] = tot;
-    if (tot) atomicMax(&s->max_doc_tokens, tot);
 }
 
-__global__ void wl_word_max(const unsigned long long* __restrict__ word_tok, int32_t V, BuildStats* s)
+// word_tok[w] = sum of the copies; the largest one goes to the statistics (one atomic per workgroup).
+__global__ __launch_bounds__(256) void wl_word_totals(const unsigned long long* __restrict__ stripes, int32_t V,
+                                                      unsigned long long* __restrict__ word_tok, BuildStats* s)
 {
+    __shared__ unsigned long long sh[256];
     const int32_t w = (int32_t)(blockIdx.x * blockDim.x + threadIdx.x);
-    if (w < V && word_tok[w]) atomicMax(&s->max_word_tokens, word_tok[w]);
+    unsigned long long tot = 0ull;
+    if (w < V) {
+        for (int c = 0; c < kTokenStripes; ++c) tot += stripes[(size_t)c * V + w];
+        word_tok[w] = tot;
+    }
+    sh[threadIdx.x] = tot;
+    __syncthreads();
+    for (int off = 128; off > 0; off >>= 1) {
+        if ((int)threadIdx.x < off) sh[threadIdx.x] = sh[threadIdx.x] > sh[threadIdx.x + off] ? sh[threadIdx.x] : sh[threadIdx.x + off];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0 && sh[0]) atomicMax(&s->max_word_tokens, sh[0]);
+}
+
+__global__ __launch_bounds__(256) void wl_doc_tokens(const int32_t* __restrict__ colptr, const int32_t* __restrict__ rowidx,
+                                                     const float* __restrict__ val, int32_t D, int32_t V,
+                                                     unsigned long long* __restrict__ doc_tok, BuildStats* s)
+{
+    __shared__ unsigned long long sh[256];
+    const int32_t d = (int32_t)(blockIdx.x * blockDim.x + threadIdx.x);
+    unsigned long long tot = 0ull;
+    if (d < D) {
+        for (int64_t i = colptr[d]; i < (int64_t)colptr[d + 1]; ++i) {
+            const int32_t w = rowidx[i];
+            const float c = val[i];
+            if (w < 0 || w >= V || !(c >= 1.0f) || c >= 16777216.0f) continue;
+            tot += (unsigned long long)c;
+        }
+        doc_tok[d] = tot;
+    }
+    sh[threadIdx.x] = tot;
+    __syncthreads();
+    for (int off = 128; off > 0; off >>= 1) {
+        if ((int)threadIdx.x < off) sh[threadIdx.x] = sh[threadIdx.x] > sh[threadIdx.x + off] ? sh[threadIdx.x] : sh[threadIdx.x + off];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0 && sh[0]) atomicMax(&s->max_doc_tokens, sh[0]);
 }
 
 // Hot words: those that hold at least one part in hot_max of all tokens (so at most hot_max of them).  They are
