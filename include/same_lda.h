@@ -177,6 +177,14 @@ int same_lda_debug_draw_noalloc(same_lda_t* h, int32_t m_t, const int64_t* task_
 int same_lda_debug_draw_poisson(same_lda_t* h, float m_t, const int64_t* task_ids, int32_t n,
                                 uint32_t* counts_out);
 
+/* Test hook for the scatter of Algorithm 3's two accumulation lines.  A task records its (topic, count) pairs in a
+ * slot of 15 and continues in 64-byte chunks taken from a pool in device memory that the handle allocates with its
+ * matrix (at most eight chunks per slot and a quarter of the free memory); counts that find the pool used up are
+ * added straight to the word rows.  Results never depend on the pool's size.  This call lowers the number of chunks a
+ * sweep may use (0: none; negative: all that were allocated) so that tests reach the fallback at small sizes.
+ *   chunks_in_use  host, optional out: chunks the sweeps may use after the call                      */
+int same_lda_debug_chunk_limit(same_lda_t* h, int64_t max_chunks, int64_t* chunks_in_use);
+
 /* The normaliser of Algorithm 3 as an operation of its own (Section 5.3, SDDMM: a product of two
  * dense matrices evaluated at the nonzeros of a sparse one): mu[i] = sum_k theta[d][k] * phi[w][k]
  * for every nonzero i = (d, w) of the resident matrix, in its storage order, from the current

@@ -24,7 +24,7 @@ _DTYPES = {THETA: np.float32, PHI: np.float32, NDK: np.uint32, NWK: np.uint32, N
 EXPORTS = ["same_lda_init", "same_lda_sweep", "same_lda_sweep_poisson", "same_lda_sweep_sampled", "same_lda_loglik", "same_lda_free",
            "same_lda_set_batch", "same_lda_stage_batch", "same_lda_commit_batch", "same_lda_debug_draw_poisson", "same_lda_sddmm",
            "same_lda_get", "same_lda_set", "same_lda_get_pass", "same_lda_set_pass", "same_lda_task_count",
-           "same_lda_debug_draw", "same_lda_debug_draw_noalloc", "same_lda_set_timing", "same_lda_get_timing", "same_lda_selftest",
+           "same_lda_debug_draw", "same_lda_debug_draw_noalloc", "same_lda_debug_chunk_limit", "same_lda_set_timing", "same_lda_get_timing", "same_lda_selftest",
            "same_lda_synchronize",
            "same_lda_last_error"]
 
@@ -76,6 +76,7 @@ def load(path: str | None = None) -> ctypes.CDLL:
         L.same_lda_task_count.argtypes = [c_void_p, POINTER(c_int64)]
         L.same_lda_debug_draw.argtypes = [c_void_p, c_int32, c_void_p, c_int32, c_void_p]
         L.same_lda_debug_draw_noalloc.argtypes = [c_void_p, c_int32, c_void_p, c_int32, c_void_p]
+        L.same_lda_debug_chunk_limit.argtypes = [c_void_p, c_int64, POINTER(c_int64)]
         L.same_lda_sddmm.argtypes = [c_void_p, c_void_p, c_int32]
         L.same_lda_set_timing.argtypes = [c_void_p, c_int32]
         L.same_lda_get_timing.argtypes = [c_void_p, POINTER(c_double), POINTER(c_int64)]
@@ -239,6 +240,12 @@ class SameLDA:
         self._check(self._lib.same_lda_debug_draw_noalloc(self._h, int(m), ids.ctypes.data if ids.size else None,
                                                           ids.shape[0], out.ctypes.data if out.size else None))
         return out
+
+    def debug_chunk_limit(self, max_chunks: int = -1) -> int:
+        """Chunks of the pair-list pool the sweeps may use from now on (negative: all); returns the number in use."""
+        n = c_int64(0)
+        self._check(self._lib.same_lda_debug_chunk_limit(self._h, int(max_chunks), ctypes.byref(n)))
+        return int(n.value)
 
     def debug_draw_poisson(self, m, task_ids) -> np.ndarray:
         ids = np.ascontiguousarray(task_ids, np.int64)

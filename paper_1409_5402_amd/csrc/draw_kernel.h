@@ -99,6 +99,8 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
     for (int i = lane; i < n_rows * K; i += kWave) rows[i] = 0u;
     int32_t next = 0, end = 0;                                     // the wave's segment: positions not yet handed out
     bool drained = false;                                          // the counter has passed the last position
+    uint32_t chunk_next = 0, chunk_end = 0;                        // the wave's share of the chunk pool not yet handed out
+    bool pool_dry = a.chunks == nullptr;                           // the pool has no chunk left for this wave
     acc[lane] = 0u;
 
     // ---- the lane's current task
@@ -496,8 +498,29 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
                 SAME_COUNT(a, 5, 1);
             }
         }
+        if (!DEBUG && !pool_dry) {
+            // lanes whose slot (or chunk) is full go on in a new chunk: the wave hands out consecutive chunks of its
+            // share of the pool and takes the next kChunkBatch from the pool's counter when they do not suffice
+            const bool need = en > 0u && sc.full();
+            const uint64_t need_mask = __ballot(need);
+            if (need_mask != 0) {
+                const uint32_t cnt = (uint32_t)__popcll((unsigned long long)need_mask);
+                if (chunk_end - chunk_next < cnt) {
+                    uint32_t first = 0;
+                    if (lane == 0) first = atomicAdd(a.chunk_counter, (uint32_t)kChunkBatch);
+                    first = (uint32_t)__builtin_amdgcn_readfirstlane((int)first);
+                    pool_dry = first >= a.n_chunks;
+                    chunk_next = pool_dry ? 0u : first;
+                    chunk_end = pool_dry ? 0u : (a.n_chunks - first < (uint32_t)kChunkBatch ? a.n_chunks : first + (uint32_t)kChunkBatch);
+                    if (lane == 0) SAME_COUNT(a, 14, 1);               // batches of chunks taken
+                }
+                const uint32_t mine = chunk_next + (uint32_t)__popcll((unsigned long long)(need_mask & ((1ull << lane) - 1ull)));
+                if (need && mine < chunk_end) { sc.extend(a.chunks, mine); SAME_COUNT(a, 15, 1); }
+                chunk_next = chunk_end - chunk_next < cnt ? chunk_end : chunk_next + cnt;
+            }
+        }
 #ifdef SAME_STATS
-        if (en > 0u && sc.pslot && sc.npairs >= (uint32_t)(kPairWords - 1)) {   // a count that finds its slot full
+        if (en > 0u && sc.full()) {                                // a count that goes straight to the word's row
             const uint32_t g = R_task_g;
             SAME_COUNT(a, 16 + min(5, 31 - __clz((int)max(g, 1u))), 1);
             SAME_COUNT(a, 22 + (w < 16 ? 0 : w < 256 ? 1 : w < 4096 ? 2 : 3), 1);

@@ -124,7 +124,11 @@ struct same_lda {
     float* phi = nullptr;          // [V][K]
     uint32_t* nwk = nullptr;       // [V][K]
     unsigned long long* nk = nullptr;  // [K]
-    uint32_t* draw_counter = nullptr;  // [2] segment counters of the draw kernel: launches on the handle's stream, on the copy stream
+    uint32_t* draw_counter = nullptr;  // [3] counters of the draw kernel: segments and chunks taken by a launch on the handle's
+                                       // stream, segments taken by a launch on the copy stream
+    uint32_t* chunks = nullptr;        // pool of chunks that continue full pair-list slots (launches on the handle's stream)
+    uint32_t n_chunks = 0;             // chunks allocated
+    int64_t chunk_limit = -1;          // chunks a launch may use (-1: all of them); lowered by tests of the fallback
     double* gamma_partial = nullptr;   // [ceil(V / kGammaRows)][K] block sums of the sampled phi step
     float* gamma_total = nullptr;      // [K]
     bool timing = false;
@@ -203,6 +207,32 @@ struct Temps {
 // Validates the matrix and builds its work list on the device (worklist_kernels.h).  The matrix may
 // live on the host or on the device; it is copied once.  All work is enqueued on st; the call
 // waits for st twice (to learn the number of tasks and of pair-list slots).
+// The pool of chunks that continue full pair-list slots (scatter.h).  A task places at most K pairs, 15 of them in
+// its slot; eight chunks per slot cover a sweep from a flat posterior (a hundred copies of a token then reach some
+// eighty topics), and a sweep that needs more sends the rest straight to the word rows.  The pool never takes more
+// than a quarter of the free device memory.  A failed allocation leaves the handle without a pool.
+void ensure_chunks(same_lda* h, int64_t n_slots)
+{
+    const int64_t per_slot_most = ((int64_t)h->K - 1) / (same::kPairWords - 1);      // ceil((K - 15) / 15), 0 up to K = 15
+    const int64_t per_slot = per_slot_most < 8 ? per_slot_most : 8;
+    int64_t want = n_slots * per_slot;
+    if (want > 0) want += 64 * (int64_t)same::kChunkBatch;                            // unused ends of the waves' shares
+    if (want > 0x7FFFFFFF) want = 0x7FFFFFFF;
+    if (want <= (int64_t)h->n_chunks) return;
+    want += want / 4;                                                                 // minibatches differ in size
+    if (want > 0x7FFFFFFF) want = 0x7FFFFFFF;
+    if (h->chunks) { (void)hipFree(h->chunks); h->chunks = nullptr; h->n_chunks = 0; }
+    size_t free_b = 0, total_b = 0;
+    if (hipMemGetInfo(&free_b, &total_b) != hipSuccess) { (void)hipGetLastError(); return; }
+    const size_t chunk_bytes = (size_t)same::kPairWords * sizeof(uint32_t);
+    if ((size_t)want > free_b / 4 / chunk_bytes) want = (int64_t)(free_b / 4 / chunk_bytes);
+    if (want <= 0) return;
+    void* p = nullptr;
+    if (hipMalloc(&p, (size_t)want * chunk_bytes) != hipSuccess) { (void)hipGetLastError(); return; }
+    h->chunks = static_cast<uint32_t*>(p);
+    h->n_chunks = (uint32_t)want;
+}
+
 int build_matrix(same_lda* h, const same_lda_csc* X, int32_t V, int32_t K, int32_t G, Matrix& M, hipStream_t st,
                  bool with_pairs)
 {
@@ -349,6 +379,7 @@ int build_matrix(same_lda* h, const same_lda_csc* X, int32_t V, int32_t K, int32
             M.n_slots = (int64_t)stats.n_slots;
             ok = M.n_slots > 0 &&
                  h->cache.get(reinterpret_cast<void**>(&M.pairs), (size_t)M.n_slots * same::kPairWords * sizeof(uint32_t)) == hipSuccess;
+            if (ok) ensure_chunks(h, M.n_slots);
         }
         if (!ok) {
             (void)hipGetLastError();
@@ -413,12 +444,16 @@ int check_m(same_lda* h, int32_t m, const Matrix& M)
     return check_accumulators(h, (double)m, 0.0, M);
 }
 
-// The multinomial kernel's segment counter for a launch on st, set to zero on st (a launch of its own, so
-// that the events around the draw kernel bracket that kernel alone).
+// The multinomial kernel's counters for a launch on st, set to zero on st (a launch of its own, so that the
+// events around the draw kernel bracket that kernel alone).  Launches on the copy stream have no pair list and
+// therefore no use for the chunk pool: they run beside launches on the handle's stream, which own it.
 int prepare_counter(same_lda* h, same::DrawArgs& a, hipStream_t st)
 {
-    a.counter = (st == h->copy_stream && st != h->stream) ? h->draw_counter + 1 : h->draw_counter;
-    hipLaunchKernelGGL(same::zero_u32_kernel, dim3(1), dim3(64), 0, st, a.counter, (size_t)1);
+    const bool beside = st == h->copy_stream && st != h->stream;
+    a.counter = beside ? h->draw_counter + 2 : h->draw_counter;
+    a.chunk_counter = h->draw_counter + 1;
+    if (beside || !a.pairs) { a.chunks = nullptr; a.n_chunks = 0; }
+    hipLaunchKernelGGL(same::zero_u32_kernel, dim3(1), dim3(64), 0, st, a.counter, (size_t)(beside ? 1 : 2));
     HIP_TRY(h, hipGetLastError());
     return SAME_LDA_OK;
 }
@@ -470,6 +505,12 @@ same::DrawArgs draw_args(const same_lda* h, const Matrix& M, Copies c, uint32_t 
     const bool pairs_fit = (c.poisson ? 4.0 * most + 128.0 : most) < (double)(1ull << (32 - same::kPairShift));
     a.pairs = (with_words && M.pairs && pairs_fit) ? M.pairs : nullptr;
     a.t_slot = M.t_slot;
+    // the chunk pool continues full slots in the multinomial kernel
+    const uint32_t usable = h->chunk_limit >= 0 && h->chunk_limit < (int64_t)h->n_chunks ? (uint32_t)h->chunk_limit : h->n_chunks;
+    const bool pool = a.pairs && !c.poisson && h->chunks && usable > 0;
+    a.chunks = pool ? h->chunks : nullptr;
+    a.chunk_counter = nullptr;
+    a.n_chunks = pool ? usable : 0u;
     a.K = h->K; a.m = c.m; a.mf = c.mf; a.seed_lo = (uint32_t)h->seed; a.seed_hi = (uint32_t)(h->seed >> 32);
     a.pass = pass_word;
     a.V = h->V;
@@ -579,8 +620,8 @@ int run_pass(same_lda* h, Matrix& M, Copies c, uint32_t pword, bool uniform, boo
         const int rows = same::reduce_rows(h->K);
         const int64_t blocks = (M.n_slots + same::kReduceChunk - 1) / same::kReduceChunk;
         hipLaunchKernelGGL(same::word_reduce_kernel, dim3((unsigned)blocks), dim3(same::kReduceThreads),
-                           (size_t)rows * h->K * sizeof(uint32_t), st, a.pairs, M.slot_word, M.n_slots, h->K, rows,
-                           h->nwk);
+                           (size_t)rows * h->K * sizeof(uint32_t), st, a.pairs, a.chunks, a.n_chunks, M.slot_word, M.n_slots,
+                           h->K, rows, h->nwk);
         HIP_TRY(h, hipGetLastError());
     }
     if (a.hot_of) {
@@ -641,7 +682,7 @@ int same_lda_init(same_lda_t** out, const same_lda_csc* X, int32_t K, float alph
     if (!rc) rc = dev_alloc(h, &h->nk, (size_t)K);
     if (!rc) rc = dev_alloc(h, &h->gamma_partial, (size_t)((h->V + kGammaRows - 1) / kGammaRows) * K);
     if (!rc) rc = dev_alloc(h, &h->gamma_total, (size_t)K);
-    if (!rc) rc = dev_alloc(h, &h->draw_counter, (size_t)2);
+    if (!rc) rc = dev_alloc(h, &h->draw_counter, (size_t)3);
     if (!rc) rc = run_pass(h, h->X, Copies::whole((uint32_t)m0), pass_word(0, 0), true, true, false, h->stream);
     if (!rc) rc = update_theta(h, h->X, (float)m0, h->stream);
     if (!rc) rc = update_phi(h, (float)m0, 1.0f, h->stream);
@@ -783,6 +824,7 @@ void same_lda_free(same_lda_t* h)
     if (h->copy_stream) { hipStreamSynchronize(h->copy_stream); hipStreamDestroy(h->copy_stream); }
     dev_free(h, h->phi); dev_free(h, h->nwk); dev_free(h, h->nk);
     dev_free(h, h->gamma_partial); dev_free(h, h->gamma_total); dev_free(h, h->draw_counter);
+    if (h->chunks) (void)hipFree(h->chunks);
     h->cache.clear_spare();
     for (auto& e : h->events) { hipEventDestroy(e.first); hipEventDestroy(e.second); }
     for (auto& e : h->pool) { hipEventDestroy(e.first); hipEventDestroy(e.second); }
@@ -932,6 +974,15 @@ int same_lda_debug_draw_noalloc(same_lda_t* h, int32_t m_t, const int64_t* task_
     if ((rc = launch_draw<true>(h, a, false, false, h->stream))) return rc;
     HIP_TRY(h, hipMemcpyAsync(counts_out, S->counts, counts * 4, hipMemcpyDeviceToHost, h->stream));
     HIP_TRY(h, hipStreamSynchronize(h->stream));
+    return SAME_LDA_OK;
+}
+
+int same_lda_debug_chunk_limit(same_lda_t* h, int64_t max_chunks, int64_t* chunks_in_use)
+{
+    if (!h) return SAME_LDA_EINVAL;
+    h->chunk_limit = max_chunks < 0 ? -1 : max_chunks;
+    if (chunks_in_use)
+        *chunks_in_use = h->chunk_limit >= 0 && h->chunk_limit < (int64_t)h->n_chunks ? h->chunk_limit : (int64_t)h->n_chunks;
     return SAME_LDA_OK;
 }
 

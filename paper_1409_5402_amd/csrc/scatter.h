@@ -13,7 +13,9 @@ namespace same {
 #define SAME_POOL_MIN 8
 #endif
 constexpr int kWave = 64;               // lanes per workgroup (one wave)
-constexpr int kPairWords = 16;          // words of a pair-list slot: a count and up to 15 (topic, count) pairs
+constexpr int kPairWords = 16;          // words of a pair-list slot: a header and up to 15 (topic, count) pairs
+constexpr uint32_t kPairLink = 0x80000000u;   // header bit: the slot is full and the chunk named by the other bits goes on
+constexpr int kChunkBatch = 256;        // chunks a wave takes from the pool at a time
 constexpr int kPairShift = 11;          // a pair is topic | count << 11 (topics < 2048, counts < 2^21)
 constexpr int kWalkSteps = SAME_WALK_STEPS;   // pmf steps per trip of a draw machine
 constexpr float kPieceMean = 32.0f;     // a binomial / Poisson variable whose mean exceeds this is cut into pieces
@@ -34,6 +36,9 @@ struct DrawArgs {
     uint32_t*       nwk;        // [V][K] or null
     uint32_t*       pairs;      // [n_slots][kPairWords] pair list in word order, or null (update nwk directly)
     const int32_t*  t_slot;     // [n_tasks] slot of each task in the pair list, -1 for a task without one
+    uint32_t*       chunks;     // [n_chunks][kPairWords] pool of chunks that continue full slots, or null
+    uint32_t*       chunk_counter;  // first chunk of the pool not yet taken by a wave (zero at launch)
+    uint32_t        n_chunks;   // chunks in the pool (below 2^31)
     int32_t         K;
     uint32_t        m;          // copies per token (multinomial form)
     float           mf;         // copies per token (Poisson form: any positive real)
@@ -63,12 +68,15 @@ constexpr int kHotCopies = 32;          // copies of a hot word's row
 // several waves may hold tasks of one document).  The word's row is updated either the same way or, when
 // the launch has a pair list, later by word_reduce_kernel: the task records (topic, count) in its slot of
 // the list (slots are in word order), so that the scattered updates of [V][K] become one streaming pass
-// with all updates of a row close together.
+// with all updates of a row close together.  A slot holds 15 pairs.  A task that places more (most tasks do
+// while the posterior is still flat) continues in chunks of the same shape taken from a pool: the header of
+// a full slot or chunk names the chunk that follows it.  When the pool is used up the remaining counts go
+// straight to the word's row.
 struct Scatter {
     uint32_t* __restrict__ out_d;     // the document's row (debug launches: the task's output row)
     uint32_t* __restrict__ out_w;     // the word's row (for a hot word: this workgroup's copy of it), or null
-    uint32_t* __restrict__ pslot;     // the task's slot in the pair list, or null
-    uint32_t npairs;
+    uint32_t* __restrict__ pslot;     // the slot or chunk the task is filling, or null
+    uint32_t npairs;                  // pairs in it
 
     __device__ __forceinline__ void emit(int k, uint32_t n)
     {
@@ -79,17 +87,24 @@ struct Scatter {
     __device__ __forceinline__ void emit_word(int k, uint32_t n)
     {
         if (pslot) {
-            if (npairs < (uint32_t)(kPairWords - 1)) pslot[1u + npairs] = (uint32_t)k | (n << kPairShift);
-            else atomicAdd(out_w + k, n);                          // slot full: straight to the row
-            npairs += 1;
+            if (npairs < (uint32_t)(kPairWords - 1)) { pslot[1u + npairs] = (uint32_t)k | (n << kPairShift); npairs += 1; }
+            else atomicAdd(out_w + k, n);                          // full and no chunk to go on with: straight to the row
         } else if (out_w) {
             atomicAdd(out_w + k, n);
         }
     }
-    // the slot's first word: how many pairs it holds
+    __device__ __forceinline__ bool full() const { return pslot != nullptr && npairs >= (uint32_t)(kPairWords - 1); }
+    // a full slot goes on in chunk idx of the pool
+    __device__ __forceinline__ void extend(uint32_t* __restrict__ pool, uint32_t idx)
+    {
+        pslot[0] = kPairLink | idx;
+        pslot = pool + (size_t)idx * kPairWords;
+        npairs = 0;
+    }
+    // the header of the last slot or chunk: how many pairs it holds
     __device__ __forceinline__ void close(bool live)
     {
-        if (pslot && live) pslot[0] = npairs < (uint32_t)(kPairWords - 1) ? npairs : (uint32_t)(kPairWords - 1);
+        if (pslot && live) pslot[0] = npairs;
     }
 };
 
@@ -140,6 +155,7 @@ constexpr int kSlotMinTasks = 32;
 constexpr int kReduceThreads = 1024;    // two slots per thread: the kernel waits on its loads, many waves hide that
 
 __global__ __launch_bounds__(kReduceThreads) void word_reduce_kernel(const uint32_t* __restrict__ pairs,
+                                                          const uint32_t* __restrict__ chunks, uint32_t n_chunks,
                                                           const int32_t* __restrict__ slot_word, int64_t n, int K,
                                                           int rows, uint32_t* __restrict__ nwk)
 {
@@ -154,18 +170,24 @@ __global__ __launch_bounds__(kReduceThreads) void word_reduce_kernel(const uint3
         const int32_t w = slot_word[s];
         const bool in_tab = w - w0 < rows;
         uint32_t* dst = in_tab ? tab + (size_t)(w - w0) * K : nwk + (size_t)w * K;
-        const uint32_t cnt = src[0];
-        uint32_t idx = ((threadIdx.x & 255u) * cnt) >> 8;          // start somewhere in [0, cnt)
-        for (uint32_t i = 0; i < cnt; i += 4u) {                   // four loads in flight, then their updates
-            uint32_t p[4];
+        for (;;) {                                                 // the slot, then the chunks that continue it
+            const uint32_t head = src[0];
+            const bool linked = (head & kPairLink) != 0u;
+            const uint32_t cnt = (linked || head > (uint32_t)(kPairWords - 1)) ? (uint32_t)(kPairWords - 1) : head;
+            uint32_t idx = ((threadIdx.x & 255u) * cnt) >> 8;      // start somewhere in [0, cnt)
+            for (uint32_t i = 0; i < cnt; i += 4u) {               // four loads in flight, then their updates
+                uint32_t p[4];
 #pragma unroll
-            for (uint32_t j = 0; j < 4u; ++j) {
-                p[j] = (i + j < cnt) ? src[1u + idx] : 0u;
-                idx = idx + 1u >= cnt ? 0u : idx + 1u;
+                for (uint32_t j = 0; j < 4u; ++j) {
+                    p[j] = (i + j < cnt) ? src[1u + idx] : 0u;
+                    idx = idx + 1u >= cnt ? 0u : idx + 1u;
+                }
+#pragma unroll
+                for (uint32_t j = 0; j < 4u; ++j)
+                    if (i + j < cnt) atomicAdd(dst + (p[j] & ((1u << kPairShift) - 1u)), p[j] >> kPairShift);
             }
-#pragma unroll
-            for (uint32_t j = 0; j < 4u; ++j)
-                if (i + j < cnt) atomicAdd(dst + (p[j] & ((1u << kPairShift) - 1u)), p[j] >> kPairShift);
+            if (!linked || (head & ~kPairLink) >= n_chunks) break;
+            src = chunks + (size_t)(head & ~kPairLink) * kPairWords;
         }
     }
     __syncthreads();

@@ -110,6 +110,32 @@ def test_word_counts_through_the_pair_list():
     g.close()
 
 
+def test_full_slots_continue_in_chunks_or_fall_back():
+    """A flat start with 100 copies per token and 64 topics: most tasks place far more than the 15 pairs of a slot.
+    The pairs beyond go to chunks of the pool (chains of up to four), and to the word rows themselves once the pool is
+    used up.  Whatever the pool's size - all of it, nothing, one batch and a bit, about a third of what the sweep
+    needs - the counts are those of the oracle."""
+    rng = np.random.default_rng(12)
+    counts = rng.integers(1, 31, size=(700, 12)) * (rng.uniform(size=(700, 12)) < 0.9)
+    X = csc_from_dense(counts)
+    K, m = 64, 100
+    o = oracle.OracleLDA(X, K, 0.5, 0.05, seed=22, m0=1, G=4)
+    gs = []
+    for limit in (-1, 0, 300, 30000):
+        g = make_gpu(X, K, 0.5, 0.05, 22, 1, 4, on_device=True)
+        allocated = g.debug_chunk_limit(-1)
+        assert allocated >= g.task_count * 4, "every task of this matrix has a slot and may need four chunks"
+        assert g.debug_chunk_limit(limit) == (allocated if limit < 0 else limit)
+        gs.append((limit, g))
+    for s in range(3):
+        o.sweep(m)
+        for limit, g in gs:
+            g.sweep(m)
+            assert_state_equal(g, o, f"sweep {s + 1}, chunk limit {limit}")
+    for _, g in gs:
+        g.close()
+
+
 def test_annealed_medium_shape():
     """Medium workload shape at reduced document count: K=64, Zipf word skew, m annealed linearly 1..20."""
     p = synth.PRESETS["medium"]
