@@ -92,7 +92,8 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
     // in storage order: the 64 lanes hold tasks of one or two documents at a time).  Counts are added here and
     // reach the matrix in one pass over the row when the wave has left the document; tasks of a document that
     // has no row here add to the matrix at once.
-    uint32_t* rows = acc + kWave;                                  // [n_rows][K]
+    uint32_t* stage = acc + kWave + lane;                          // [4][64] pairs on their way to the pair list
+    uint32_t* rows = acc + 5 * kWave;                              // [n_rows][K]
     const int n_rows = DEBUG ? 0 : doc_rows(K);
     int tag0 = -1, tag1 = -1;                                      // the documents of rows 0 and 1 (wave-uniform), -1: free
     int myrow = -1;                                                // the row of this lane's document, -1: none
@@ -145,7 +146,7 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
     // per half-wave: lane hl of a half owns block hl), each new lane turns its sums into running sums.
     auto refill = [&](uint64_t idle_mask) {
         const bool idle = (idle_mask >> lane) & 1ull;
-        if (idle && open) { sc.close(true); open = false; }
+        if (idle && open) { sc.close(true, stage); open = false; }
         const int rank = (int)__popcll(idle_mask & ((1ull << lane) - 1ull));
         const int avail = end - next;
         const bool take = idle && rank < avail;
@@ -515,7 +516,7 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
                     if (lane == 0) SAME_COUNT(a, 14, 1);               // batches of chunks taken
                 }
                 const uint32_t mine = chunk_next + (uint32_t)__popcll((unsigned long long)(need_mask & ((1ull << lane) - 1ull)));
-                if (need && mine < chunk_end) { sc.extend(a.chunks, mine); SAME_COUNT(a, 15, 1); }
+                if (need && mine < chunk_end) { sc.extend(a.chunks, mine, stage); SAME_COUNT(a, 15, 1); }
                 chunk_next = chunk_end - chunk_next < cnt ? chunk_end : chunk_next + cnt;
             }
         }
@@ -527,8 +528,8 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
         }
 #endif
         if (en > 0u) {
-            if (myrow >= 0) { atomicAdd(rows + myrow * K + ek, en); sc.emit_word(ek, en); }
-            else sc.emit(ek, en);
+            if (myrow >= 0) { atomicAdd(rows + myrow * K + ek, en); sc.emit_word(ek, en, stage); }
+            else sc.emit(ek, en, stage);
         }
     };
 
@@ -552,11 +553,11 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
         if (idle_mask == ~0ull) break;                             // nothing in flight and nothing left to take
         trip();
     }
-    if (open) sc.close(true);
+    if (open) sc.close(true, stage);
     if (n_rows > 0 && tag0 >= 0) flush_row(0, tag0);
     if (n_rows > 1 && tag1 >= 0) flush_row(1, tag1);
 }
 
-inline size_t draw_lds_bytes(int K) { return 4u * ((size_t)kWave * (size_t)(kSumStride + 1) + (size_t)doc_rows(K) * (size_t)K); }
+inline size_t draw_lds_bytes(int K) { return 4u * ((size_t)kWave * (size_t)(kSumStride + 5) + (size_t)doc_rows(K) * (size_t)K); }
 
 }  // namespace same

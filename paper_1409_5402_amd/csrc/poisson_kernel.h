@@ -97,6 +97,7 @@ __global__ __launch_bounds__(kWave) void poisson_draw_kernel(DrawArgs a)
     constexpr int qw = 3;                                          // words per queue entry
     uint32_t* que = lds;                                           // [kQCap][qw][64], a ring per lane
     uint32_t* acc = lds + (size_t)(qw * kQCap) * kWave;            // [64] piece totals by owner lane
+    uint32_t* stage = acc + kWave + threadIdx.x;                   // [4][64] pairs on their way to the pair list
     static_assert(kQCap <= 16, "two bits per ring slot in one register");
     uint32_t khi = 0;       // bits 9 and 10 of the topic queued in each ring slot (the entry holds the low nine)
 
@@ -196,7 +197,7 @@ __global__ __launch_bounds__(kWave) void poisson_draw_kernel(DrawArgs a)
         if (st == 3) {
             const uint32_t nk = acc[lane];
             acc[lane] = 0u;
-            if (nk > 0) { sc.emit(kk, nk); SAME_COUNT(a, 5, 1); }
+            if (nk > 0) { sc.emit(kk, nk, stage); SAME_COUNT(a, 5, 1); }
             st = 0;
         }
         __syncthreads();
@@ -253,7 +254,7 @@ __global__ __launch_bounds__(kWave) void poisson_draw_kernel(DrawArgs a)
                 stalled = stalled || (go && still);
             }
             if (walking && (stalled || !(u > cdf))) {              // the piece is finished
-                if (xw > 0) { sc.emit(kk, xw); SAME_COUNT(a, 5, 1); }
+                if (xw > 0) { sc.emit(kk, xw, stage); SAME_COUNT(a, 5, 1); }
                 st = 0;
             }
         }
@@ -297,12 +298,12 @@ __global__ __launch_bounds__(kWave) void poisson_draw_kernel(DrawArgs a)
         }
     }
     while (__any(st != 0 || cnt > 0)) trip();
-    sc.close(live);
+    sc.close(live, stage);
     // The ordering key for the next pass: a running mean (weight 1/4 on this pass) predicts a task's next
     // cost a little better than this pass's cost alone.
     if (!DEBUG && live && a.cost) a.cost[tau] = (3u * a.cost[tau] + busy + 2u) >> 2;
 }
 
-inline size_t poisson_lds_bytes() { return 4u * (size_t)kWave * (size_t)(3 * kQCap + 1); }
+inline size_t poisson_lds_bytes() { return 4u * (size_t)kWave * (size_t)(3 * kQCap + 5); }
 
 }  // namespace same

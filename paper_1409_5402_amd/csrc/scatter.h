@@ -13,7 +13,7 @@ namespace same {
 #define SAME_POOL_MIN 8
 #endif
 constexpr int kWave = 64;               // lanes per workgroup (one wave)
-constexpr int kPairWords = 16;          // words of a pair-list slot: a header and up to 15 (topic, count) pairs
+constexpr int kPairWords = 16;          // words of a pair-list slot: up to 15 (topic, count) pairs and a header
 constexpr uint32_t kPairLink = 0x80000000u;   // header bit: the slot is full and the chunk named by the other bits goes on
 constexpr int kChunkBatch = 256;        // chunks a wave takes from the pool at a time
 constexpr int kPairShift = 11;          // a pair is topic | count << 11 (topics < 2048, counts < 2^21)
@@ -68,43 +68,68 @@ constexpr int kHotCopies = 32;          // copies of a hot word's row
 // several waves may hold tasks of one document).  The word's row is updated either the same way or, when
 // the launch has a pair list, later by word_reduce_kernel: the task records (topic, count) in its slot of
 // the list (slots are in word order), so that the scattered updates of [V][K] become one streaming pass
-// with all updates of a row close together.  A slot holds 15 pairs.  A task that places more (most tasks do
-// while the posterior is still flat) continues in chunks of the same shape taken from a pool: the header of
-// a full slot or chunk names the chunk that follows it.  When the pool is used up the remaining counts go
-// straight to the word's row.
+// with all updates of a row close together.  A slot is 16 words: 15 pairs and, last, a header.  A task that
+// places more than 15 pairs (most tasks do while the posterior is still flat) continues in chunks of the same
+// shape taken from a pool: the header of a full slot or chunk names the chunk that follows it, the header of
+// the last one holds its number of pairs.  When the pool is used up the remaining counts go straight to the
+// word's row.  Pairs are collected four at a time in LDS (stage: this lane's four words, kWave words apart)
+// and written with one 16-byte store: the memory system handles a 16-byte write as fast as a 4-byte one.
 struct Scatter {
     uint32_t* __restrict__ out_d;     // the document's row (debug launches: the task's output row)
     uint32_t* __restrict__ out_w;     // the word's row (for a hot word: this workgroup's copy of it), or null
     uint32_t* __restrict__ pslot;     // the slot or chunk the task is filling, or null
     uint32_t npairs;                  // pairs in it
 
-    __device__ __forceinline__ void emit(int k, uint32_t n)
+    // words 4q .. 4q+3 of the slot from the staged four
+    __device__ __forceinline__ void store_quad(uint32_t q, const uint32_t* stage)
+    {
+        uint4 v;
+        v.x = stage[0]; v.y = stage[kWave]; v.z = stage[2 * kWave]; v.w = stage[3 * kWave];
+        *reinterpret_cast<uint4*>(pslot + 4u * q) = v;
+    }
+    __device__ __forceinline__ void emit(int k, uint32_t n, uint32_t* stage)
     {
         atomicAdd(out_d + k, n);
-        emit_word(k, n);
+        emit_word(k, n, stage);
     }
     // the word's half alone (the caller has added the count to the document's row itself)
-    __device__ __forceinline__ void emit_word(int k, uint32_t n)
+    __device__ __forceinline__ void emit_word(int k, uint32_t n, uint32_t* stage)
     {
         if (pslot) {
-            if (npairs < (uint32_t)(kPairWords - 1)) { pslot[1u + npairs] = (uint32_t)k | (n << kPairShift); npairs += 1; }
-            else atomicAdd(out_w + k, n);                          // full and no chunk to go on with: straight to the row
+            if (npairs < (uint32_t)(kPairWords - 1)) {
+                const uint32_t j = npairs & 3u;
+                stage[j * kWave] = (uint32_t)k | (n << kPairShift);
+                if (j == 3u) store_quad(npairs >> 2, stage);       // pairs 0-3, 4-7 or 8-11
+                npairs += 1;
+            } else {
+                atomicAdd(out_w + k, n);                           // full and no chunk to go on with: straight to the row
+            }
         } else if (out_w) {
             atomicAdd(out_w + k, n);
         }
     }
     __device__ __forceinline__ bool full() const { return pslot != nullptr && npairs >= (uint32_t)(kPairWords - 1); }
-    // a full slot goes on in chunk idx of the pool
-    __device__ __forceinline__ void extend(uint32_t* __restrict__ pool, uint32_t idx)
+    // a full slot (pairs 12-14 are still staged) goes on in chunk idx of the pool
+    __device__ __forceinline__ void extend(uint32_t* __restrict__ pool, uint32_t idx, uint32_t* stage)
     {
-        pslot[0] = kPairLink | idx;
+        stage[3 * kWave] = kPairLink | idx;
+        store_quad(3u, stage);
         pslot = pool + (size_t)idx * kPairWords;
         npairs = 0;
     }
-    // the header of the last slot or chunk: how many pairs it holds
-    __device__ __forceinline__ void close(bool live)
+    // the staged pairs and the header of the last slot or chunk: how many pairs it holds
+    __device__ __forceinline__ void close(bool live, uint32_t* stage)
     {
-        if (pslot && live) pslot[0] = npairs;
+        if (pslot && live) {
+            const uint32_t q = npairs >> 2;
+            if (q == 3u) {                                         // the header shares the last quad
+                stage[3 * kWave] = npairs;
+                store_quad(3u, stage);
+            } else {
+                if ((npairs & 3u) != 0u) store_quad(q, stage);     // words past the last pair are never read
+                pslot[kPairWords - 1] = npairs;
+            }
+        }
     }
 };
 
@@ -148,8 +173,9 @@ __global__ void hot_fold_kernel(uint32_t* __restrict__ nwk, const int32_t* __res
 // Adds the recorded pairs to the word rows.  Slots are in word order and exist only for words with
 // at least kSlotMinTasks tasks: a workgroup takes kReduceChunk consecutive slots, sums the pairs of
 // the first `rows` words it meets in an LDS table and sends the rest straight to [V][K]; the table is
-// then added to the rows it stands for.  Threads start at different pairs of their slots: tasks of
-// one word have their large counts at the same topics, and aligned walks would meet at one address.
+// then added to the rows it stands for.  A thread reads a slot with four 16-byte loads and starts with the
+// quad picked by its index: tasks of one word have their large counts at the same topics in the same places
+// of their slots, and aligned walks would meet at one address.
 constexpr int kReduceChunk = 2048;
 constexpr int kSlotMinTasks = 32;
 constexpr int kReduceThreads = 1024;    // two slots per thread: the kernel waits on its loads, many waves hide that
@@ -170,31 +196,41 @@ __global__ __launch_bounds__(kReduceThreads) void word_reduce_kernel(const uint3
         const int32_t w = slot_word[s];
         const bool in_tab = w - w0 < rows;
         uint32_t* dst = in_tab ? tab + (size_t)(w - w0) * K : nwk + (size_t)w * K;
+        const uint32_t t = threadIdx.x & 3u;                       // which quad of the slot this thread starts with
         for (;;) {                                                 // the slot, then the chunks that continue it
-            const uint32_t head = src[0];
+            const uint4* __restrict__ s4 = reinterpret_cast<const uint4*>(src);
+            uint4 q[4];                                            // the whole slot: four 16-byte loads in flight
+#pragma unroll
+            for (uint32_t i = 0; i < 4u; ++i) q[i] = s4[(t + i) & 3u];
+            const uint32_t head = t == 0u ? q[3].w : (t == 1u ? q[2].w : (t == 2u ? q[1].w : q[0].w));
             const bool linked = (head & kPairLink) != 0u;
             const uint32_t cnt = (linked || head > (uint32_t)(kPairWords - 1)) ? (uint32_t)(kPairWords - 1) : head;
-            uint32_t idx = ((threadIdx.x & 255u) * cnt) >> 8;      // start somewhere in [0, cnt)
-            for (uint32_t i = 0; i < cnt; i += 4u) {               // four loads in flight, then their updates
-                uint32_t p[4];
 #pragma unroll
-                for (uint32_t j = 0; j < 4u; ++j) {
-                    p[j] = (i + j < cnt) ? src[1u + idx] : 0u;
-                    idx = idx + 1u >= cnt ? 0u : idx + 1u;
-                }
+            for (uint32_t i = 0; i < 4u; ++i) {
+                const uint32_t first = 4u * ((t + i) & 3u);        // index of the quad's first pair
+                const uint32_t p[4] = {q[i].x, q[i].y, q[i].z, q[i].w};
 #pragma unroll
                 for (uint32_t j = 0; j < 4u; ++j)
-                    if (i + j < cnt) atomicAdd(dst + (p[j] & ((1u << kPairShift) - 1u)), p[j] >> kPairShift);
+                    if (first + j < cnt) atomicAdd(dst + (p[j] & ((1u << kPairShift) - 1u)), p[j] >> kPairShift);
             }
             if (!linked || (head & ~kPairLink) >= n_chunks) break;
             src = chunks + (size_t)(head & ~kPairLink) * kPairWords;
         }
     }
     __syncthreads();
+    // A word whose slots all lie in this workgroup's range is updated by no other workgroup of this launch (and
+    // nothing else runs beside the launch): its row takes plain additions.  Only the first and the last word of
+    // the range may share their rows with the neighbours.
+    const int32_t w1 = slot_word[s1 - 1];                          // the last word of the range
+    const bool first_shared = s0 > 0 && slot_word[s0 - 1] == w0;
+    const bool last_shared = s1 < n && slot_word[s1] == w1;
     uint32_t* base = nwk + (size_t)w0 * K;                         // row w0 + r, topic k is at base[r*K + k]
     for (int i = threadIdx.x; i < rows * K; i += blockDim.x) {
         const uint32_t v = tab[i];
-        if (v != 0u) atomicAdd(base + i, v);                       // only rows of real words hold counts
+        if (v == 0u) continue;                                     // only rows of real words hold counts
+        const int32_t w = w0 + i / K;
+        if ((w == w0 && first_shared) || (w == w1 && last_shared)) atomicAdd(base + i, v);
+        else base[i] += v;
     }
 }
 
