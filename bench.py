@@ -195,7 +195,8 @@ def stats_bench(args):
                                    "waiting_for_a_shared_pass": round(v[10] / max(v[2], 1), 2),
                                    "idle": round(v[11] / max(v[2], 1), 2)},
                 "pmf_rounds_per_trip": round(v[12] / max(v[2], 1), 3), "refills_per_64_tasks": round(v[13] / nw, 3),
-                "counts_past_a_full_slot_per_task": round(sum(v[16:22]) / nt, 4),
+                "chunks_per_task": round(v[15] / nt, 4), "chunk_batches_per_64_tasks": round(v[14] / nw, 4),
+                "counts_sent_straight_to_a_word_row_with_a_full_slot_per_task": round(sum(v[16:22]) / nt, 4),
                 "of_them_by_group_size_1_2_4_8_16_32up": [int(x) for x in v[16:22]],
                 "of_them_by_word_id_below_16_256_4096_rest": [int(x) for x in v[22:26]]}
 

@@ -65,8 +65,10 @@ __device__ __forceinline__ float top_position(float U, uint32_t R, float u)
 constexpr int kRefillMin = SAME_REFILL_MIN;     // idle lanes that make the wave fetch new tasks
 constexpr int kWalkRounds = SAME_WALK_ROUNDS;   // rounds of kWalkSteps pmf terms per trip, while some lane needs them
 
-// TB: float4 loads per block and matrix when known at compile time (1 for K <= 128, 2 for K <= 256),
-// 0: taken from K at run time.  VEC: K is a multiple of 4 (16-byte loads), else element-wise loads.
+// VEC: K is a multiple of 4 (16-byte loads), else element-wise loads (TB = 0).  TB: 16-byte loads per matrix that
+// a lane has in flight at a time: a block of T = 4 ceil(K / 128) topics is read in T / (4 TB) batches of TB loads
+// per matrix, TB the largest of 1, 2, 4 that divides T / 4 (one batch of one up to K = 128, one of two up to 256,
+// one of four from 385 to 512, two of four from 897 to 1024).  ONE: a block is a single batch.
 //
 // The launch positions are handed out in segments of kSegment consecutive positions through a counter in
 // device memory (a.counter, zero at launch): a workgroup (one wave) takes a segment, its lanes take the
@@ -77,7 +79,7 @@ constexpr int kWalkRounds = SAME_WALK_ROUNDS;   // rounds of kWalkSteps pmf term
 // lane the next position, scans the new tasks (two per instruction) and goes on.
 constexpr int kSegment = 256;
 
-template <bool UNIFORM, bool VEC, bool DEBUG, int TB>
+template <bool UNIFORM, bool VEC, bool DEBUG, int TB, bool ONE>
 __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
 {
     extern __shared__ uint32_t lds[];
@@ -85,7 +87,8 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
     uint32_t* acc = lds + (size_t)kWave * kSumStride;              // [64] piece totals by owner lane
     const int lane = threadIdx.x;
     const int K = a.K;
-    const int T = TB > 0 ? 4 * TB : block_len(K);                  // topics per block
+    const int T = (TB > 0 && ONE) ? 4 * TB : block_len(K);         // topics per block
+    const int nb = (TB > 0 && !ONE) ? T / (4 * TB) : 1;            // batches of loads per block
     const int nblk = (K + T - 1) / T;                              // blocks in use (<= 32)
     const int half = lane >> 5, hl = lane & 31;
     // Rows of the new document counts kept in LDS while the wave works on their documents (the launch positions are
@@ -201,15 +204,16 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
                 return half ? lb : la;
             };
             if (VEC && TB > 0) {
-                // the loads of a task pair are issued before the previous pair is summed
+                // the loads of a batch are issued before the previous batch is summed
                 float4 pv[TB > 0 ? TB : 1], tv[TB > 0 ? TB : 1];
-                auto issue = [&](int src) {
+                auto issue = [&](int src, int b) {
                     const int32_t pd = __shfl(d, src), pw = __shfl(w, src);
-                    const float* __restrict__ tp = a.theta + (size_t)pd * K + k0;
-                    const float* __restrict__ pp = a.phi + (size_t)pw * K + k0;
+                    const int kb = k0 + 4 * TB * b;
+                    const float* __restrict__ tp = a.theta + (size_t)pd * K + kb;
+                    const float* __restrict__ pp = a.phi + (size_t)pw * K + kb;
 #pragma unroll
                     for (int c = 0; c < TB; ++c) {
-                        if (k0 + 4 * c < K) {
+                        if (kb + 4 * c < K) {
                             pv[c] = *reinterpret_cast<const float4*>(pp + 4 * c);
                             tv[c] = *reinterpret_cast<const float4*>(tp + 4 * c);
                         } else {
@@ -218,17 +222,24 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
                         }
                     }
                 };
-                int src = 0;
+                int src = 0, b = 0;
                 bool more = fresh != 0;
-                if (more) { src = pick(fresh); issue(src); }
+                if (more) { src = pick(fresh); issue(src, 0); }
+                float rs = 0.0f;
                 while (more) {
                     const int cur = src;
+                    const bool last = b == nb - 1;
                     float4 cp[TB > 0 ? TB : 1], ct[TB > 0 ? TB : 1];
 #pragma unroll
                     for (int c = 0; c < TB; ++c) { cp[c] = pv[c]; ct[c] = tv[c]; }
-                    more = fresh != 0;
-                    if (more) { src = pick(fresh); issue(src); }
-                    float rs = 0.0f;
+                    if (last) {
+                        b = 0;
+                        more = fresh != 0;
+                        if (more) src = pick(fresh);
+                    } else {
+                        b += 1;
+                    }
+                    if (more) issue(src, b);
 #pragma unroll
                     for (int c = 0; c < TB; ++c) {
                         rs = rs + ct[c].x * cp[c].x;
@@ -236,7 +247,7 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
                         rs = rs + ct[c].z * cp[c].z;
                         rs = rs + ct[c].w * cp[c].w;
                     }
-                    sums[cur * kSumStride + hl] = rs;
+                    if (last) { sums[cur * kSumStride + hl] = rs; rs = 0.0f; }
                 }
             } else {
                 while (fresh) {
@@ -388,19 +399,22 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
                 if (UNIFORM) {
                     for (int j = 0; j < T; ++j) visit(k0 + j < K ? 1.0f : 0.0f);
                 } else if (VEC && TB > 0) {
-                    float4 pv[TB > 0 ? TB : 1], tv[TB > 0 ? TB : 1];
+                    for (int b = 0; b < nb; ++b) {
+                        const int kb = k0 + 4 * TB * b;
+                        float4 pv[TB > 0 ? TB : 1], tv[TB > 0 ? TB : 1];
 #pragma unroll
-                    for (int c = 0; c < TB; ++c) {
-                        const bool in = k0 + 4 * c < K;
-                        pv[c] = in ? *reinterpret_cast<const float4*>(ph + k0 + 4 * c) : make_float4(0.f, 0.f, 0.f, 0.f);
-                        tv[c] = in ? *reinterpret_cast<const float4*>(th + k0 + 4 * c) : make_float4(0.f, 0.f, 0.f, 0.f);
-                    }
+                        for (int c = 0; c < TB; ++c) {
+                            const bool in = kb + 4 * c < K;
+                            pv[c] = in ? *reinterpret_cast<const float4*>(ph + kb + 4 * c) : make_float4(0.f, 0.f, 0.f, 0.f);
+                            tv[c] = in ? *reinterpret_cast<const float4*>(th + kb + 4 * c) : make_float4(0.f, 0.f, 0.f, 0.f);
+                        }
 #pragma unroll
-                    for (int c = 0; c < TB; ++c) {
-                        visit(tv[c].x * pv[c].x);
-                        visit(tv[c].y * pv[c].y);
-                        visit(tv[c].z * pv[c].z);
-                        visit(tv[c].w * pv[c].w);
+                        for (int c = 0; c < TB; ++c) {
+                            visit(tv[c].x * pv[c].x);
+                            visit(tv[c].y * pv[c].y);
+                            visit(tv[c].z * pv[c].z);
+                            visit(tv[c].w * pv[c].w);
+                        }
                     }
                 } else if (VEC) {
                     for (int c = 0; c < T / 4; ++c) {

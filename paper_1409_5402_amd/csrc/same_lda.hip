@@ -476,15 +476,20 @@ int launch_draw(same_lda* h, const same::DrawArgs& a, bool uniform, bool poisson
         // unit more than fit at once, so that the chip is full from the first moment to the last.
         const int64_t segments = (a.n + same::kSegment - 1) / same::kSegment;
         dim3 grid((unsigned)(segments < 256 * 24 ? segments : 256 * 24));
-        // blocks of 4 * ceil(K / 128) topics: one or two 16-byte loads per block and matrix up to K = 256
+        // blocks of 4 * ceil(K / 128) topics, read in batches of one, two or four 16-byte loads per matrix
         const size_t lds = same::draw_lds_bytes(a.K);
         const bool vec = a.K % 4 == 0;
-        const int tb = same::block_len(a.K) / 4;
-        if (uniform)             hipLaunchKernelGGL((same::draw_kernel<true, false, DEBUG, 0>), grid, block, lds, st, a);
-        else if (!vec)           hipLaunchKernelGGL((same::draw_kernel<false, false, DEBUG, 0>), grid, block, lds, st, a);
-        else if (tb == 1)        hipLaunchKernelGGL((same::draw_kernel<false, true, DEBUG, 1>), grid, block, lds, st, a);
-        else if (tb == 2)        hipLaunchKernelGGL((same::draw_kernel<false, true, DEBUG, 2>), grid, block, lds, st, a);
-        else                     hipLaunchKernelGGL((same::draw_kernel<false, true, DEBUG, 0>), grid, block, lds, st, a);
+        const int quads = same::block_len(a.K) / 4;                // 16-byte loads per block and matrix
+        const int tb = quads % 4 == 0 ? 4 : (quads % 2 == 0 ? 2 : 1);
+        const bool one = quads == tb;
+        if (uniform)             hipLaunchKernelGGL((same::draw_kernel<true, false, DEBUG, 0, true>), grid, block, lds, st, a);
+        else if (!vec)           hipLaunchKernelGGL((same::draw_kernel<false, false, DEBUG, 0, true>), grid, block, lds, st, a);
+        else if (tb == 1 && one) hipLaunchKernelGGL((same::draw_kernel<false, true, DEBUG, 1, true>), grid, block, lds, st, a);
+        else if (tb == 2 && one) hipLaunchKernelGGL((same::draw_kernel<false, true, DEBUG, 2, true>), grid, block, lds, st, a);
+        else if (tb == 4 && one) hipLaunchKernelGGL((same::draw_kernel<false, true, DEBUG, 4, true>), grid, block, lds, st, a);
+        else if (tb == 1)        hipLaunchKernelGGL((same::draw_kernel<false, true, DEBUG, 1, false>), grid, block, lds, st, a);
+        else if (tb == 2)        hipLaunchKernelGGL((same::draw_kernel<false, true, DEBUG, 2, false>), grid, block, lds, st, a);
+        else                     hipLaunchKernelGGL((same::draw_kernel<false, true, DEBUG, 4, false>), grid, block, lds, st, a);
     }
     HIP_TRY(h, hipGetLastError());
     return SAME_LDA_OK;

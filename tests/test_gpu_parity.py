@@ -64,9 +64,11 @@ def test_tiny_config_ten_sweeps_bit_exact():
     g.close()
 
 
-@pytest.mark.parametrize("K", [1, 2, 3, 5, 16, 17, 40, 64, 100, 256])
+@pytest.mark.parametrize("K", [1, 2, 3, 5, 16, 17, 40, 64, 100, 256, 300, 512, 516, 640, 768, 1000])
 def test_topic_counts_incl_ragged_K(K):
-    """K not a multiple of 4 or 16, K=1, several checkpoint blocks; ragged last thread block; empty docs."""
+    """K not a multiple of 4 or 16, K=1; blocks of topics read in one batch of loads (up to 256, 512) and in
+    three, five, three and two batches of one, one, two and four loads (300, 516 and 640, 768, 1000); a last block
+    that is partly or wholly past K; ragged last thread block; empty docs."""
     X = toy(seed=K, D=37, V=53, density=0.35, cmax=12)
     m = 7
     o = oracle.OracleLDA(X, K, 0.2, 0.01, seed=99, m0=m, G=4)
