@@ -41,8 +41,10 @@ constexpr int kSumStride = kMaxBlocks + 1;      // words between the block sums 
 
 __host__ __device__ inline int block_len(int K) { return 4 * ((K + 127) / 128); }
 
-// Rows of document counts a wave keeps in LDS: two up to K = 256, one up to K = 512 (2 KB at most), none beyond.
-__host__ __device__ inline int doc_rows(int K) { return K <= 256 ? 2 : (K <= 512 ? 1 : 0); }
+// Rows of document counts a wave keeps in LDS: two up to K = 128, one up to K = 1024 (4 KB at most), none beyond.
+// A second row at K = 256 would serve the waves that straddle two documents, but its kilobyte costs two of the
+// fifteen waves a compute unit holds, which costs more.
+__host__ __device__ inline int doc_rows(int K) { return K <= 128 ? 2 : (K <= 1024 ? 1 : 0); }
 
 // Position of the highest of R copies uniform on (0, U).
 __device__ __forceinline__ float top_position(float U, uint32_t R, float u)
@@ -60,7 +62,7 @@ __device__ __forceinline__ float top_position(float U, uint32_t R, float u)
 #define SAME_REFILL_MIN 24
 #endif
 #ifndef SAME_WALK_ROUNDS
-#define SAME_WALK_ROUNDS 4
+#define SAME_WALK_ROUNDS 1
 #endif
 constexpr int kRefillMin = SAME_REFILL_MIN;     // idle lanes that make the wave fetch new tasks
 constexpr int kWalkRounds = SAME_WALK_ROUNDS;   // rounds of kWalkSteps pmf terms per trip, while some lane needs them
