@@ -113,6 +113,19 @@ MUTS = [
 ]
 
 
+VB_FILE = "vb_estep.py"
+VB_MUTS = [
+ ("vb: beta normalised over the topics of a word", "digamma(l.sum(axis=0, keepdims=True))", "digamma(l.sum(axis=1, keepdims=True))"),
+ ("vb: theta normalised over documents", "digamma(g.sum(axis=1, keepdims=True))", "digamma(g.sum(axis=0, keepdims=True))"),
+ ("vb: counts multiplied by the normaliser", "((c / mu) @ B)", "((c * mu) @ B)"),
+ ("vb: prior dropped", "g = alpha + a * ((c / mu) @ B) if hi > lo", "g = a * ((c / mu) @ B) if hi > lo"),
+ ("vb: expectation of theta instead of exp E log", "a = np.exp(digamma(g) - digamma(g.sum()))", "a = g / g.sum()"),
+ ("vb: counts ignored", "c = X.val[lo:hi].astype(np.float64)", "c = np.ones(hi - lo)"),
+ ("vb: rows of beta of the wrong words", "B = b[words]", "B = b[(words + 1) % b.shape[0]]"),
+]
+PINS_OF = {VB_FILE: "tests/test_oracle_pins_vb.py"}
+
+
 def run_mutant(fname: str, src: str, work: str, old: str, new: str):
     """Builds a tree with the mutated oracle under work/ and runs the pins there; returns (caught, first failure)."""
     shutil.rmtree(work, ignore_errors=True)
@@ -123,9 +136,10 @@ def run_mutant(fname: str, src: str, work: str, old: str, new: str):
     os.symlink(os.path.join(ROOT, "paper_1409_5402_amd"), os.path.join(work, "paper_1409_5402_amd"))
     with open(os.path.join(work, "oracle", fname), "w") as f:
         f.write(src.replace(old, new, 1))
-    r = subprocess.run([sys.executable, "-m", "pytest", "tests/test_oracle_pins.py", "-x", "-q", "-p", "no:cacheprovider"],
+    pins = PINS_OF.get(fname, "tests/test_oracle_pins.py")
+    r = subprocess.run([sys.executable, "-m", "pytest", pins, "-x", "-q", "-p", "no:cacheprovider"],
                        cwd=work, capture_output=True, text=True)
-    m = re.search(r"FAILED tests/test_oracle_pins.py::(\S+)", r.stdout)
+    m = re.search(r"FAILED " + re.escape(pins) + r"::(\S+)", r.stdout)
     return r.returncode != 0, (m.group(1) if m else "")
 
 
@@ -133,7 +147,7 @@ def check(verbose: bool):
     """Returns (survivors, stale): mutants no pin notices, and mutants whose text is no longer in the oracle."""
     base = tempfile.mkdtemp(prefix="oracle_mutants_")
     survivors, stale = [], []
-    for fname, muts in ((C_FILE, MUTS), (PY_FILE, PY_MUTS)):
+    for fname, muts in ((C_FILE, MUTS), (PY_FILE, PY_MUTS), (VB_FILE, VB_MUTS)):
         src = open(os.path.join(ROOT, "oracle", fname)).read()
         for name, old, new in muts:
             if old not in src:
@@ -158,7 +172,7 @@ def test_every_planted_mistake_is_noticed_by_a_pin():
 
 def test_mutant_texts_are_current():
     """Cheap guard, always run: every mutant still names text that is in the oracle's sources."""
-    for fname, muts in ((C_FILE, MUTS), (PY_FILE, PY_MUTS)):
+    for fname, muts in ((C_FILE, MUTS), (PY_FILE, PY_MUTS), (VB_FILE, VB_MUTS)):
         src = open(os.path.join(ROOT, "oracle", fname)).read()
         missing = [name for name, old, _ in muts if old not in src]
         assert not missing, (fname, missing)
