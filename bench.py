@@ -267,6 +267,69 @@ def sddmm_bench(args):
                      "kernel_ms": kernel_ms / launches, "bytes_per_launch": bytes_per_launch}}))
 
 
+def vb_bench(args):
+    """The E-step of online variational Bayes LDA (the second consumer of the normaliser, Section 5.3) over the
+    news-shaped matrix at full size: `--vb-iters` iterations per document from gamma = 1, lambda a seeded
+    concentrated topic-word state."""
+    import torch
+    from paper_1409_5402_amd import binding, synth
+
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    p = synth.PRESETS[args.workload]
+    K = p["K"]
+    corpus = synth.preset(args.workload, device=dev, scale=args.scale)
+    n_train = corpus.D - corpus.D // 10 if corpus.D >= 10 else corpus.D
+    train = corpus.slice_docs(0, n_train)
+    st = train.stats()
+    _, phi_s = synth.state(train, K, p["alpha"], p["beta"], seed=123, zipf_s=p["gen"].get("zipf_s", 0.0))
+    lam = (0.01 + phi_s * (float(st["tokens"]) / K)).contiguous()
+    del phi_s
+    g = binding.SameLDA(train.D, train.V, train.colptr, train.rowidx, train.val, K, p["alpha"], p["beta"],
+                        seed=2, m0=1, tokens_per_draw=args.tokens_per_draw)
+    b = torch.empty_like(lam)
+    shift = torch.empty(train.V, dtype=torch.float32, device=dev)
+    gamma = torch.empty((train.D, K), dtype=torch.float32, device=dev)
+    log_mu = torch.empty(train.nnz, dtype=torch.float32, device=dev)
+    alpha, iters = 0.1, args.vb_iters
+
+    def step():
+        gamma.fill_(1.0)
+        g.vb_exp_elog_beta(lam, b, shift)
+        g.vb_estep(b, shift, alpha, iters, gamma, log_mu)
+
+    warm = min(args.warmup, 3)
+    for _ in range(warm):
+        step()
+    g.synchronize()
+    g.set_timing(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    g.synchronize()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    kernel_ms, launches = g.get_timing()
+    bound = float((log_mu.double() * train.val.double()).sum() / st["tokens"])      # sum c log mu / tokens
+    g.close()
+    # per iteration: word id, count and the b row of every nonzero; per launch: gamma read and written, log mu written
+    bytes_per_launch = float(iters) * float(st["nnz"]) * (8 + 4 * K) + float(st["D"]) * 8 * K + 4.0 * float(st["nnz"])
+    achieved = bytes_per_launch / (kernel_ms / launches * 1e-3) / 1e9
+    print(json.dumps({
+        "metric": f"tokens/sec of the variational E-step ({iters} iterations per document, K={K}) + achieved HBM GB/s vs 8 TB/s",
+        "value": st["tokens"] / (dt / args.steps), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": warm,
+        "ms_per_step": 1e3 * dt / args.steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{args.workload} (LDA-generated, scale {args.scale})", "D": st["D"], "V": st["V"], "K": K,
+                   "nnz": st["nnz"], "tokens": st["tokens"], "vb_iters": iters, "alpha": alpha,
+                   "step": "exp E[log beta] of lambda, then the E-step of all documents from gamma = 1",
+                   "mean_log_mu_per_token": bound},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel": "vb_estep_kernel",
+                     "kernel_ms": kernel_ms / launches, "bytes_per_launch": bytes_per_launch}}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -287,10 +350,12 @@ def main():
     ap.add_argument("--update", choices=["collapsed", "sampled"], default="collapsed",
                     help="parameter step: the posterior means of Eq. 6 (what the paper runs, the headline) or "
                          "Dirichlet draws of theta and phi (Algorithm 2, third step; multinomial form only)")
-    ap.add_argument("--mode", choices=["resident", "stream", "sddmm", "stats"], default="resident",
+    ap.add_argument("--mode", choices=["resident", "stream", "sddmm", "stats", "vb"], default="resident",
                     help="resident: sweeps over one matrix held in HBM (the headline); stream: one sweep per "
                          "minibatch of a stream of host-resident minibatches; sddmm: the normaliser alone; "
-                         "stats: event counts of the draw kernel from a counting build of the library")
+                         "stats: event counts of the draw kernel from a counting build of the library; "
+                         "vb: the E-step of online variational Bayes LDA on the same matrix")
+    ap.add_argument("--vb-iters", type=int, default=5, help="vb mode: iterations per document")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-spec-run", action="store_true",
                     help="skip the legs beside the headline: the workload's specified run from the random start "
@@ -314,6 +379,8 @@ def main():
         args.warmup = 10
     if args.mode == "sddmm":
         return sddmm_bench(args)
+    if args.mode == "vb":
+        return vb_bench(args)
     if args.mode == "stats":
         return stats_bench(args)
     import oracle

@@ -195,6 +195,32 @@ int same_lda_debug_chunk_limit(same_lda_t* h, int64_t max_chunks, int64_t* chunk
  * When kernel timing is enabled the launch is recorded like a draw launch.                       */
 int same_lda_sddmm(same_lda_t* h, float* mu_out, int32_t out_on_device);
 
+/* A second consumer of the normaliser (Section 5.3 names it as the bottleneck the sampler shares with online
+ * variational Bayes LDA): the E-step of that method on the resident matrix.  The paper does not print the method;
+ * the update is the published one (Hoffman, Blei and Bach, 2010):
+ *     a_dk = exp(psi(gamma_dk) - psi(sum_k gamma_dk)),  b_wk = exp(psi(lambda_wk) - psi(sum_w lambda_wk)),
+ *     mu_i = sum_k a_dk b_wk for nonzero i = (d, w, c),  gamma'_dk = alpha + a_dk sum_{i in d} (c_i / mu_i) b_wk.
+ * psi and exp in double, sums over topics and nonzeros in binary32; the handle's theta and phi are not used or
+ * changed.  All pointers are DEVICE pointers owned by the caller; both calls are asynchronous on the handle's
+ * stream and allocate nothing.  Entries of lambda and gamma must be positive (not checked: others give NaN).
+ * gamma' is unchanged when a word's row of b is multiplied by a constant, and exp of E[log beta] leaves the range
+ * of binary32 for small lambda (psi(0.01) = -100.6): a row of b is therefore stored divided by its largest entry
+ * and the logarithm of that entry is kept beside it.
+ *
+ * same_lda_vb_exp_elog_beta:
+ *   lambda     [V][K] float, word-major like phi (a topic is a column, normalised over the V words)
+ *   b_out      [V][K] float: exp(E[log beta_kw] - shift_w), the largest entry of every row is 1
+ *   shift_out  [V] float: shift_w = max_k E[log beta_kw]
+ * same_lda_vb_estep: `iters` iterations gamma -> gamma' for every document of the resident matrix.
+ *   b, shift    from same_lda_vb_exp_elog_beta (shift may be null: log_mu_out then lacks the word's shift)
+ *   alpha       the documents' Dirichlet prior of this method (positive; the handle's own alpha is not used)
+ *   gamma       [D][K] float, in: the start (e.g. all ones), out: the result; iters = 0 leaves it as it is
+ *   log_mu_out  [nnz] float or null: log mu_i of the last iteration, in storage order
+ * When kernel timing is enabled the E-step launch is recorded like a draw launch.                     */
+int same_lda_vb_exp_elog_beta(same_lda_t* h, const float* lambda, float* b_out, float* shift_out);
+int same_lda_vb_estep(same_lda_t* h, const float* b, const float* shift, float alpha, int32_t iters, float* gamma,
+                      float* log_mu_out);
+
 /* Kernel timing.  When enabled, HIP events bracket the draw-and-scatter kernel of every sweep on
  * the handle's stream.  same_lda_get_timing synchronises, returns the summed duration (ms) and
  * the number of launches since the last call, and resets both.                                  */

@@ -23,6 +23,7 @@ _DTYPES = {THETA: np.float32, PHI: np.float32, NDK: np.uint32, NWK: np.uint32, N
 
 EXPORTS = ["same_lda_init", "same_lda_sweep", "same_lda_sweep_poisson", "same_lda_sweep_sampled", "same_lda_loglik", "same_lda_free",
            "same_lda_set_batch", "same_lda_stage_batch", "same_lda_commit_batch", "same_lda_debug_draw_poisson", "same_lda_sddmm",
+           "same_lda_vb_exp_elog_beta", "same_lda_vb_estep",
            "same_lda_get", "same_lda_set", "same_lda_get_pass", "same_lda_set_pass", "same_lda_task_count",
            "same_lda_debug_draw", "same_lda_debug_draw_noalloc", "same_lda_debug_chunk_limit", "same_lda_set_timing", "same_lda_get_timing", "same_lda_selftest",
            "same_lda_synchronize",
@@ -78,6 +79,8 @@ def load(path: str | None = None) -> ctypes.CDLL:
         L.same_lda_debug_draw_noalloc.argtypes = [c_void_p, c_int32, c_void_p, c_int32, c_void_p]
         L.same_lda_debug_chunk_limit.argtypes = [c_void_p, c_int64, POINTER(c_int64)]
         L.same_lda_sddmm.argtypes = [c_void_p, c_void_p, c_int32]
+        L.same_lda_vb_exp_elog_beta.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p]
+        L.same_lda_vb_estep.argtypes = [c_void_p, c_void_p, c_void_p, c_float, c_int32, c_void_p, c_void_p]
         L.same_lda_set_timing.argtypes = [c_void_p, c_int32]
         L.same_lda_get_timing.argtypes = [c_void_p, POINTER(c_double), POINTER(c_int64)]
         L.same_lda_selftest.argtypes = [POINTER(c_int64)]
@@ -263,6 +266,21 @@ class SameLDA:
         mu = np.zeros(self.nnz, np.float32)
         self._check(self._lib.same_lda_sddmm(self._h, mu.ctypes.data if mu.size else None, 0))
         return mu
+
+    def vb_exp_elog_beta(self, lam, b_out, shift_out):
+        """Rows of exp E[log beta] of lambda divided by their largest entry (b_out [V][K]) and the logarithm of that
+        entry (shift_out [V]); all float32 torch tensors on the device; asynchronous."""
+        self._check(self._lib.same_lda_vb_exp_elog_beta(self._h, lam.data_ptr(), b_out.data_ptr(), shift_out.data_ptr()))
+        return b_out, shift_out
+
+    def vb_estep(self, b, shift, alpha: float, iters: int, gamma, log_mu=None):
+        """`iters` iterations of the variational E-step on the resident matrix; b [V][K], shift [V] (or None),
+        gamma [D][K] (updated in place) and log_mu [nnz] (optional) are float32 torch tensors on the device;
+        asynchronous."""
+        self._check(self._lib.same_lda_vb_estep(self._h, b.data_ptr(), shift.data_ptr() if shift is not None else None,
+                                                float(alpha), int(iters), gamma.data_ptr(),
+                                                log_mu.data_ptr() if log_mu is not None else None))
+        return gamma
 
     def set_timing(self, enabled: bool):
         self._check(self._lib.same_lda_set_timing(self._h, 1 if enabled else 0))

@@ -19,6 +19,7 @@
 #include "gamma_kernels.h"
 #include "poisson_kernel.h"
 #include "update_kernels.h"
+#include "vb_kernels.h"
 #include "worklist_kernels.h"
 
 namespace {
@@ -131,6 +132,7 @@ struct same_lda {
     int64_t chunk_limit = -1;          // chunks a launch may use (-1: all of them); lowered by tests of the fallback
     double* gamma_partial = nullptr;   // [ceil(V / kGammaRows)][K] block sums of the sampled phi step
     float* gamma_total = nullptr;      // [K]
+    double* vb_psi = nullptr;          // [K] psi of the column sums of lambda (variational E-step)
     bool timing = false;
     std::vector<std::pair<hipEvent_t, hipEvent_t>> events;   // recorded, not yet read
     std::vector<std::pair<hipEvent_t, hipEvent_t>> pool;     // free event pairs
@@ -687,6 +689,7 @@ int same_lda_init(same_lda_t** out, const same_lda_csc* X, int32_t K, float alph
     if (!rc) rc = dev_alloc(h, &h->nk, (size_t)K);
     if (!rc) rc = dev_alloc(h, &h->gamma_partial, (size_t)((h->V + kGammaRows - 1) / kGammaRows) * K);
     if (!rc) rc = dev_alloc(h, &h->gamma_total, (size_t)K);
+    if (!rc) rc = dev_alloc(h, &h->vb_psi, (size_t)K);
     if (!rc) rc = dev_alloc(h, &h->draw_counter, (size_t)3);
     if (!rc) rc = run_pass(h, h->X, Copies::whole((uint32_t)m0), pass_word(0, 0), true, true, false, h->stream);
     if (!rc) rc = update_theta(h, h->X, (float)m0, h->stream);
@@ -828,7 +831,7 @@ void same_lda_free(same_lda_t* h)
     if (h->has_staged) free_matrix(h, h->staged);
     if (h->copy_stream) { hipStreamSynchronize(h->copy_stream); hipStreamDestroy(h->copy_stream); }
     dev_free(h, h->phi); dev_free(h, h->nwk); dev_free(h, h->nk);
-    dev_free(h, h->gamma_partial); dev_free(h, h->gamma_total); dev_free(h, h->draw_counter);
+    dev_free(h, h->gamma_partial); dev_free(h, h->gamma_total); dev_free(h, h->draw_counter); dev_free(h, h->vb_psi);
     if (h->chunks) (void)hipFree(h->chunks);
     h->cache.clear_spare();
     for (auto& e : h->events) { hipEventDestroy(e.first); hipEventDestroy(e.second); }
@@ -1028,6 +1031,56 @@ int same_lda_sddmm(same_lda_t* h, float* mu_out, int32_t out_on_device)
     }
     if (!out_on_device) dev_free(h, dst);
     if (e != hipSuccess) return fail(h, SAME_LDA_EHIP, "sddmm: %s", hipGetErrorString(e));
+    return SAME_LDA_OK;
+}
+
+int same_lda_vb_exp_elog_beta(same_lda_t* h, const float* lambda, float* b_out, float* shift_out)
+{
+    if (!h) return SAME_LDA_EINVAL;
+    if (!lambda || !b_out || !shift_out) return fail(h, SAME_LDA_EINVAL, "vb_exp_elog_beta: lambda, b_out and shift_out must be device pointers");
+    static_assert(same::kVbRows == kGammaRows, "the column sums reuse the block-sum buffer of the sampled phi step");
+    const int blocks = (h->V + same::kVbRows - 1) / same::kVbRows;
+    hipLaunchKernelGGL(same::vb_colsum_kernel, dim3(blocks), dim3(256), 0, h->stream, lambda, h->V, h->K, h->gamma_partial);
+    hipLaunchKernelGGL(same::vb_colpsi_kernel, dim3((h->K + 255) / 256), dim3(256), 0, h->stream, h->gamma_partial, blocks, h->K,
+                       h->vb_psi);
+    hipLaunchKernelGGL(same::vb_exp_elog_beta_kernel, dim3((unsigned)((h->V + 3) / 4)), dim3(256), 0, h->stream, lambda, h->V, h->K,
+                       h->vb_psi, b_out, shift_out);
+    HIP_TRY(h, hipGetLastError());
+    return SAME_LDA_OK;
+}
+
+int same_lda_vb_estep(same_lda_t* h, const float* b, const float* shift, float alpha, int32_t iters, float* gamma,
+                      float* log_mu_out)
+{
+    if (!h) return SAME_LDA_EINVAL;
+    const Matrix& M = h->X;
+    if (!(alpha > 0.f) || !std::isfinite(alpha)) return fail(h, SAME_LDA_EINVAL, "alpha must be positive and finite (got %g)", (double)alpha);
+    if (iters < 0) return fail(h, SAME_LDA_EINVAL, "iters must be >= 0 (got %d)", iters);
+    if (M.D == 0 || iters == 0) return SAME_LDA_OK;
+    if (!b || !gamma) return fail(h, SAME_LDA_EINVAL, "vb_estep: b and gamma must be device pointers");
+    const int waves_per_block = 4;
+    const unsigned blocks = (unsigned)((M.D + waves_per_block - 1) / waves_per_block);
+    std::pair<hipEvent_t, hipEvent_t> ev{nullptr, nullptr};
+    if (h->timing) {
+        if (!h->pool.empty()) { ev = h->pool.back(); h->pool.pop_back(); }
+        else { HIP_TRY(h, hipEventCreate(&ev.first)); HIP_TRY(h, hipEventCreate(&ev.second)); }
+        HIP_TRY(h, hipEventRecord(ev.first, h->stream));
+    }
+    const int K = h->K;
+    const dim3 grid(blocks), block(64 * waves_per_block);
+#define SAME_VB_LAUNCH(CH) hipLaunchKernelGGL(same::vb_estep_kernel<CH>, grid, block, 0, h->stream, M.colptr, M.rowidx, M.val, \
+                                              M.D, K, b, shift, alpha, iters, gamma, log_mu_out)
+    if (K % 4 != 0)
+        hipLaunchKernelGGL(same::vb_estep_any_kernel, grid, block, (size_t)waves_per_block * (2 * K + (K + 1) / 2) * sizeof(double), h->stream, M.colptr,
+                           M.rowidx, M.val, M.D, K, b, shift, alpha, iters, gamma, log_mu_out);
+    else if (K <= 256)  SAME_VB_LAUNCH(1);
+    else if (K <= 512)  SAME_VB_LAUNCH(2);
+    else if (K <= 1024) SAME_VB_LAUNCH(4);
+    else                SAME_VB_LAUNCH(8);
+#undef SAME_VB_LAUNCH
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess && h->timing) { e = hipEventRecord(ev.second, h->stream); if (e == hipSuccess) h->events.push_back(ev); }
+    if (e != hipSuccess) return fail(h, SAME_LDA_EHIP, "vb_estep: %s", hipGetErrorString(e));
     return SAME_LDA_OK;
 }
 
