@@ -223,7 +223,12 @@ void ensure_chunks(same_lda* h, int64_t n_slots)
     if (want <= (int64_t)h->n_chunks) return;
     want += want / 4;                                                                 // minibatches differ in size
     if (want > 0x7FFFFFFF) want = 0x7FFFFFFF;
-    if (h->chunks) { (void)hipFree(h->chunks); h->chunks = nullptr; h->n_chunks = 0; }
+    if (h->chunks) {
+        // a sweep that is still running on the handle's stream (this may be the build of a staged minibatch on the
+        // other stream) reads and writes the pool: it ends before the pool is replaced
+        (void)hipStreamSynchronize(h->stream);
+        (void)hipFree(h->chunks); h->chunks = nullptr; h->n_chunks = 0;
+    }
     size_t free_b = 0, total_b = 0;
     if (hipMemGetInfo(&free_b, &total_b) != hipSuccess) { (void)hipGetLastError(); return; }
     const size_t chunk_bytes = (size_t)same::kPairWords * sizeof(uint32_t);
