@@ -31,6 +31,7 @@
 // the sampler cuts into several pieces (independent, one uniform each) is handed to the whole wave,
 // one piece per lane.  Two consecutive steps of a task share one Philox block.
 #pragma once
+#include <type_traits>
 #include "scatter.h"
 
 namespace same {
@@ -82,7 +83,7 @@ constexpr int kWalkRounds = SAME_WALK_ROUNDS;   // rounds of kWalkSteps pmf term
 constexpr int kSegment = 256;
 
 template <bool UNIFORM, bool VEC, bool DEBUG, int TB, bool ONE>
-__global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
+__global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(TB <= 2 ? 4 : 3))) void draw_kernel(DrawArgs a)
 {
     extern __shared__ uint32_t lds[];
     float* sums = reinterpret_cast<float*>(lds);                   // [64 lanes][kSumStride]: block sums, then running sums
@@ -206,51 +207,60 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
                 return half ? lb : la;
             };
             if (VEC && TB > 0) {
-                // the loads of a batch are issued before the previous batch is summed
-                float4 pv[TB > 0 ? TB : 1], tv[TB > 0 ? TB : 1];
-                auto issue = [&](int src, int b) {
-                    const int32_t pd = __shfl(d, src), pw = __shfl(w, src);
-                    const int kb = k0 + 4 * TB * b;
-                    const float* __restrict__ tp = a.theta + (size_t)pd * K + kb;
-                    const float* __restrict__ pp = a.phi + (size_t)pw * K + kb;
+                // The loads of a batch are issued before the previous batch is summed, into two sets of registers
+                // used in turn.  Where every block is whole (K = 32 T: 256 at T = 8) the loads need no bounds.
+                struct Item { int src, b; bool last, valid; };
+                auto advance = [&](Item& it) {                     // the next (pair of tasks, batch) of this refill
+                    if (it.valid && !it.last) { it.b += 1; it.last = it.b == nb - 1; return; }
+                    if (fresh == 0) { it.valid = false; return; }
+                    it.src = pick(fresh); it.b = 0; it.last = nb == 1; it.valid = true;
+                };
+                auto run = [&](auto whole) {
+                    constexpr bool WHOLE = decltype(whole)::value;
+                    auto issue = [&](float4* pv, float4* tv, const Item& it) {
+                        const int32_t pd = __shfl(d, it.src), pw = __shfl(w, it.src);
+                        const int kb = k0 + 4 * TB * it.b;
+                        const float* __restrict__ tp = a.theta + (size_t)pd * K + kb;
+                        const float* __restrict__ pp = a.phi + (size_t)pw * K + kb;
 #pragma unroll
-                    for (int c = 0; c < TB; ++c) {
-                        if (kb + 4 * c < K) {
-                            pv[c] = *reinterpret_cast<const float4*>(pp + 4 * c);
-                            tv[c] = *reinterpret_cast<const float4*>(tp + 4 * c);
-                        } else {
-                            pv[c] = make_float4(0.f, 0.f, 0.f, 0.f);
-                            tv[c] = make_float4(0.f, 0.f, 0.f, 0.f);
+                        for (int c = 0; c < TB; ++c) {
+                            if (WHOLE || kb + 4 * c < K) {
+                                pv[c] = *reinterpret_cast<const float4*>(pp + 4 * c);
+                                tv[c] = *reinterpret_cast<const float4*>(tp + 4 * c);
+                            } else {
+                                pv[c] = make_float4(0.f, 0.f, 0.f, 0.f);
+                                tv[c] = make_float4(0.f, 0.f, 0.f, 0.f);
+                            }
                         }
+                    };
+                    float rs = 0.0f;
+                    auto consume = [&](const float4* pv, const float4* tv, const Item& it) {
+#pragma unroll
+                        for (int c = 0; c < TB; ++c) {
+                            rs = rs + tv[c].x * pv[c].x;
+                            rs = rs + tv[c].y * pv[c].y;
+                            rs = rs + tv[c].z * pv[c].z;
+                            rs = rs + tv[c].w * pv[c].w;
+                        }
+                        if (it.last) { sums[it.src * kSumStride + hl] = rs; rs = 0.0f; }
+                    };
+                    float4 pa[TB > 0 ? TB : 1], ta[TB > 0 ? TB : 1], pb[TB > 0 ? TB : 1], tb[TB > 0 ? TB : 1];
+                    Item cur{0, 0, false, false};
+                    advance(cur);
+                    if (cur.valid) issue(pa, ta, cur);
+                    while (cur.valid) {
+                        Item nxt = cur;
+                        advance(nxt);
+                        if (nxt.valid) issue(pb, tb, nxt);
+                        consume(pa, ta, cur);
+                        if (!nxt.valid) break;
+                        cur = nxt;
+                        advance(cur);
+                        if (cur.valid) issue(pa, ta, cur);
+                        consume(pb, tb, nxt);
                     }
                 };
-                int src = 0, b = 0;
-                bool more = fresh != 0;
-                if (more) { src = pick(fresh); issue(src, 0); }
-                float rs = 0.0f;
-                while (more) {
-                    const int cur = src;
-                    const bool last = b == nb - 1;
-                    float4 cp[TB > 0 ? TB : 1], ct[TB > 0 ? TB : 1];
-#pragma unroll
-                    for (int c = 0; c < TB; ++c) { cp[c] = pv[c]; ct[c] = tv[c]; }
-                    if (last) {
-                        b = 0;
-                        more = fresh != 0;
-                        if (more) src = pick(fresh);
-                    } else {
-                        b += 1;
-                    }
-                    if (more) issue(src, b);
-#pragma unroll
-                    for (int c = 0; c < TB; ++c) {
-                        rs = rs + ct[c].x * cp[c].x;
-                        rs = rs + ct[c].y * cp[c].y;
-                        rs = rs + ct[c].z * cp[c].z;
-                        rs = rs + ct[c].w * cp[c].w;
-                    }
-                    if (last) { sums[cur * kSumStride + hl] = rs; rs = 0.0f; }
-                }
+                if (nblk * T == K) run(std::true_type{}); else run(std::false_type{});
             } else {
                 while (fresh) {
                     const int src = pick(fresh);
@@ -401,23 +411,27 @@ __global__ __launch_bounds__(kWave) void draw_kernel(DrawArgs a)
                 if (UNIFORM) {
                     for (int j = 0; j < T; ++j) visit(k0 + j < K ? 1.0f : 0.0f);
                 } else if (VEC && TB > 0) {
-                    for (int b = 0; b < nb; ++b) {
-                        const int kb = k0 + 4 * TB * b;
-                        float4 pv[TB > 0 ? TB : 1], tv[TB > 0 ? TB : 1];
+                    auto reload = [&](auto whole) {
+                        constexpr bool WHOLE = decltype(whole)::value;
+                        for (int b = 0; b < nb; ++b) {
+                            const int kb = k0 + 4 * TB * b;
+                            float4 pv[TB > 0 ? TB : 1], tv[TB > 0 ? TB : 1];
 #pragma unroll
-                        for (int c = 0; c < TB; ++c) {
-                            const bool in = kb + 4 * c < K;
-                            pv[c] = in ? *reinterpret_cast<const float4*>(ph + kb + 4 * c) : make_float4(0.f, 0.f, 0.f, 0.f);
-                            tv[c] = in ? *reinterpret_cast<const float4*>(th + kb + 4 * c) : make_float4(0.f, 0.f, 0.f, 0.f);
-                        }
+                            for (int c = 0; c < TB; ++c) {
+                                const bool in = WHOLE || kb + 4 * c < K;
+                                pv[c] = in ? *reinterpret_cast<const float4*>(ph + kb + 4 * c) : make_float4(0.f, 0.f, 0.f, 0.f);
+                                tv[c] = in ? *reinterpret_cast<const float4*>(th + kb + 4 * c) : make_float4(0.f, 0.f, 0.f, 0.f);
+                            }
 #pragma unroll
-                        for (int c = 0; c < TB; ++c) {
-                            visit(tv[c].x * pv[c].x);
-                            visit(tv[c].y * pv[c].y);
-                            visit(tv[c].z * pv[c].z);
-                            visit(tv[c].w * pv[c].w);
+                            for (int c = 0; c < TB; ++c) {
+                                visit(tv[c].x * pv[c].x);
+                                visit(tv[c].y * pv[c].y);
+                                visit(tv[c].z * pv[c].z);
+                                visit(tv[c].w * pv[c].w);
+                            }
                         }
-                    }
+                    };
+                    if (nblk * T == K) reload(std::true_type{}); else reload(std::false_type{});
                 } else if (VEC) {
                     for (int c = 0; c < T / 4; ++c) {
                         const int k = k0 + 4 * c;
