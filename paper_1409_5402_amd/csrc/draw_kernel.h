@@ -87,7 +87,8 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(TB <= 2 ?
 {
     extern __shared__ uint32_t lds[];
     float* sums = reinterpret_cast<float*>(lds);                   // [64 lanes][kSumStride]: block sums, then running sums
-    uint32_t* acc = lds + (size_t)kWave * kSumStride;              // [64] piece totals by owner lane
+    uint32_t* acc = lds + kMaxBlocks;                              // piece totals by owner lane: lane l's is acc[l * kSumStride],
+                                                                   // the word of its row of sums that pads the stride
     const int lane = threadIdx.x;
     const int K = a.K;
     const int T = (TB > 0 && ONE) ? 4 * TB : block_len(K);         // topics per block
@@ -98,8 +99,8 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(TB <= 2 ?
     // in storage order: the 64 lanes hold tasks of one or two documents at a time).  Counts are added here and
     // reach the matrix in one pass over the row when the wave has left the document; tasks of a document that
     // has no row here add to the matrix at once.
-    uint32_t* stage = acc + kWave + lane;                          // [4][64] pairs on their way to the pair list
-    uint32_t* rows = acc + 5 * kWave;                              // [n_rows][K]
+    uint32_t* stage = lds + (size_t)kWave * kSumStride + lane;     // [3][64] pairs on their way to the pair list
+    uint32_t* rows = lds + (size_t)kWave * (kSumStride + 3);       // [n_rows][K]
     const int n_rows = DEBUG ? 0 : doc_rows(K);
     int tag0 = -1, tag1 = -1;                                      // the documents of rows 0 and 1 (wave-uniform), -1: free
     int myrow = -1;                                                // the row of this lane's document, -1: none
@@ -108,7 +109,7 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(TB <= 2 ?
     bool drained = false;                                          // the counter has passed the last position
     uint32_t chunk_next = 0, chunk_end = 0;                        // the wave's share of the chunk pool not yet handed out
     bool pool_dry = a.chunks == nullptr;                           // the pool has no chunk left for this wave
-    acc[lane] = 0u;
+    acc[lane * kSumStride] = 0u;
 
     // ---- the lane's current task
 #ifdef SAME_STATS
@@ -346,12 +347,12 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(TB <= 2 ?
                     if (next_cdf == cdfj) break;
                     cdfj = next_cdf;
                 }
-                if (xj > 0) atomicAdd(acc + owner, xj);
+                if (xj > 0) atomicAdd(acc + owner * kSumStride, xj);
             }
         }
         __syncthreads();
         uint32_t part = 0;
-        if (st == 3) { part = acc[lane]; acc[lane] = 0u; }
+        if (st == 3) { part = acc[lane * kSumStride]; acc[lane * kSumStride] = 0u; }
         __syncthreads();
         return part;
     };
@@ -588,6 +589,6 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(TB <= 2 ?
     if (n_rows > 1 && tag1 >= 0) flush_row(1, tag1);
 }
 
-inline size_t draw_lds_bytes(int K) { return 4u * ((size_t)kWave * (size_t)(kSumStride + 5) + (size_t)doc_rows(K) * (size_t)K); }
+inline size_t draw_lds_bytes(int K) { return 4u * ((size_t)kWave * (size_t)(kSumStride + 3) + (size_t)doc_rows(K) * (size_t)K); }
 
 }  // namespace same

@@ -97,7 +97,7 @@ __global__ __launch_bounds__(kWave) void poisson_draw_kernel(DrawArgs a)
     constexpr int qw = 3;                                          // words per queue entry
     uint32_t* que = lds;                                           // [kQCap][qw][64], a ring per lane
     uint32_t* acc = lds + (size_t)(qw * kQCap) * kWave;            // [64] piece totals by owner lane
-    uint32_t* stage = acc + kWave + threadIdx.x;                   // [4][64] pairs on their way to the pair list
+    uint32_t* stage = acc + kWave + threadIdx.x;                   // [3][64] pairs on their way to the pair list
     static_assert(kQCap <= 16, "two bits per ring slot in one register");
     uint32_t khi = 0;       // bits 9 and 10 of the topic queued in each ring slot (the entry holds the low nine)
 
@@ -304,6 +304,6 @@ __global__ __launch_bounds__(kWave) void poisson_draw_kernel(DrawArgs a)
     if (!DEBUG && live && a.cost) a.cost[tau] = (3u * a.cost[tau] + busy + 2u) >> 2;
 }
 
-inline size_t poisson_lds_bytes() { return 4u * (size_t)kWave * (size_t)(3 * kQCap + 5); }
+inline size_t poisson_lds_bytes() { return 4u * (size_t)kWave * (size_t)(3 * kQCap + 4); }
 
 }  // namespace same

@@ -72,19 +72,20 @@ constexpr int kHotCopies = 32;          // copies of a hot word's row
 // places more than 15 pairs (most tasks do while the posterior is still flat) continues in chunks of the same
 // shape taken from a pool: the header of a full slot or chunk names the chunk that follows it, the header of
 // the last one holds its number of pairs.  When the pool is used up the remaining counts go straight to the
-// word's row.  Pairs are collected four at a time in LDS (stage: this lane's four words, kWave words apart)
-// and written with one 16-byte store: the memory system handles a 16-byte write as fast as a 4-byte one.
+// word's row.  Pairs are collected in LDS (stage: this lane's three words, kWave words apart) and written four
+// at a time, the fourth from its register, with one 16-byte store: the memory system handles a 16-byte write
+// as fast as a 4-byte one.
 struct Scatter {
     uint32_t* __restrict__ out_d;     // the document's row (debug launches: the task's output row)
     uint32_t* __restrict__ out_w;     // the word's row (for a hot word: this workgroup's copy of it), or null
     uint32_t* __restrict__ pslot;     // the slot or chunk the task is filling, or null
     uint32_t npairs;                  // pairs in it
 
-    // words 4q .. 4q+3 of the slot from the staged four
-    __device__ __forceinline__ void store_quad(uint32_t q, const uint32_t* stage)
+    // words 4q .. 4q+3 of the slot: the three staged words and a fourth
+    __device__ __forceinline__ void store_quad(uint32_t q, const uint32_t* stage, uint32_t fourth)
     {
         uint4 v;
-        v.x = stage[0]; v.y = stage[kWave]; v.z = stage[2 * kWave]; v.w = stage[3 * kWave];
+        v.x = stage[0]; v.y = stage[kWave]; v.z = stage[2 * kWave]; v.w = fourth;
         *reinterpret_cast<uint4*>(pslot + 4u * q) = v;
     }
     __device__ __forceinline__ void emit(int k, uint32_t n, uint32_t* stage)
@@ -98,8 +99,9 @@ struct Scatter {
         if (pslot) {
             if (npairs < (uint32_t)(kPairWords - 1)) {
                 const uint32_t j = npairs & 3u;
-                stage[j * kWave] = (uint32_t)k | (n << kPairShift);
-                if (j == 3u) store_quad(npairs >> 2, stage);       // pairs 0-3, 4-7 or 8-11
+                const uint32_t pair = (uint32_t)k | (n << kPairShift);
+                if (j == 3u) store_quad(npairs >> 2, stage, pair);  // pairs 0-3, 4-7 or 8-11
+                else stage[j * kWave] = pair;
                 npairs += 1;
             } else {
                 atomicAdd(out_w + k, n);                           // full and no chunk to go on with: straight to the row
@@ -112,8 +114,7 @@ struct Scatter {
     // a full slot (pairs 12-14 are still staged) goes on in chunk idx of the pool
     __device__ __forceinline__ void extend(uint32_t* __restrict__ pool, uint32_t idx, uint32_t* stage)
     {
-        stage[3 * kWave] = kPairLink | idx;
-        store_quad(3u, stage);
+        store_quad(3u, stage, kPairLink | idx);
         pslot = pool + (size_t)idx * kPairWords;
         npairs = 0;
     }
@@ -123,10 +124,9 @@ struct Scatter {
         if (pslot && live) {
             const uint32_t q = npairs >> 2;
             if (q == 3u) {                                         // the header shares the last quad
-                stage[3 * kWave] = npairs;
-                store_quad(3u, stage);
+                store_quad(3u, stage, npairs);
             } else {
-                if ((npairs & 3u) != 0u) store_quad(q, stage);     // words past the last pair are never read
+                if ((npairs & 3u) != 0u) store_quad(q, stage, 0u); // words past the last pair are never read
                 pslot[kPairWords - 1] = npairs;
             }
         }
