@@ -80,7 +80,10 @@ constexpr int kWalkRounds = SAME_WALK_ROUNDS;   // rounds of kWalkSteps pmf term
 // for the slowest of 64 fixed tasks would idle most of the time, and a wave with a fixed share of the matrix
 // would end with one lane busy.  Whenever kRefillMin lanes are idle the wave stops stepping, gives each idle
 // lane the next position, scans the new tasks (two per instruction) and goes on.
-constexpr int kSegment = 256;
+#ifndef SAME_SEGMENT
+#define SAME_SEGMENT 512
+#endif
+constexpr int kSegment = SAME_SEGMENT;
 
 template <bool UNIFORM, bool VEC, bool DEBUG, int TB, bool ONE>
 __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(TB <= 2 ? 4 : 3))) void draw_kernel(DrawArgs a)

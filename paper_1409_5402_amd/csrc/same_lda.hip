@@ -27,6 +27,10 @@ namespace {
 thread_local std::string g_init_error;
 
 constexpr int32_t kTileDocs = 16;   // documents per tile of the processing order
+#ifndef SAME_GRID_PER_CU
+#define SAME_GRID_PER_CU 16
+#endif
+constexpr int64_t kDrawGrid = 256 * SAME_GRID_PER_CU;   // workgroups of the multinomial draw kernel: as many as are resident at once (sixteen waves per compute unit)
 constexpr int kGammaRows = 64;      // rows of n_wk per workgroup of the sampled phi step
 
 // Device copy of one sparse matrix plus its draw work list.
@@ -479,10 +483,10 @@ int launch_draw(same_lda* h, const same::DrawArgs& a, bool uniform, bool poisson
         if (a.K % same::kBlk == 0) hipLaunchKernelGGL((same::poisson_draw_kernel<true, DEBUG>), grid, block, lds, st, a);
         else                       hipLaunchKernelGGL((same::poisson_draw_kernel<false, DEBUG>), grid, block, lds, st, a);
     } else {
-        // Workgroups take segments of launch positions from a counter until none is left: a few per compute
-        // unit more than fit at once, so that the chip is full from the first moment to the last.
+        // Workgroups take segments of launch positions from a counter until none is left: as many workgroups as
+        // the chip holds at once, so that it is full from the first moment to the last.
         const int64_t segments = (a.n + same::kSegment - 1) / same::kSegment;
-        dim3 grid((unsigned)(segments < 256 * 24 ? segments : 256 * 24));
+        dim3 grid((unsigned)(segments < kDrawGrid ? segments : kDrawGrid));
         // blocks of 4 * ceil(K / 128) topics, read in batches of one, two or four 16-byte loads per matrix
         const size_t lds = same::draw_lds_bytes(a.K);
         const bool vec = a.K % 4 == 0;
