@@ -127,6 +127,49 @@ def _assert_counts_equal(g, o, what):
 
 
 @pytest.mark.timeout(900)
+def test_news_full_size_one_sweep_every_element():
+    """One sweep at m = 100 over the whole news-shaped matrix (60.6M nonzeros, K = 256) from a seeded concentrated
+    state, then one from the flat state right after the initialisation (every task overflows its pair-list slot and
+    goes on in chunks of the pool): both count matrices equal the oracle's in every element, theta and phi follow.
+    The oracle needs some ten seconds per sweep on the machine's host cores."""
+    dev = torch.device("cuda:0")
+    p = synth.PRESETS["news"]
+    K, m, alpha, beta, G = p["K"], p["m"], p["alpha"], p["beta"], binding.DEFAULT_TOKENS_PER_DRAW
+    corpus = synth.preset("news", device=dev)
+    train = corpus.slice_docs(0, corpus.D - corpus.D // 10)
+    X = oracle.CSC(train.D, train.V, train.colptr.cpu().numpy(), train.rowidx.cpu().numpy(), train.val.cpu().numpy())
+    g = binding.SameLDA(train.D, train.V, train.colptr, train.rowidx, train.val, K, alpha, beta,
+                        seed=9, m0=1, tokens_per_draw=G)
+
+    def check(theta, phi, what):
+        pword = oracle.pass_word(g.pass_index)
+        g.sweep(m)
+        ndk_o, nwk_o, _ = oracle.run_pass(X, K, G, m, 9, pword, theta, phi)
+        ndk = g.get(binding.NDK)
+        bad = np.flatnonzero((ndk != ndk_o).any(axis=1))
+        assert bad.size == 0, f"{what}: n_dk differs in {bad.size} documents, first {bad[:5]}"
+        del ndk
+        nwk = g.get(binding.NWK)
+        bad = np.flatnonzero((nwk != nwk_o).any(axis=1))
+        assert bad.size == 0, f"{what}: n_wk differs in {bad.size} words, first {bad[:5]}"
+        np.testing.assert_allclose(g.get(binding.THETA), oracle.theta_update(ndk_o, m, alpha), rtol=1e-5, err_msg=what)
+        np.testing.assert_allclose(g.get(binding.PHI), oracle.phi_update(nwk_o, m, beta, 1.0, None), rtol=1e-5, err_msg=what)
+
+    # the flat state the library's own initialisation leaves (the oracle repeats the initial pass)
+    ndk0, nwk0, _ = oracle.run_pass(X, K, G, 1, 9, oracle.pass_word(0), None, None)
+    theta0, phi0 = oracle.theta_update(ndk0, 1, alpha), oracle.phi_update(nwk0, 1, beta, 1.0, None)
+    assert np.array_equal(g.get(binding.NDK), ndk0) and np.array_equal(g.get(binding.NWK), nwk0)
+    del ndk0, nwk0
+    check(theta0, phi0, "first sweep after the initialisation")
+    del theta0, phi0
+    theta_t, phi_t = synth.state(train, K, alpha, beta, seed=126, zipf_s=1.1)
+    g.set(binding.THETA, theta_t)
+    g.set(binding.PHI, phi_t)
+    check(theta_t.cpu().numpy(), phi_t.cpu().numpy(), "sweep from the seeded concentrated state")
+    g.close()
+
+
+@pytest.mark.timeout(900)
 def test_medium_full_size_all_twenty_annealed_sweeps():
     """The medium workload at its real size (D=50,000, V=20,000, K=64; Zipf-skewed words) through all twenty
     sweeps of the linear schedule m = 1..20 (Section 6.1.3): the whole state against the oracle after every
