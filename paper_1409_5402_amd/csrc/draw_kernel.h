@@ -120,10 +120,8 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(TB <= 2 ?
 #endif
     bool open = false;      // a task was taken and its slot of the pair list is not yet closed
     int32_t d = 0, w = 0;
-    const float* __restrict__ th = nullptr;
-    const float* __restrict__ ph = nullptr;
     Scatter sc;
-    sc.out_d = nullptr; sc.out_w = nullptr; sc.pslot = nullptr; sc.npairs = 0;
+    sc.drow = 0; sc.wrow = kNone; sc.slot = kNone; sc.npairs = 0;
     StreamKey key;
     key.seed_lo = a.seed_lo; key.seed_hi = a.seed_hi; key.tau_lo = 0; key.tau_hi = 0; key.pass = a.pass;
     PrimaryPre pre = primary_pre(key);
@@ -156,7 +154,7 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(TB <= 2 ?
     // per half-wave: lane hl of a half owns block hl), each new lane turns its sums into running sums.
     auto refill = [&](uint64_t idle_mask) {
         const bool idle = (idle_mask >> lane) & 1ull;
-        if (idle && open) { sc.close(true, stage); open = false; }
+        if (idle && open) { sc.close(a, true, stage); open = false; }
         const int rank = (int)__popcll(idle_mask & ((1ull << lane) - 1ull));
         const int avail = end - next;
         const bool take = idle && rank < avail;
@@ -169,8 +167,6 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(TB <= 2 ?
 #ifdef SAME_STATS
             R_task_g = a.t_g[tau];
 #endif
-            th = UNIFORM ? nullptr : a.theta + (size_t)d * K;
-            ph = UNIFORM ? nullptr : a.phi + (size_t)w * K;
             sc = make_scatter<DEBUG>(a, pos, tau, d, w);
             key.tau_lo = (uint32_t)tau; key.tau_hi = (uint32_t)((uint64_t)tau >> 32) & 0xFFu;
             pre = primary_pre(key);
@@ -221,16 +217,20 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(TB <= 2 ?
                 };
                 auto run = [&](auto whole) {
                     constexpr bool WHOLE = decltype(whole)::value;
-                    auto issue = [&](float4* pv, float4* tv, const Item& it) {
+                    // a set of registers keeps the theta values it holds while the document stays the same (a document's
+                    // tasks are consecutive): only the phi row of the next task is loaded then
+                    auto issue = [&](float4* pv, float4* tv, int32_t& held, const Item& it) {
                         const int32_t pd = __shfl(d, it.src), pw = __shfl(w, it.src);
                         const int kb = k0 + 4 * TB * it.b;
                         const float* __restrict__ tp = a.theta + (size_t)pd * K + kb;
                         const float* __restrict__ pp = a.phi + (size_t)pw * K + kb;
+                        const bool same = ONE && pd == held;
+                        held = pd;
 #pragma unroll
                         for (int c = 0; c < TB; ++c) {
                             if (WHOLE || kb + 4 * c < K) {
                                 pv[c] = *reinterpret_cast<const float4*>(pp + 4 * c);
-                                tv[c] = *reinterpret_cast<const float4*>(tp + 4 * c);
+                                if (!same) tv[c] = *reinterpret_cast<const float4*>(tp + 4 * c);
                             } else {
                                 pv[c] = make_float4(0.f, 0.f, 0.f, 0.f);
                                 tv[c] = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -249,18 +249,19 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(TB <= 2 ?
                         if (it.last) { sums[it.src * kSumStride + hl] = rs; rs = 0.0f; }
                     };
                     float4 pa[TB > 0 ? TB : 1], ta[TB > 0 ? TB : 1], pb[TB > 0 ? TB : 1], tb[TB > 0 ? TB : 1];
+                    int32_t da = -1, db = -1;                      // the documents whose theta values ta and tb hold
                     Item cur{0, 0, false, false};
                     advance(cur);
-                    if (cur.valid) issue(pa, ta, cur);
+                    if (cur.valid) issue(pa, ta, da, cur);
                     while (cur.valid) {
                         Item nxt = cur;
                         advance(nxt);
-                        if (nxt.valid) issue(pb, tb, nxt);
+                        if (nxt.valid) issue(pb, tb, db, nxt);
                         consume(pa, ta, cur);
                         if (!nxt.valid) break;
                         cur = nxt;
                         advance(cur);
-                        if (cur.valid) issue(pa, ta, cur);
+                        if (cur.valid) issue(pa, ta, da, cur);
                         consume(pb, tb, nxt);
                     }
                 };
@@ -403,6 +404,8 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(TB <= 2 ?
                 const float base = l > 0 ? sums[lane * kSumStride + l - 1] : 0.0f;
                 // inside the block: rebuild P_k from the block's weights, count the topics still below y
                 const int k0 = l * T;
+                const float* __restrict__ th = UNIFORM ? nullptr : a.theta + (size_t)d * K;   // the task's rows
+                const float* __restrict__ ph = UNIFORM ? nullptr : a.phi + (size_t)w * K;
                 int below = 0;
                 float prev = base, rs = 0.0f;
                 auto visit = [&](float wk) {
@@ -550,7 +553,7 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(TB <= 2 ?
                     if (lane == 0) SAME_COUNT(a, 14, 1);               // batches of chunks taken
                 }
                 const uint32_t mine = chunk_next + (uint32_t)__popcll((unsigned long long)(need_mask & ((1ull << lane) - 1ull)));
-                if (need && mine < chunk_end) { sc.extend(a.chunks, mine, stage); SAME_COUNT(a, 15, 1); }
+                if (need && mine < chunk_end) { sc.extend(a, mine, stage); SAME_COUNT(a, 15, 1); }
                 chunk_next = chunk_end - chunk_next < cnt ? chunk_end : chunk_next + cnt;
             }
         }
@@ -562,8 +565,8 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(TB <= 2 ?
         }
 #endif
         if (en > 0u) {
-            if (myrow >= 0) { atomicAdd(rows + myrow * K + ek, en); sc.emit_word(ek, en, stage); }
-            else sc.emit(ek, en, stage);
+            if (myrow >= 0) { atomicAdd(rows + myrow * K + ek, en); sc.emit_word(a, ek, en, stage); }
+            else sc.emit(a, ek, en, stage);
         }
     };
 
@@ -587,7 +590,7 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(TB <= 2 ?
         if (idle_mask == ~0ull) break;                             // nothing in flight and nothing left to take
         trip();
     }
-    if (open) sc.close(true, stage);
+    if (open) sc.close(a, true, stage);
     if (n_rows > 0 && tag0 >= 0) flush_row(0, tag0);
     if (n_rows > 1 && tag1 >= 0) flush_row(1, tag1);
 }

@@ -197,7 +197,7 @@ __global__ __launch_bounds__(kWave) void poisson_draw_kernel(DrawArgs a)
         if (st == 3) {
             const uint32_t nk = acc[lane];
             acc[lane] = 0u;
-            if (nk > 0) { sc.emit(kk, nk, stage); SAME_COUNT(a, 5, 1); }
+            if (nk > 0) { sc.emit(a, kk, nk, stage); SAME_COUNT(a, 5, 1); }
             st = 0;
         }
         __syncthreads();
@@ -254,7 +254,7 @@ __global__ __launch_bounds__(kWave) void poisson_draw_kernel(DrawArgs a)
                 stalled = stalled || (go && still);
             }
             if (walking && (stalled || !(u > cdf))) {              // the piece is finished
-                if (xw > 0) { sc.emit(kk, xw, stage); SAME_COUNT(a, 5, 1); }
+                if (xw > 0) { sc.emit(a, kk, xw, stage); SAME_COUNT(a, 5, 1); }
                 st = 0;
             }
         }
@@ -298,7 +298,7 @@ __global__ __launch_bounds__(kWave) void poisson_draw_kernel(DrawArgs a)
         }
     }
     while (__any(st != 0 || cnt > 0)) trip();
-    sc.close(live, stage);
+    sc.close(a, live, stage);
     // The ordering key for the next pass: a running mean (weight 1/4 on this pass) predicts a task's next
     // cost a little better than this pass's cost alone.
     if (!DEBUG && live && a.cost) a.cost[tau] = (3u * a.cost[tau] + busy + 2u) >> 2;

@@ -75,59 +75,69 @@ constexpr int kHotCopies = 32;          // copies of a hot word's row
 // word's row.  Pairs are collected in LDS (stage: this lane's three words, kWave words apart) and written four
 // at a time, the fourth from its register, with one 16-byte store: the memory system handles a 16-byte write
 // as fast as a 4-byte one.
-struct Scatter {
-    uint32_t* __restrict__ out_d;     // the document's row (debug launches: the task's output row)
-    uint32_t* __restrict__ out_w;     // the word's row (for a hot word: this workgroup's copy of it), or null
-    uint32_t* __restrict__ pslot;     // the slot or chunk the task is filling, or null
-    uint32_t npairs;                  // pairs in it
+constexpr uint32_t kNone = 0xFFFFFFFFu;
+constexpr uint32_t kInPool = 0x80000000u;   // Scatter::slot: the index is one of the pool's chunks, not of the pair list's slots
 
+// The struct holds row and slot numbers, not addresses: a lane keeps it for the whole life of its task, and
+// registers decide how many waves a compute unit holds.
+struct Scatter {
+    uint32_t drow;      // row of a.ndk that takes the counts (the document; debug launches: the task's output row)
+    uint32_t wrow;      // row of a.nwk that takes direct updates (the word, or this workgroup's copy of a hot word's row), kNone: none
+    uint32_t slot;      // the slot (or, with kInPool, the chunk) the task is filling, kNone: none
+    uint32_t npairs;    // pairs in it
+
+    __device__ __forceinline__ uint32_t* slot_words(const DrawArgs& a) const
+    {
+        uint32_t* base = (slot & kInPool) ? a.chunks : a.pairs;
+        return base + (size_t)(slot & ~kInPool) * kPairWords;
+    }
     // words 4q .. 4q+3 of the slot: the three staged words and a fourth
-    __device__ __forceinline__ void store_quad(uint32_t q, const uint32_t* stage, uint32_t fourth)
+    __device__ __forceinline__ void store_quad(const DrawArgs& a, uint32_t q, const uint32_t* stage, uint32_t fourth) const
     {
         uint4 v;
         v.x = stage[0]; v.y = stage[kWave]; v.z = stage[2 * kWave]; v.w = fourth;
-        *reinterpret_cast<uint4*>(pslot + 4u * q) = v;
+        *reinterpret_cast<uint4*>(slot_words(a) + 4u * q) = v;
     }
-    __device__ __forceinline__ void emit(int k, uint32_t n, uint32_t* stage)
+    __device__ __forceinline__ void emit(const DrawArgs& a, int k, uint32_t n, uint32_t* stage)
     {
-        atomicAdd(out_d + k, n);
-        emit_word(k, n, stage);
+        atomicAdd(a.ndk + (size_t)drow * a.K + k, n);
+        emit_word(a, k, n, stage);
     }
     // the word's half alone (the caller has added the count to the document's row itself)
-    __device__ __forceinline__ void emit_word(int k, uint32_t n, uint32_t* stage)
+    __device__ __forceinline__ void emit_word(const DrawArgs& a, int k, uint32_t n, uint32_t* stage)
     {
-        if (pslot) {
+        if (slot != kNone) {
             if (npairs < (uint32_t)(kPairWords - 1)) {
                 const uint32_t j = npairs & 3u;
                 const uint32_t pair = (uint32_t)k | (n << kPairShift);
-                if (j == 3u) store_quad(npairs >> 2, stage, pair);  // pairs 0-3, 4-7 or 8-11
+                if (j == 3u) store_quad(a, npairs >> 2, stage, pair);   // pairs 0-3, 4-7 or 8-11
                 else stage[j * kWave] = pair;
                 npairs += 1;
             } else {
-                atomicAdd(out_w + k, n);                           // full and no chunk to go on with: straight to the row
+                atomicAdd(a.nwk + (size_t)wrow * a.K + k, n);      // full and no chunk to go on with: straight to the row
             }
-        } else if (out_w) {
-            atomicAdd(out_w + k, n);
+        } else if (wrow != kNone) {
+            atomicAdd(a.nwk + (size_t)wrow * a.K + k, n);
         }
     }
-    __device__ __forceinline__ bool full() const { return pslot != nullptr && npairs >= (uint32_t)(kPairWords - 1); }
+    __device__ __forceinline__ bool full() const { return slot != kNone && npairs >= (uint32_t)(kPairWords - 1); }
     // a full slot (pairs 12-14 are still staged) goes on in chunk idx of the pool
-    __device__ __forceinline__ void extend(uint32_t* __restrict__ pool, uint32_t idx, uint32_t* stage)
+    __device__ __forceinline__ void extend(const DrawArgs& a, uint32_t idx, uint32_t* stage)
     {
-        store_quad(3u, stage, kPairLink | idx);
-        pslot = pool + (size_t)idx * kPairWords;
+        store_quad(a, 3u, stage, kPairLink | idx);
+        slot = kInPool | idx;
         npairs = 0;
     }
     // the staged pairs and the header of the last slot or chunk: how many pairs it holds
-    __device__ __forceinline__ void close(bool live, uint32_t* stage)
+    __device__ __forceinline__ void close(const DrawArgs& a, bool live, uint32_t* stage) const
     {
-        if (pslot && live) {
+        if (slot != kNone && live) {
             const uint32_t q = npairs >> 2;
             if (q == 3u) {                                         // the header shares the last quad
-                store_quad(3u, stage, npairs);
+                store_quad(a, 3u, stage, npairs);
             } else {
-                if ((npairs & 3u) != 0u) store_quad(q, stage, 0u); // words past the last pair are never read
-                pslot[kPairWords - 1] = npairs;
+                if ((npairs & 3u) != 0u) store_quad(a, q, stage, 0u);   // words past the last pair are never read
+                slot_words(a)[kPairWords - 1] = npairs;
             }
         }
     }
@@ -137,17 +147,15 @@ template <bool DEBUG>
 __device__ __forceinline__ Scatter make_scatter(const DrawArgs& a, int64_t row, int64_t tau, int32_t d, int32_t w)
 {
     Scatter s;
-    const int K = a.K;
-    s.out_d = DEBUG ? a.ndk + (size_t)row * K : a.ndk + (size_t)d * K;
-    s.out_w = nullptr;
-    s.pslot = nullptr;
+    s.drow = DEBUG ? (uint32_t)row : (uint32_t)d;
+    s.wrow = kNone;
+    s.slot = kNone;
     if (!DEBUG && a.nwk != nullptr) {
         const int hot = a.hot_of ? (int)a.hot_of[w] : -1;
-        const size_t wrow = hot < 0 ? (size_t)w : (size_t)a.V + (size_t)(blockIdx.x % kHotCopies) * kHotMax + (size_t)hot;
-        s.out_w = a.nwk + wrow * K;
+        s.wrow = hot < 0 ? (uint32_t)w : (uint32_t)a.V + (uint32_t)(blockIdx.x % kHotCopies) * (uint32_t)kHotMax + (uint32_t)hot;
         if (a.pairs != nullptr) {
             const int32_t slot_id = a.t_slot[tau];
-            if (slot_id >= 0) s.pslot = a.pairs + (size_t)slot_id * kPairWords;
+            if (slot_id >= 0) s.slot = (uint32_t)slot_id;
         }
     }
     s.npairs = 0;
