@@ -5,7 +5,7 @@ import os
 import subprocess
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-SRC = [os.path.join(HERE, "csrc", "same_lda.hip"), os.path.join(HERE, "csrc", "worklist.hip")]
+SRC = [os.path.join(HERE, "csrc", "same_lda.hip")]
 LIB = os.path.join(HERE, "libsame_lda.so")
 
 # -ffp-contract=off: every binary32 step of the draw is rounded once (no fused multiply-add);

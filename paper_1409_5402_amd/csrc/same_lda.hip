@@ -210,9 +210,26 @@ struct Temps {
     ~Temps() { (void)hipStreamSynchronize(st); for (void* v : ptrs) h->cache.put(v); }
 };
 
-// Validates the matrix and builds its work list on the device (worklist_kernels.h).  The matrix may
-// live on the host or on the device; it is copied once.  All work is enqueued on st; the call
-// waits for st twice (to learn the number of tasks and of pair-list slots).
+// out[i] = in[0] + ... + in[i-1] for n items (worklist_kernels.h): tile totals, their exclusive sum by the same
+// steps, then the tiles.  Temporaries come from tmp and are handed back with it.
+hipError_t exclusive_sum(Temps& tmp, const uint32_t* in, uint32_t* out, size_t n, hipStream_t st)
+{
+    if (n == 0) return hipSuccess;
+    const size_t tiles = (n + same::kScanTile - 1) / same::kScanTile;
+    uint32_t* tile_base = nullptr;
+    if (tiles > 1) {
+        uint32_t* tile_sum = nullptr;
+        hipError_t e = tmp.get(&tile_sum, tiles);
+        if (e == hipSuccess) e = tmp.get(&tile_base, tiles);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(same::wl_tile_sums, dim3((unsigned)tiles), dim3(same::kScanThreads), 0, st, in, n, tile_sum);
+        e = exclusive_sum(tmp, tile_sum, tile_base, tiles, st);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(same::wl_tile_scan, dim3((unsigned)tiles), dim3(same::kScanThreads), 0, st, in, n, tile_base, out);
+    return hipGetLastError();
+}
+
 // The pool of chunks that continue full pair-list slots (scatter.h).  A task places at most K pairs, 15 of them in
 // its slot; eight chunks per slot cover a sweep from a flat posterior (a hundred copies of a token then reach some
 // eighty topics), and a sweep that needs more sends the rest straight to the word rows.  The pool never takes more
@@ -244,6 +261,9 @@ void ensure_chunks(same_lda* h, int64_t n_slots)
     h->n_chunks = (uint32_t)want;
 }
 
+// Validates the matrix and builds its work list on the device (worklist_kernels.h).  The matrix may
+// live on the host or on the device; it is copied once.  All work is enqueued on st; the call
+// waits for st twice (to learn the number of tasks and of pair-list slots).
 int build_matrix(same_lda* h, const same_lda_csc* X, int32_t V, int32_t K, int32_t G, Matrix& M, hipStream_t st,
                  bool with_pairs)
 {
@@ -281,12 +301,9 @@ int build_matrix(same_lda* h, const same_lda_csc* X, int32_t V, int32_t K, int32
     Temps tmp(h, st);
     same::BuildStats* d_stats = nullptr;
     uint32_t *ntask = nullptr, *tbase = nullptr;
-    void* scan_tmp = nullptr;
-    const size_t scan_bytes = same::wl_exclusive_sum_bytes((size_t)nnz + 1);
     HIP_TRY(h, tmp.get(&d_stats, 1));
     HIP_TRY(h, tmp.get(&ntask, (size_t)nnz + 1));
     HIP_TRY(h, tmp.get(&tbase, (size_t)nnz + 1));
-    HIP_TRY(h, tmp.get(reinterpret_cast<char**>(&scan_tmp), scan_bytes));
     hipLaunchKernelGGL(same::wl_init_stats, dim3(1), dim3(1), 0, st, d_stats);
     if (D > 0) hipLaunchKernelGGL(same::wl_check_cols, dim3((unsigned)((D + 255) / 256)), dim3(256), 0, st, M.colptr, D, d_stats);
     hipLaunchKernelGGL(same::wl_scan_nonzeros, dim3(grid_for((size_t)nnz + 1)), dim3(256), 0, st, M.colptr, M.rowidx,
@@ -349,7 +366,7 @@ int build_matrix(same_lda* h, const same_lda_csc* X, int32_t V, int32_t K, int32
     if ((rc = dev_alloc(h, &M.tile_start, (size_t)M.n_tiles + 1))) return rc;
     if ((rc = dev_alloc(h, &M.theta, (size_t)D * K))) return rc;
     if ((rc = dev_alloc(h, &M.ndk, (size_t)D * K))) return rc;
-    HIP_TRY(h, same::wl_exclusive_sum(scan_tmp, scan_bytes, ntask, tbase, (size_t)nnz + 1, st));
+    HIP_TRY(h, exclusive_sum(tmp, ntask, tbase, (size_t)nnz + 1, st));
     if (nnz)
         hipLaunchKernelGGL(same::wl_expand, dim3(grid_for((size_t)nnz)), dim3(256), 0, st, M.nz_doc, M.rowidx, M.val,
                            tbase, nnz, (uint32_t)G, M.t_doc, M.t_word, M.t_g, M.order, M.cost);
@@ -357,31 +374,41 @@ int build_matrix(same_lda* h, const same_lda_csc* X, int32_t V, int32_t K, int32
                        kTileDocs, M.n_tiles, M.tile_start);
     HIP_TRY(h, hipGetLastError());
 
-    // Pair list: slots in (word, task id) order for the tasks of frequent words.  Optional: without
-    // it the draw kernel updates the word rows directly.
+    // Pair list: slots in (word, task id) order for the tasks of frequent words: a stable radix sort of the tasks
+    // by word (worklist_kernels.h), the words' ranges in the sorted list, a flag per task of a word with enough
+    // tasks, the flags' exclusive sum.  Optional: without it the draw kernel updates the word rows directly.
     if (with_pairs && n > 0) {
         int bits = 1;
         while (((int64_t)1 << bits) < (int64_t)V) ++bits;
-        int32_t *iota = nullptr, *keys = nullptr, *tasks = nullptr, *wstart = nullptr;
-        uint32_t *flag = nullptr, *pos = nullptr;
-        void *sort_tmp = nullptr, *scan2_tmp = nullptr;
-        const size_t sort_bytes = same::wl_sort_pairs_bytes(n, bits);
-        const size_t scan2_bytes = same::wl_exclusive_sum_bytes(n + 1);
-        bool ok = tmp.get(&iota, n) == hipSuccess && tmp.get(&keys, n) == hipSuccess && tmp.get(&tasks, n) == hipSuccess &&
+        const uint32_t tiles = (uint32_t)((n + same::kSortTile - 1) / same::kSortTile);
+        const size_t cells = (size_t)same::kSortDigits * tiles;
+        int32_t *kbuf[2] = {nullptr, nullptr}, *vbuf[2] = {nullptr, nullptr}, *wstart = nullptr;
+        uint32_t *hist = nullptr, *hstart = nullptr, *flag = nullptr, *pos = nullptr;
+        bool ok = tmp.get(&kbuf[0], n) == hipSuccess && tmp.get(&kbuf[1], n) == hipSuccess &&
+                  tmp.get(&vbuf[0], n) == hipSuccess && tmp.get(&vbuf[1], n) == hipSuccess &&
+                  tmp.get(&hist, cells) == hipSuccess && tmp.get(&hstart, cells) == hipSuccess &&
                   tmp.get(&wstart, (size_t)V + 1) == hipSuccess && tmp.get(&flag, n + 1) == hipSuccess &&
                   tmp.get(&pos, n + 1) == hipSuccess &&
-                  tmp.get(reinterpret_cast<char**>(&sort_tmp), sort_bytes) == hipSuccess &&
-                  tmp.get(reinterpret_cast<char**>(&scan2_tmp), scan2_bytes) == hipSuccess &&
                   h->cache.get(reinterpret_cast<void**>(&M.t_slot), n * 4) == hipSuccess &&
                   h->cache.get(reinterpret_cast<void**>(&M.slot_word), n * 4) == hipSuccess;
         if (ok) {
-            hipLaunchKernelGGL(same::wl_iota, dim3(grid_for(n)), dim3(256), 0, st, iota, (int64_t)n);
-            HIP_TRY(h, same::wl_sort_pairs(sort_tmp, sort_bytes, M.t_word, keys, iota, tasks, n, bits, st));
+            const int32_t* kin = M.t_word;                         // the first pass reads the tasks' words and numbers them itself
+            const int32_t* vin = nullptr;
+            int to = 0;
+            for (int shift = 0; shift < bits; shift += 8, to ^= 1) {
+                hipLaunchKernelGGL(same::wl_sort_histogram, dim3(tiles), dim3(same::kSortThreads), 0, st, kin, (int64_t)n, shift, tiles, hist);
+                HIP_TRY(h, exclusive_sum(tmp, hist, hstart, cells, st));
+                hipLaunchKernelGGL(same::wl_sort_scatter, dim3(tiles), dim3(same::kSortThreads), 0, st, kin, vin, (int64_t)n, shift, tiles,
+                                   hstart, kbuf[to], vbuf[to]);
+                kin = kbuf[to]; vin = vbuf[to];
+            }
+            const int32_t* keys = kin;                             // words in ascending order, tasks of a word in task order
+            const int32_t* tasks = vin;
             hipLaunchKernelGGL(same::wl_word_starts, dim3((unsigned)((V + 256) / 256)), dim3(256), 0, st, keys,
                                (int32_t)n, V, wstart);
             hipLaunchKernelGGL(same::wl_slot_flags, dim3(grid_for(n + 1)), dim3(256), 0, st, keys, wstart, (int64_t)n,
                                (int32_t)same::kSlotMinTasks, flag);
-            HIP_TRY(h, same::wl_exclusive_sum(scan2_tmp, scan2_bytes, flag, pos, n + 1, st));
+            HIP_TRY(h, exclusive_sum(tmp, flag, pos, n + 1, st));
             hipLaunchKernelGGL(same::wl_slot_scatter, dim3(grid_for(n)), dim3(256), 0, st, keys, tasks, flag, pos,
                                (int64_t)n, M.t_slot, M.slot_word, d_stats);
             HIP_TRY(h, hipGetLastError());

@@ -4,8 +4,7 @@
 // groups ("tasks") of at most G.  These kernels validate the matrix and produce, without a host
 // copy of the matrix: the document of every nonzero, the tasks (document, word, group size) in
 // storage order, the first task of every tile of documents, and the slots of the word-ordered pair
-// list.  The two library primitives they need (an exclusive sum and a stable radix sort) are wrapped
-// in worklist.hip.
+// list.  The exclusive sums and the stable sort by word that this takes are kernels of this file too.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -209,10 +208,140 @@ __global__ void wl_tiles(const int32_t* __restrict__ colptr, const uint32_t* __r
     tile_start[T] = (int32_t)tbase[colptr[d < D ? d : D]];
 }
 
-__global__ void wl_iota(int32_t* __restrict__ a, int64_t n)
+// ---- Exclusive sum of 32-bit counts.  A workgroup owns a tile of kScanTile consecutive items.  One launch adds up
+// every tile, the tile totals are summed the same way (recursively, until one tile is left), and a last launch
+// per level writes the items' exclusive sums from the tile's base.  All sums are modulo 2^32 (the callers' totals
+// stay below 2^31).
+constexpr int kScanThreads = 256;
+constexpr int kScanItems = 8;                                     // consecutive items per thread
+constexpr int kScanTile = kScanThreads * kScanItems;
+
+// sum over the workgroup; every thread receives it
+__device__ __forceinline__ uint32_t wl_block_sum(uint32_t v, uint32_t* sh /* [kScanThreads / 64] */)
 {
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) a[i] = (int32_t)i;
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+    __syncthreads();
+    uint32_t t = 0;
+    for (int i = 0; i < kScanThreads / 64; ++i) t += sh[i];
+    __syncthreads();
+    return t;
+}
+
+__global__ __launch_bounds__(kScanThreads) void wl_tile_sums(const uint32_t* __restrict__ in, size_t n, uint32_t* __restrict__ tile_sum)
+{
+    __shared__ uint32_t sh[kScanThreads / 64];
+    const size_t first = (size_t)blockIdx.x * kScanTile + (size_t)threadIdx.x * kScanItems;
+    uint32_t v = 0;
+#pragma unroll
+    for (int j = 0; j < kScanItems; ++j) if (first + j < n) v += in[first + j];
+    const uint32_t t = wl_block_sum(v, sh);
+    if (threadIdx.x == 0) tile_sum[blockIdx.x] = t;
+}
+
+// out[i] = tile_base[tile of i] + sum of the items of the tile before i (tile_base null: zero, a single tile)
+__global__ __launch_bounds__(kScanThreads) void wl_tile_scan(const uint32_t* __restrict__ in, size_t n, const uint32_t* __restrict__ tile_base,
+                                                            uint32_t* __restrict__ out)
+{
+    __shared__ uint32_t wave_total[kScanThreads / 64];
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const size_t first = (size_t)blockIdx.x * kScanTile + (size_t)threadIdx.x * kScanItems;
+    uint32_t x[kScanItems];
+    uint32_t mine = 0;
+#pragma unroll
+    for (int j = 0; j < kScanItems; ++j) { x[j] = first + j < n ? in[first + j] : 0u; mine += x[j]; }
+    uint32_t incl = mine;                                          // inclusive sum over the wave's lanes
+    for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t up = __shfl_up(incl, o);
+        if (lane >= o) incl += up;
+    }
+    if (lane == 63) wave_total[wv] = incl;
+    __syncthreads();
+    uint32_t base = tile_base ? tile_base[blockIdx.x] : 0u;
+    for (int i = 0; i < wv; ++i) base += wave_total[i];
+    uint32_t run = base + incl - mine;
+#pragma unroll
+    for (int j = 0; j < kScanItems; ++j) {
+        if (first + j < n) out[first + j] = run;
+        run += x[j];
+    }
+}
+
+// ---- Stable radix sort of (key, value) pairs by 8-bit digits, least significant first.  A workgroup owns a tile of
+// kSortTile consecutive items, wave v of it the items [v * 1024, (v + 1) * 1024) of the tile, read 64 at a time (a row).
+// Per pass: wl_sort_histogram counts the tile's items per digit into hist[digit][tile]; the exclusive sum of hist
+// in that order is where each tile's run of each digit starts in the output; wl_sort_scatter places the items: a
+// lane's position is the start of its (digit, tile) run, plus the items of the same digit in the waves before its
+// own, in the earlier rows of its wave, and in the lower lanes of its row.  Items keep their order inside a digit:
+// the sort is stable, and the passes from the lowest digit up sort by the whole key.
+constexpr int kSortThreads = 256;
+constexpr int kSortRows = 16;                                     // rows of 64 items per wave
+constexpr int kSortTile = kSortThreads * kSortRows;               // 4096 items
+constexpr int kSortDigits = 256;
+static_assert(kSortThreads == kSortDigits, "thread d of a workgroup owns digit d");
+
+__global__ __launch_bounds__(kSortThreads) void wl_sort_histogram(const int32_t* __restrict__ keys, int64_t n, int shift, uint32_t n_tiles,
+                                                                 uint32_t* __restrict__ hist)
+{
+    __shared__ uint32_t h[kSortDigits];
+    h[threadIdx.x] = 0u;
+    __syncthreads();
+    const int64_t first = (int64_t)blockIdx.x * kSortTile;
+    for (int j = 0; j < kSortRows; ++j) {
+        const int64_t i = first + (int64_t)j * kSortThreads + threadIdx.x;
+        if (i < n) atomicAdd(&h[((uint32_t)keys[i] >> shift) & (kSortDigits - 1)], 1u);
+    }
+    __syncthreads();
+    hist[(size_t)threadIdx.x * n_tiles + blockIdx.x] = h[threadIdx.x];
+}
+
+// vals_in null: the value of item i is i (the first pass sorts the identity)
+__global__ __launch_bounds__(kSortThreads) void wl_sort_scatter(const int32_t* __restrict__ keys_in, const int32_t* __restrict__ vals_in,
+                                                                int64_t n, int shift, uint32_t n_tiles, const uint32_t* __restrict__ start,
+                                                                int32_t* __restrict__ keys_out, int32_t* __restrict__ vals_out)
+{
+    __shared__ uint32_t cnt[kSortThreads / 64][kSortDigits];      // per wave and digit: items, then the next output position
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    for (int v = 0; v < kSortThreads / 64; ++v) cnt[v][threadIdx.x] = 0u;
+    __syncthreads();
+    const int64_t first = (int64_t)blockIdx.x * kSortTile + (int64_t)wv * (kSortRows * 64) + lane;
+    int32_t key[kSortRows], val[kSortRows];
+#pragma unroll
+    for (int j = 0; j < kSortRows; ++j) {
+        const int64_t i = first + (int64_t)j * 64;
+        const bool in = i < n;
+        key[j] = in ? keys_in[i] : 0;
+        val[j] = in ? (vals_in ? vals_in[i] : (int32_t)i) : 0;
+        if (in) atomicAdd(&cnt[wv][((uint32_t)key[j] >> shift) & (kSortDigits - 1)], 1u);
+    }
+    __syncthreads();
+    {   // thread d: where the waves' items of digit d start
+        uint32_t pos = start[(size_t)threadIdx.x * n_tiles + blockIdx.x];
+        for (int v = 0; v < kSortThreads / 64; ++v) { const uint32_t c = cnt[v][threadIdx.x]; cnt[v][threadIdx.x] = pos; pos += c; }
+    }
+    __syncthreads();
+    const uint64_t below = (1ull << lane) - 1ull;
+#pragma unroll
+    for (int j = 0; j < kSortRows; ++j) {
+        const bool in = first + (int64_t)j * 64 < n;
+        const uint32_t dgt = ((uint32_t)key[j] >> shift) & (kSortDigits - 1);
+        uint64_t peers = __ballot(in);                             // the lanes of this row that hold the same digit
+#pragma unroll
+        for (int bit = 0; bit < 8; ++bit) {
+            const bool one = (dgt >> bit) & 1u;
+            const uint64_t m = __ballot(one);
+            peers &= one ? m : ~m;
+        }
+        if (in) {
+            const uint32_t rank = (uint32_t)__popcll((unsigned long long)(peers & below));
+            const uint32_t pos = cnt[wv][dgt] + rank;              // every peer reads the position before the first one moves it on
+            if (rank == 0u) cnt[wv][dgt] = pos + (uint32_t)__popcll((unsigned long long)peers);
+            if ((int64_t)pos < n) {                                // always true; keeps a wrong count from becoming a wild store
+                keys_out[pos] = key[j];
+                vals_out[pos] = val[j];
+            }
+        }
+    }
 }
 
 // wstart[w] = first position of word w in the word-sorted task list (n for words beyond the last), V + 1 entries.
@@ -249,12 +378,5 @@ __global__ void wl_slot_scatter(const int32_t* __restrict__ keys, const int32_t*
     }
     if (blockIdx.x == 0 && threadIdx.x == 0) s->n_slots = pos[n];
 }
-
-// Library primitives (worklist.hip): temporary storage is taken from the caller's arena.
-size_t wl_exclusive_sum_bytes(size_t n);
-hipError_t wl_exclusive_sum(void* tmp, size_t tmp_bytes, const uint32_t* in, uint32_t* out, size_t n, hipStream_t st);
-size_t wl_sort_pairs_bytes(size_t n, int end_bit);
-hipError_t wl_sort_pairs(void* tmp, size_t tmp_bytes, const int32_t* keys_in, int32_t* keys_out,
-                         const int32_t* vals_in, int32_t* vals_out, size_t n, int end_bit, hipStream_t st);
 
 }  // namespace same
