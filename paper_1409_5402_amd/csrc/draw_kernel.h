@@ -71,7 +71,8 @@ constexpr int kWalkRounds = SAME_WALK_ROUNDS;   // rounds of kWalkSteps pmf term
 // VEC: K is a multiple of 4 (16-byte loads), else element-wise loads (TB = 0).  TB: 16-byte loads per matrix that
 // a lane has in flight at a time: a block of T = 4 ceil(K / 128) topics is read in T / (4 TB) batches of TB loads
 // per matrix, TB the largest of 1, 2, 4 that divides T / 4 (one batch of one up to K = 128, one of two up to 256,
-// one of four from 385 to 512, two of four from 897 to 1024).  ONE: a block is a single batch.
+// one of four from 385 to 512, two of four from 897 to 1024).  ONE: a block is a single batch.  KC = 256: the
+// same kernel with the number of topics a constant (row addresses become shifts, the bounds of the loads vanish).
 //
 // The launch positions are handed out in segments of kSegment consecutive positions through a counter in
 // device memory (a.counter, zero at launch): a workgroup (one wave) takes a segment, its lanes take the
@@ -85,7 +86,7 @@ constexpr int kWalkRounds = SAME_WALK_ROUNDS;   // rounds of kWalkSteps pmf term
 #endif
 constexpr int kSegment = SAME_SEGMENT;
 
-template <bool UNIFORM, bool VEC, bool DEBUG, int TB, bool ONE>
+template <bool UNIFORM, bool VEC, bool DEBUG, int TB, bool ONE, int KC = 0>
 __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(TB <= 2 ? 4 : 3))) void draw_kernel(DrawArgs a)
 {
     extern __shared__ uint32_t lds[];
@@ -93,7 +94,7 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(TB <= 2 ?
     uint32_t* acc = lds + kMaxBlocks;                              // piece totals by owner lane: lane l's is acc[l * kSumStride],
                                                                    // the word of its row of sums that pads the stride
     const int lane = threadIdx.x;
-    const int K = a.K;
+    const int K = KC > 0 ? KC : a.K;                              // KC: the number of topics where it is known at compile time
     const int T = (TB > 0 && ONE) ? 4 * TB : block_len(K);         // topics per block
     const int nb = (TB > 0 && !ONE) ? T / (4 * TB) : 1;            // batches of loads per block
     const int nblk = (K + T - 1) / T;                              // blocks in use (<= 32)

@@ -523,6 +523,8 @@ int launch_draw(same_lda* h, const same::DrawArgs& a, bool uniform, bool poisson
         if (uniform)             hipLaunchKernelGGL((same::draw_kernel<true, false, DEBUG, 0, true>), grid, block, lds, st, a);
         else if (!vec)           hipLaunchKernelGGL((same::draw_kernel<false, false, DEBUG, 0, true>), grid, block, lds, st, a);
         else if (tb == 1 && one) hipLaunchKernelGGL((same::draw_kernel<false, true, DEBUG, 1, true>), grid, block, lds, st, a);
+        else if (a.K == 256)     hipLaunchKernelGGL((same::draw_kernel<false, true, DEBUG, 2, true, 256>), grid, block, lds, st, a);
+        else if (a.K == 1024)    hipLaunchKernelGGL((same::draw_kernel<false, true, DEBUG, 4, false, 1024>), grid, block, lds, st, a);
         else if (tb == 2 && one) hipLaunchKernelGGL((same::draw_kernel<false, true, DEBUG, 2, true>), grid, block, lds, st, a);
         else if (tb == 4 && one) hipLaunchKernelGGL((same::draw_kernel<false, true, DEBUG, 4, true>), grid, block, lds, st, a);
         else if (tb == 1)        hipLaunchKernelGGL((same::draw_kernel<false, true, DEBUG, 1, false>), grid, block, lds, st, a);
