@@ -87,12 +87,12 @@ struct ZeroTest {
     }
 };
 
-template <bool VEC, bool DEBUG>
+template <bool VEC, bool DEBUG, int KC = 0>   // KC: the number of topics where it is known at compile time
 __global__ __launch_bounds__(kWave) void poisson_draw_kernel(DrawArgs a)
 {
     extern __shared__ uint32_t lds[];
     const int lane = threadIdx.x;
-    const int K = a.K;
+    const int K = KC > 0 ? KC : a.K;
     const int nblk = (K + kBlk - 1) / kBlk;
     constexpr int qw = 3;                                          // words per queue entry
     uint32_t* que = lds;                                           // [kQCap][qw][64], a ring per lane

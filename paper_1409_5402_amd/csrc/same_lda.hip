@@ -507,7 +507,8 @@ int launch_draw(same_lda* h, const same::DrawArgs& a, bool uniform, bool poisson
         if (blocks >= (int64_t)1 << 31) return fail(h, SAME_LDA_EINVAL, "too many draw tasks for one launch");
         dim3 grid((unsigned)blocks);
         const size_t lds = same::poisson_lds_bytes();
-        if (a.K % same::kBlk == 0) hipLaunchKernelGGL((same::poisson_draw_kernel<true, DEBUG>), grid, block, lds, st, a);
+        if (a.K == 256)            hipLaunchKernelGGL((same::poisson_draw_kernel<true, DEBUG, 256>), grid, block, lds, st, a);
+        else if (a.K % same::kBlk == 0) hipLaunchKernelGGL((same::poisson_draw_kernel<true, DEBUG>), grid, block, lds, st, a);
         else                       hipLaunchKernelGGL((same::poisson_draw_kernel<false, DEBUG>), grid, block, lds, st, a);
     } else {
         // Workgroups take segments of launch positions from a counter until none is left: as many workgroups as
