@@ -227,13 +227,15 @@ int same_lda_vb_estep(same_lda_t* h, const float* b, const float* shift, float a
 int same_lda_set_timing(same_lda_t* h, int32_t enabled);
 int same_lda_get_timing(same_lda_t* h, double* draw_ms_total, int64_t* launches);
 
-/* Device self-test of the two building blocks whose exactness the draw relies on (no handle
+/* Device self-test of building blocks that the parity tests exercise only indirectly (no handle
  * needed; runs on the current device's default stream and synchronises):
  *   - the Philox4x32-10 block function against the three published known-answer vectors
  *     (Salmon et al., SC'11);
  *   - the integer reciprocal used in the pmf walk against the correctly rounded 1/x for EVERY
- *     integer x in [1, 2^24).
- * *failures (host) receives the number of mismatches; 0 means both hold.                        */
+ *     integer x in [1, 2^24);
+ *   - the exclusive sum and the stable radix sort that build the work list, on a seeded million
+ *     items, against the host's sum and the (key, position) order.
+ * *failures (host) receives the number of mismatches; 0 means all hold.                         */
 int same_lda_selftest(int64_t* failures);
 
 /* Wait for everything enqueued on the handle's stream. */

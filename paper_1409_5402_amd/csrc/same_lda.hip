@@ -1147,6 +1147,74 @@ int same_lda_get_timing(same_lda_t* h, double* draw_ms_total, int64_t* launches)
     return SAME_LDA_OK;
 }
 
+namespace {
+// The work list's exclusive sum and stable radix sort on a seeded array of a million items over several tiles with a
+// ragged end: sums against the host's, the sorted pairs must be the input's pairs in (key, position) order.
+int selftest_sort_and_sum(int64_t* bad)
+{
+    const size_t n = 1000003;
+    const int32_t V = 70001;                                       // 17 bits: three passes
+    std::vector<int32_t> keys(n);
+    std::vector<uint32_t> cnt(n);
+    uint32_t x = 12345u;
+    for (size_t i = 0; i < n; ++i) { x = x * 1664525u + 1013904223u; keys[i] = (int32_t)((x >> 8) % (uint32_t)V); cnt[i] = (x >> 28); }
+    same_lda* h = new (std::nothrow) same_lda();
+    if (!h) return fail(nullptr, SAME_LDA_ENOMEM, "host allocation failed");
+    int rc = SAME_LDA_OK;
+    int64_t wrong = 0;
+    {
+        Temps tmp(h, nullptr);
+        const uint32_t tiles = (uint32_t)((n + same::kSortTile - 1) / same::kSortTile);
+        const size_t cells = (size_t)same::kSortDigits * tiles;
+        int32_t *kin = nullptr, *kb[2] = {nullptr, nullptr}, *vb[2] = {nullptr, nullptr};
+        uint32_t *hist = nullptr, *hstart = nullptr, *cin = nullptr, *cout = nullptr;
+        hipError_t e = tmp.get(&kin, n);
+        if (e == hipSuccess) e = tmp.get(&kb[0], n);
+        if (e == hipSuccess) e = tmp.get(&kb[1], n);
+        if (e == hipSuccess) e = tmp.get(&vb[0], n);
+        if (e == hipSuccess) e = tmp.get(&vb[1], n);
+        if (e == hipSuccess) e = tmp.get(&hist, cells);
+        if (e == hipSuccess) e = tmp.get(&hstart, cells);
+        if (e == hipSuccess) e = tmp.get(&cin, n);
+        if (e == hipSuccess) e = tmp.get(&cout, n);
+        if (e == hipSuccess) e = hipMemcpy(kin, keys.data(), n * 4, hipMemcpyHostToDevice);
+        if (e == hipSuccess) e = hipMemcpy(cin, cnt.data(), n * 4, hipMemcpyHostToDevice);
+        const int32_t* k = kin;
+        const int32_t* v = nullptr;
+        int to = 0;
+        for (int shift = 0; e == hipSuccess && shift < 17; shift += 8, to ^= 1) {
+            hipLaunchKernelGGL(same::wl_sort_histogram, dim3(tiles), dim3(same::kSortThreads), 0, nullptr, k, (int64_t)n, shift, tiles, hist);
+            e = exclusive_sum(tmp, hist, hstart, cells, nullptr);
+            if (e != hipSuccess) break;
+            hipLaunchKernelGGL(same::wl_sort_scatter, dim3(tiles), dim3(same::kSortThreads), 0, nullptr, k, v, (int64_t)n, shift, tiles, hstart,
+                               kb[to], vb[to]);
+            k = kb[to]; v = vb[to];
+        }
+        if (e == hipSuccess) e = exclusive_sum(tmp, cin, cout, n, nullptr);
+        std::vector<int32_t> ks(n), vs(n);
+        std::vector<uint32_t> sums(n);
+        if (e == hipSuccess) e = hipMemcpy(ks.data(), k, n * 4, hipMemcpyDeviceToHost);
+        if (e == hipSuccess) e = hipMemcpy(vs.data(), v, n * 4, hipMemcpyDeviceToHost);
+        if (e == hipSuccess) e = hipMemcpy(sums.data(), cout, n * 4, hipMemcpyDeviceToHost);
+        if (e != hipSuccess) rc = fail(nullptr, SAME_LDA_EHIP, "selftest: %s", hipGetErrorString(e));
+        else {
+            uint32_t run = 0;
+            for (size_t i = 0; i < n; ++i) {
+                if (sums[i] != run) ++wrong;
+                run += cnt[i];
+                const int32_t src = vs[i];
+                if (src < 0 || (size_t)src >= n || keys[(size_t)src] != ks[i]) { ++wrong; continue; }
+                if (i > 0 && (ks[i] < ks[i - 1] || (ks[i] == ks[i - 1] && vs[i] <= vs[i - 1]))) ++wrong;   // a permutation follows
+            }
+        }
+    }
+    h->cache.clear_spare();
+    delete h;
+    *bad = wrong;
+    return rc;
+}
+}  // namespace
+
 int same_lda_selftest(int64_t* failures)
 {
     if (!failures) return fail(nullptr, SAME_LDA_EINVAL, "failures is null");
@@ -1161,7 +1229,10 @@ int same_lda_selftest(int64_t* failures)
     if (e == hipSuccess) e = hipMemcpy(&got, d, sizeof got, hipMemcpyDeviceToHost);
     hipFree(d);
     if (e != hipSuccess) return fail(nullptr, SAME_LDA_EHIP, "selftest: %s", hipGetErrorString(e));
-    *failures = (int64_t)got;
+    int64_t bad = 0;
+    const int rc = selftest_sort_and_sum(&bad);
+    if (rc) return rc;
+    *failures = (int64_t)got + bad;
     return SAME_LDA_OK;
 }
 
