@@ -8,7 +8,8 @@
 // its task's topics, T = 4*ceil(K/128) consecutive topics (T = 8 at K = 256: the 32 lanes read the
 // task's phi row and its document's theta row as two 16-byte loads each), multiplies them
 // (w_k = theta[d][k] * phi[w][k]) and adds the block's weights left to right.  The 32 block sums of a
-// task go to LDS.  No random numbers are used here and nothing is kept per topic.
+// task go to LDS.  No random numbers are used here and nothing is kept per topic.  (For K = 512 and 1024 the
+// lanes of a half read consecutive 16-byte pieces instead and share the blocks' sums: see COAL below.)
 //
 // Draw (one lane per task).  A lane first turns its task's block sums into running sums S_0..S_31 (left to
 // right, so S_l is the cumulative weight at the end of block l and S_31 = mu, the normaliser of
@@ -47,6 +48,12 @@ __host__ __device__ inline int block_len(int K) { return 4 * ((K + 127) / 128); 
 // fifteen waves a compute unit holds, which costs more.
 __host__ __device__ inline int doc_rows(int K) { return K <= 128 ? 2 : (K <= 1024 ? 1 : 0); }
 
+// The value of v in the next lower lane (lanes 0, 16, 32, 48 receive 0): a row shift inside the vector ALU.
+__device__ __forceinline__ float from_lane_below(float v)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x111, 0xf, 0xf, true));
+}
+
 // Position of the highest of R copies uniform on (0, U).
 __device__ __forceinline__ float top_position(float U, uint32_t R, float u)
 {
@@ -71,8 +78,14 @@ constexpr int kWalkRounds = SAME_WALK_ROUNDS;   // rounds of kWalkSteps pmf term
 // VEC: K is a multiple of 4 (16-byte loads), else element-wise loads (TB = 0).  TB: 16-byte loads per matrix that
 // a lane has in flight at a time: a block of T = 4 ceil(K / 128) topics is read in T / (4 TB) batches of TB loads
 // per matrix, TB the largest of 1, 2, 4 that divides T / 4 (one batch of one up to K = 128, one of two up to 256,
-// one of four from 385 to 512, two of four from 897 to 1024).  ONE: a block is a single batch.  KC = 256: the
+// one of four from 385 to 512, two of four from 897 to 1024).  ONE: a block is a single batch.  KC > 0: the
 // same kernel with the number of topics a constant (row addresses become shifts, the bounds of the loads vanish).
+// COAL (KC = 128 n, n = 2, 4 or 8): in the scan a load covers 128 consecutive topics per half-wave, four per lane,
+// instead of four topics of every lane's own block: a wave's load touches 8 cache lines, not 64 (blocks of 32
+// topics are a whole line each, and the cache serves a load one line at a time: with 64 lines per load the kernel
+// at K = 1024 was bound there, at half the speed).  The n lanes that hold a block then add its products in the
+// same left-to-right order through a chain of lane-to-lane shifts; the block sums are the same bits.  The steps'
+// reloads of single blocks stay as they are (a lane's block belongs to its own task).
 //
 // The launch positions are handed out in segments of kSegment consecutive positions through a counter in
 // device memory (a.counter, zero at launch): a workgroup (one wave) takes a segment, its lanes take the
@@ -86,7 +99,7 @@ constexpr int kWalkRounds = SAME_WALK_ROUNDS;   // rounds of kWalkSteps pmf term
 #endif
 constexpr int kSegment = SAME_SEGMENT;
 
-template <bool UNIFORM, bool VEC, bool DEBUG, int TB, bool ONE, int KC = 0>
+template <bool UNIFORM, bool VEC, bool DEBUG, int TB, bool ONE, int KC = 0, bool COAL = false>
 __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(TB <= 2 ? 4 : 3))) void draw_kernel(DrawArgs a)
 {
     extern __shared__ uint32_t lds[];
@@ -222,7 +235,8 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(TB <= 2 ?
                     // tasks are consecutive): only the phi row of the next task is loaded then
                     auto issue = [&](float4* pv, float4* tv, int32_t& held, const Item& it) {
                         const int32_t pd = __shfl(d, it.src), pw = __shfl(w, it.src);
-                        const int kb = k0 + 4 * TB * it.b;
+                        const int kb = COAL ? 128 * TB * it.b + 4 * hl : k0 + 4 * TB * it.b;
+                        constexpr int kStep = COAL ? 128 : 4;      // topics between two loads of a lane
                         const float* __restrict__ tp = a.theta + (size_t)pd * K + kb;
                         const float* __restrict__ pp = a.phi + (size_t)pw * K + kb;
                         const bool same = ONE && pd == held;
@@ -230,8 +244,8 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(TB <= 2 ?
 #pragma unroll
                         for (int c = 0; c < TB; ++c) {
                             if (WHOLE || kb + 4 * c < K) {
-                                pv[c] = *reinterpret_cast<const float4*>(pp + 4 * c);
-                                if (!same) tv[c] = *reinterpret_cast<const float4*>(tp + 4 * c);
+                                pv[c] = *reinterpret_cast<const float4*>(pp + kStep * c);
+                                if (!same) tv[c] = *reinterpret_cast<const float4*>(tp + kStep * c);
                             } else {
                                 pv[c] = make_float4(0.f, 0.f, 0.f, 0.f);
                                 tv[c] = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -240,6 +254,31 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(TB <= 2 ?
                     };
                     float rs = 0.0f;
                     auto consume = [&](const float4* pv, const float4* tv, const Item& it) {
+                        if constexpr (COAL) {
+                            // A load covers 128 consecutive topics of the task, four per lane: the kNL lanes that hold a block
+                            // add its products left to right, the running sum handed from lane to lane.  Every lane
+                            // runs all kNL stages; stage j is meaningful in the block's lane j, and the block's last lane
+                            // ends with the same sum, rounded in the same order, as one lane that adds the block alone.
+                            constexpr int kNL = KC / 128;
+                            static_assert(!COAL || (KC >= 256 && KC % 128 == 0 && 16 % (KC / 128) == 0), "blocks must not straddle loads");
+#pragma unroll
+                            for (int c = 0; c < TB; ++c) {
+                                const float x0 = tv[c].x * pv[c].x, x1 = tv[c].y * pv[c].y;
+                                const float x2 = tv[c].z * pv[c].z, x3 = tv[c].w * pv[c].w;
+                                float s = 0.0f;
+#pragma unroll
+                                for (int j = 0; j < kNL; ++j) {
+                                    const float in = j == 0 ? 0.0f : from_lane_below(s);
+                                    s = in + x0;
+                                    s = s + x1;
+                                    s = s + x2;
+                                    s = s + x3;
+                                }
+                                if ((hl & (kNL - 1)) == kNL - 1)
+                                    sums[it.src * kSumStride + (TB * it.b + c) * (32 / kNL) + hl / kNL] = s;
+                            }
+                            return;
+                        }
 #pragma unroll
                         for (int c = 0; c < TB; ++c) {
                             rs = rs + tv[c].x * pv[c].x;

@@ -516,6 +516,8 @@ int launch_draw(same_lda* h, const same::DrawArgs& a, bool uniform, bool poisson
         const int64_t segments = (a.n + same::kSegment - 1) / same::kSegment;
         dim3 grid((unsigned)(segments < kDrawGrid ? segments : kDrawGrid));
         // blocks of 4 * ceil(K / 128) topics, read in batches of one, two or four 16-byte loads per matrix
+        // (K = 512 and K = 1024: the scan reads a row 512 contiguous bytes per half-wave and load; at K = 256, where the
+        // kernel is bound by vector-ALU issue, the extra additions of that form cost more than the fewer cache lines save)
         const size_t lds = same::draw_lds_bytes(a.K);
         const bool vec = a.K % 4 == 0;
         const int quads = same::block_len(a.K) / 4;                // 16-byte loads per block and matrix
@@ -525,7 +527,8 @@ int launch_draw(same_lda* h, const same::DrawArgs& a, bool uniform, bool poisson
         else if (!vec)           hipLaunchKernelGGL((same::draw_kernel<false, false, DEBUG, 0, true>), grid, block, lds, st, a);
         else if (tb == 1 && one) hipLaunchKernelGGL((same::draw_kernel<false, true, DEBUG, 1, true>), grid, block, lds, st, a);
         else if (a.K == 256)     hipLaunchKernelGGL((same::draw_kernel<false, true, DEBUG, 2, true, 256>), grid, block, lds, st, a);
-        else if (a.K == 1024)    hipLaunchKernelGGL((same::draw_kernel<false, true, DEBUG, 4, false, 1024>), grid, block, lds, st, a);
+        else if (a.K == 1024)    hipLaunchKernelGGL((same::draw_kernel<false, true, DEBUG, 4, false, 1024, true>), grid, block, lds, st, a);
+        else if (a.K == 512)     hipLaunchKernelGGL((same::draw_kernel<false, true, DEBUG, 4, true, 512, true>), grid, block, lds, st, a);
         else if (tb == 2 && one) hipLaunchKernelGGL((same::draw_kernel<false, true, DEBUG, 2, true>), grid, block, lds, st, a);
         else if (tb == 4 && one) hipLaunchKernelGGL((same::draw_kernel<false, true, DEBUG, 4, true>), grid, block, lds, st, a);
         else if (tb == 1)        hipLaunchKernelGGL((same::draw_kernel<false, true, DEBUG, 1, false>), grid, block, lds, st, a);
