@@ -142,8 +142,21 @@ __global__ __launch_bounds__(256) void loglik_kernel(int64_t nnz, const int32_t*
         const int d = nz_doc[i];
         const float* th = theta + (size_t)d * K;
         const float* ph = phi + (size_t)rowidx[i] * K;
-        float S = th[0] * ph[0];
-        for (int k = 1; k < K; ++k) { const float wk = th[k] * ph[k]; S = S + wk; }
+        float S;
+        if ((K & 3) == 0) {                                        // 16-byte loads, the same order of additions (0 + x = x)
+            S = 0.0f;
+            for (int k = 0; k < K; k += 4) {
+                const float4 t = *reinterpret_cast<const float4*>(th + k);
+                const float4 p = *reinterpret_cast<const float4*>(ph + k);
+                S = S + t.x * p.x;
+                S = S + t.y * p.y;
+                S = S + t.z * p.z;
+                S = S + t.w * p.w;
+            }
+        } else {
+            S = th[0] * ph[0];
+            for (int k = 1; k < K; ++k) { const float wk = th[k] * ph[k]; S = S + wk; }
+        }
         v = (double)val[i] * (log((double)S) - doc_log_total[d]);
     }
     red[threadIdx.x] = v;
