@@ -66,6 +66,10 @@ __device__ __forceinline__ float top_position(float U, uint32_t R, float u)
     return y;
 }
 
+#ifndef SAME_SCAN_DEPTH
+#define SAME_SCAN_DEPTH 2
+#endif
+constexpr int kScanDepth = SAME_SCAN_DEPTH;     // pairs of tasks whose phi loads the scan has issued at a time
 #ifndef SAME_REFILL_MIN
 #define SAME_REFILL_MIN 24
 #endif
@@ -221,8 +225,9 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(TB <= 2 ?
                 return half ? lb : la;
             };
             if (VEC && TB > 0) {
-                // The loads of a batch are issued before the previous batch is summed, into two sets of registers
-                // used in turn.  Where every block is whole (K = 32 T: 256 at T = 8) the loads need no bounds.
+                // Where every block is whole (K = 32 T: 256 at T = 8) the loads need no bounds.  Blocks of one batch
+                // (ONE) go through the pipeline at the top of run(); blocks of several batches load the next batch
+                // into a second set of registers before the current one is summed.
                 struct Item { int src, b; bool last, valid; };
                 auto advance = [&](Item& it) {                     // the next (pair of tasks, batch) of this refill
                     if (it.valid && !it.last) { it.b += 1; it.last = it.b == nb - 1; return; }
@@ -231,21 +236,17 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(TB <= 2 ?
                 };
                 auto run = [&](auto whole) {
                     constexpr bool WHOLE = decltype(whole)::value;
-                    // a set of registers keeps the theta values it holds while the document stays the same (a document's
-                    // tasks are consecutive): only the phi row of the next task is loaded then
-                    auto issue = [&](float4* pv, float4* tv, int32_t& held, const Item& it) {
+                    auto issue = [&](float4* pv, float4* tv, const Item& it) {     // blocks of several batches
                         const int32_t pd = __shfl(d, it.src), pw = __shfl(w, it.src);
                         const int kb = COAL ? 128 * TB * it.b + 4 * hl : k0 + 4 * TB * it.b;
                         constexpr int kStep = COAL ? 128 : 4;      // topics between two loads of a lane
                         const float* __restrict__ tp = a.theta + (size_t)pd * K + kb;
                         const float* __restrict__ pp = a.phi + (size_t)pw * K + kb;
-                        const bool same = ONE && pd == held;
-                        held = pd;
 #pragma unroll
                         for (int c = 0; c < TB; ++c) {
                             if (WHOLE || kb + 4 * c < K) {
                                 pv[c] = *reinterpret_cast<const float4*>(pp + kStep * c);
-                                if (!same) tv[c] = *reinterpret_cast<const float4*>(tp + kStep * c);
+                                tv[c] = *reinterpret_cast<const float4*>(tp + kStep * c);
                             } else {
                                 pv[c] = make_float4(0.f, 0.f, 0.f, 0.f);
                                 tv[c] = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -288,20 +289,103 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(TB <= 2 ?
                         }
                         if (it.last) { sums[it.src * kSumStride + hl] = rs; rs = 0.0f; }
                     };
+                    if constexpr (ONE) {
+                        // A block is one batch.  The pairs of a refill are worked off in runs whose documents stay the
+                        // same (a document's tasks are consecutive): the run's theta values are loaded once, into one
+                        // set of registers, and the phi loads of kScanDepth - 1 pairs are in flight while a pair is
+                        // summed.  The loop is laid out so that the number of loads issued after those a sum waits
+                        // for is the same on every path that reaches it: the wait then lets the younger loads fly.
+                        constexpr int N = kScanDepth;
+                        constexpr int kStep = COAL ? 128 : 4;      // topics between two loads of a lane
+                        const int kb = COAL ? 4 * hl : k0;
+                        float4 pv[N][TB > 0 ? TB : 1], tv[TB > 0 ? TB : 1];
+                        int srcs[N];
+                        int32_t held = -1;                         // the document whose theta values tv holds
+                        // The next run: the leading new lanes whose document is that of the first one, taken in pairs
+                        // (one lane per half-wave; a last lane alone is its own partner).  Its pairs are inside one
+                        // document, so every lane needs the same piece of one theta row for all of them.
+                        auto lane_of = [&](uint64_t m) { return __ffsll((unsigned long long)m) - 1; };
+                        auto of_lane = [&](int32_t v, int l0, int l1) {    // v of lane l0 (first half-wave) or l1 (second)
+                            const int32_t va = __builtin_amdgcn_readlane(v, l0), vb = __builtin_amdgcn_readlane(v, l1);
+                            return half ? vb : va;
+                        };
+                        auto issue_phi = [&](float4* p, int& src) {    // takes the next pair of the run
+                            const int l0 = lane_of(fresh);
+                            fresh &= fresh - 1;
+                            const int l1 = fresh ? lane_of(fresh) : l0;
+                            fresh &= fresh - 1;
+                            src = half ? l1 : l0;
+                            const float* __restrict__ pp = a.phi + (size_t)of_lane(w, l0, l1) * K + kb;
+#pragma unroll
+                            for (int c = 0; c < TB; ++c)
+                                p[c] = (WHOLE || kb + 4 * c < K) ? *reinterpret_cast<const float4*>(pp + kStep * c)
+                                                                  : make_float4(0.f, 0.f, 0.f, 0.f);
+                        };
+                        auto sum_pair = [&](const float4* p, int src) {
+                            Item it{src, 0, true, true};
+                            consume(p, tv, it);
+                        };
+                        while (fresh) {
+                            const int32_t doc = __builtin_amdgcn_readlane(d, lane_of(fresh));
+                            const uint64_t other = fresh & ~__ballot(d == doc);
+                            const uint64_t lead = other ? fresh & ((other & (~other + 1ull)) - 1ull) : fresh;
+                            const int lanes_in = (int)__popcll((unsigned long long)lead);
+                            // pairs inside the document; a lane left over pairs with the first lane of the next document
+                            // only when nothing else is left of this one: it is then scanned alone, as its own partner
+                            int P = lanes_in / 2;
+                            uint64_t rest = 0;                     // new lanes set aside while this run is scanned
+                            if (P == 0) { P = 1; rest = fresh & (fresh - 1); fresh &= ~rest; }
+                            else { rest = fresh & ~lead; if (lanes_in & 1) rest |= 1ull << (63 - __clzll((unsigned long long)lead)); fresh &= ~rest; }
+                            if (doc != held) {
+                                const float* __restrict__ tp = a.theta + (size_t)doc * K + kb;
+#pragma unroll
+                                for (int c = 0; c < TB; ++c)
+                                    tv[c] = (WHOLE || kb + 4 * c < K) ? *reinterpret_cast<const float4*>(tp + kStep * c)
+                                                                       : make_float4(0.f, 0.f, 0.f, 0.f);
+                                held = doc;
+                            }
+#pragma unroll
+                            for (int j = 0; j < N - 1; ++j) if (j < P) issue_phi(pv[j], srcs[j]);
+                            if (P < N - 1) {                       // a short run
+#pragma unroll
+                                for (int j = 0; j < N - 1; ++j) if (j < P) sum_pair(pv[j], srcs[j]);
+                            } else {
+                                int issued = N - 1;
+                                while (P - issued >= N) {          // whole rounds: every sum has the loads of N - 1 pairs behind it
+#pragma unroll
+                                    for (int j = 0; j < N; ++j) {
+                                        issue_phi(pv[(j + N - 1) % N], srcs[(j + N - 1) % N]);
+                                        __builtin_amdgcn_sched_barrier(0);     // the loads first, then the sum that waits
+                                        sum_pair(pv[j], srcs[j]);
+                                        __builtin_amdgcn_sched_barrier(0);
+                                    }
+                                    issued += N;
+                                }
+                                const int r = P - issued;          // 0 .. N - 1 pairs not yet issued
+#pragma unroll
+                                for (int t = 0; t < N - 1; ++t)
+                                    if (t < r) { issue_phi(pv[(t + N - 1) % N], srcs[(t + N - 1) % N]); sum_pair(pv[t], srcs[t]); }
+#pragma unroll
+                                for (int t = 0; t < 2 * N - 2; ++t)
+                                    if (t >= r && t < r + N - 1) sum_pair(pv[t % N], srcs[t % N]);
+                            }
+                            fresh = rest;
+                        }
+                        return;
+                    }
                     float4 pa[TB > 0 ? TB : 1], ta[TB > 0 ? TB : 1], pb[TB > 0 ? TB : 1], tb[TB > 0 ? TB : 1];
-                    int32_t da = -1, db = -1;                      // the documents whose theta values ta and tb hold
                     Item cur{0, 0, false, false};
                     advance(cur);
-                    if (cur.valid) issue(pa, ta, da, cur);
+                    if (cur.valid) issue(pa, ta, cur);
                     while (cur.valid) {
                         Item nxt = cur;
                         advance(nxt);
-                        if (nxt.valid) issue(pb, tb, db, nxt);
+                        if (nxt.valid) issue(pb, tb, nxt);
                         consume(pa, ta, cur);
                         if (!nxt.valid) break;
                         cur = nxt;
                         advance(cur);
-                        if (cur.valid) issue(pa, ta, da, cur);
+                        if (cur.valid) issue(pa, ta, cur);
                         consume(pb, tb, nxt);
                     }
                 };
