@@ -66,10 +66,6 @@ __device__ __forceinline__ float top_position(float U, uint32_t R, float u)
     return y;
 }
 
-#ifndef SAME_SCAN_DEPTH
-#define SAME_SCAN_DEPTH 2
-#endif
-constexpr int kScanDepth = SAME_SCAN_DEPTH;     // pairs of tasks whose phi loads the scan has issued at a time
 #ifndef SAME_REFILL_MIN
 #define SAME_REFILL_MIN 24
 #endif
@@ -289,89 +285,108 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(TB <= 2 ?
                         }
                         if (it.last) { sums[it.src * kSumStride + hl] = rs; rs = 0.0f; }
                     };
-                    if constexpr (ONE) {
-                        // A block is one batch.  The pairs of a refill are worked off in runs whose documents stay the
-                        // same (a document's tasks are consecutive): the run's theta values are loaded once, into one
-                        // set of registers, and the phi loads of kScanDepth - 1 pairs are in flight while a pair is
-                        // summed.  The loop is laid out so that the number of loads issued after those a sum waits
-                        // for is the same on every path that reaches it: the wait then lets the younger loads fly.
-                        constexpr int N = kScanDepth;
+                    // Blocks of one batch, or of two (K = 1024).  The new tasks of a refill are worked off in runs whose
+                    // document stays the same (a document's tasks are consecutive): the run's theta values are loaded once,
+                    // one set of registers per batch, and the phi loads of the next batch are in flight while a batch is
+                    // summed, in two sets used in turn (with two batches per block a set always holds the same batch).
+                    // The loop has the same number of loads behind every sum on every path that reaches it: the
+                    // compiler's wait then lets the younger loads fly.
+                    auto pipeline = [&](auto batches) {
+                        constexpr int NB = decltype(batches)::value;   // batches per block: 1 or 2
+                        constexpr int N = 2;                       // sets of phi registers
                         constexpr int kStep = COAL ? 128 : 4;      // topics between two loads of a lane
-                        const int kb = COAL ? 4 * hl : k0;
-                        float4 pv[N][TB > 0 ? TB : 1], tv[TB > 0 ? TB : 1];
+                        constexpr int kBatch = COAL ? 128 * TB : 4 * TB;   // topics between two batches of a lane
+                        const int kb0 = COAL ? 4 * hl : k0;
+                        float4 pv[N][TB > 0 ? TB : 1], tv[NB][TB > 0 ? TB : 1];
                         int srcs[N];
                         int32_t held = -1;                         // the document whose theta values tv holds
-                        // The next run: the leading new lanes whose document is that of the first one, taken in pairs
-                        // (one lane per half-wave; a last lane alone is its own partner).  Its pairs are inside one
-                        // document, so every lane needs the same piece of one theta row for all of them.
+                        int src_cur = 0;
+                        const float* __restrict__ row_cur = a.phi; // the phi row of the pair whose batches are being issued
                         auto lane_of = [&](uint64_t m) { return __ffsll((unsigned long long)m) - 1; };
                         auto of_lane = [&](int32_t v, int l0, int l1) {    // v of lane l0 (first half-wave) or l1 (second)
                             const int32_t va = __builtin_amdgcn_readlane(v, l0), vb = __builtin_amdgcn_readlane(v, l1);
                             return half ? vb : va;
                         };
-                        auto issue_phi = [&](float4* p, int& src) {    // takes the next pair of the run
-                            const int l0 = lane_of(fresh);
-                            fresh &= fresh - 1;
-                            const int l1 = fresh ? lane_of(fresh) : l0;
-                            fresh &= fresh - 1;
-                            src = half ? l1 : l0;
-                            const float* __restrict__ pp = a.phi + (size_t)of_lane(w, l0, l1) * K + kb;
+                        // batch i % NB of pair i / NB of the run goes to set i % N: with N = 2 and NB = 1 or 2 the batch
+                        // of a set is known at compile time (j % NB)
+                        auto issue_phi = [&](float4* p, int& src, int bt) {
+                            if (bt == 0) {                         // the next pair of the run
+                                const int l0 = lane_of(fresh);
+                                fresh &= fresh - 1;
+                                const int l1 = fresh ? lane_of(fresh) : l0;
+                                fresh &= fresh - 1;
+                                src_cur = half ? l1 : l0;
+                                row_cur = a.phi + (size_t)of_lane(w, l0, l1) * K;
+                            }
+                            src = src_cur;
+                            const int kb = kb0 + kBatch * bt;
 #pragma unroll
                             for (int c = 0; c < TB; ++c)
-                                p[c] = (WHOLE || kb + 4 * c < K) ? *reinterpret_cast<const float4*>(pp + kStep * c)
+                                p[c] = (WHOLE || kb + 4 * c < K) ? *reinterpret_cast<const float4*>(row_cur + kb + kStep * c)
                                                                   : make_float4(0.f, 0.f, 0.f, 0.f);
                         };
-                        auto sum_pair = [&](const float4* p, int src) {
-                            Item it{src, 0, true, true};
-                            consume(p, tv, it);
+                        auto sum_batch = [&](const float4* p, int src, int bt) {
+                            Item it{src, bt, bt == NB - 1, true};
+                            consume(p, tv[bt], it);
                         };
                         while (fresh) {
                             const int32_t doc = __builtin_amdgcn_readlane(d, lane_of(fresh));
                             const uint64_t other = fresh & ~__ballot(d == doc);
                             const uint64_t lead = other ? fresh & ((other & (~other + 1ull)) - 1ull) : fresh;
                             const int lanes_in = (int)__popcll((unsigned long long)lead);
-                            // pairs inside the document; a lane left over pairs with the first lane of the next document
-                            // only when nothing else is left of this one: it is then scanned alone, as its own partner
-                            int P = lanes_in / 2;
+                            // pairs inside the document; a lane left over is scanned alone, as its own partner, when
+                            // nothing else of its document is left
+                            int pairs = lanes_in / 2;
                             uint64_t rest = 0;                     // new lanes set aside while this run is scanned
-                            if (P == 0) { P = 1; rest = fresh & (fresh - 1); fresh &= ~rest; }
-                            else { rest = fresh & ~lead; if (lanes_in & 1) rest |= 1ull << (63 - __clzll((unsigned long long)lead)); fresh &= ~rest; }
+                            if (pairs == 0) { pairs = 1; rest = fresh & (fresh - 1); fresh &= ~rest; }
+                            else {
+                                rest = fresh & ~lead;
+                                if (lanes_in & 1) rest |= 1ull << (63 - __clzll((unsigned long long)lead));
+                                fresh &= ~rest;
+                            }
+                            const int P = pairs * NB;              // batches of the run
                             if (doc != held) {
-                                const float* __restrict__ tp = a.theta + (size_t)doc * K + kb;
+                                const float* __restrict__ tp = a.theta + (size_t)doc * K;
 #pragma unroll
-                                for (int c = 0; c < TB; ++c)
-                                    tv[c] = (WHOLE || kb + 4 * c < K) ? *reinterpret_cast<const float4*>(tp + kStep * c)
-                                                                       : make_float4(0.f, 0.f, 0.f, 0.f);
+                                for (int bt = 0; bt < NB; ++bt)
+#pragma unroll
+                                    for (int c = 0; c < TB; ++c) {
+                                        const int kb = kb0 + kBatch * bt;
+                                        tv[bt][c] = (WHOLE || kb + 4 * c < K) ? *reinterpret_cast<const float4*>(tp + kb + kStep * c)
+                                                                               : make_float4(0.f, 0.f, 0.f, 0.f);
+                                    }
                                 held = doc;
                             }
+                            issue_phi(pv[0], srcs[0], 0);          // P >= 1
+                            int issued = 1;
+                            while (P - issued >= N) {              // whole rounds: every sum has the loads of one batch behind it
 #pragma unroll
-                            for (int j = 0; j < N - 1; ++j) if (j < P) issue_phi(pv[j], srcs[j]);
-                            if (P < N - 1) {                       // a short run
-#pragma unroll
-                                for (int j = 0; j < N - 1; ++j) if (j < P) sum_pair(pv[j], srcs[j]);
-                            } else {
-                                int issued = N - 1;
-                                while (P - issued >= N) {          // whole rounds: every sum has the loads of N - 1 pairs behind it
-#pragma unroll
-                                    for (int j = 0; j < N; ++j) {
-                                        issue_phi(pv[(j + N - 1) % N], srcs[(j + N - 1) % N]);
-                                        __builtin_amdgcn_sched_barrier(0);     // the loads first, then the sum that waits
-                                        sum_pair(pv[j], srcs[j]);
-                                        __builtin_amdgcn_sched_barrier(0);
-                                    }
-                                    issued += N;
+                                for (int j = 0; j < N; ++j) {
+                                    issue_phi(pv[(j + 1) % N], srcs[(j + 1) % N], (j + 1) % NB);
+                                    __builtin_amdgcn_sched_barrier(0);     // the loads first, then the sum that waits
+                                    sum_batch(pv[j], srcs[j], j % NB);
+                                    __builtin_amdgcn_sched_barrier(0);
                                 }
-                                const int r = P - issued;          // 0 .. N - 1 pairs not yet issued
-#pragma unroll
-                                for (int t = 0; t < N - 1; ++t)
-                                    if (t < r) { issue_phi(pv[(t + N - 1) % N], srcs[(t + N - 1) % N]); sum_pair(pv[t], srcs[t]); }
-#pragma unroll
-                                for (int t = 0; t < 2 * N - 2; ++t)
-                                    if (t >= r && t < r + N - 1) sum_pair(pv[t % N], srcs[t % N]);
+                                issued += N;
+                            }
+                            if (P - issued == 1) {                 // one batch not yet issued: it goes to set 1
+                                issue_phi(pv[1], srcs[1], 1 % NB);
+                                sum_batch(pv[0], srcs[0], 0);
+                                sum_batch(pv[1], srcs[1], 1 % NB);
+                            } else {
+                                sum_batch(pv[0], srcs[0], 0);
                             }
                             fresh = rest;
                         }
+                    };
+                    if constexpr (ONE) {
+                        pipeline(std::integral_constant<int, 1>{});
                         return;
+                    } else if constexpr (TB == 4) {
+                        if (nb == 2) {
+                            pipeline(std::integral_constant<int, 2>{});
+                            return;
+                        }
                     }
                     float4 pa[TB > 0 ? TB : 1], ta[TB > 0 ? TB : 1], pb[TB > 0 ? TB : 1], tb[TB > 0 ? TB : 1];
                     Item cur{0, 0, false, false};
