@@ -77,7 +77,8 @@ __global__ __launch_bounds__(256) void vb_exp_elog_beta_kernel(const float* __re
 
 // One wave per document, lanes across topics (lane l owns topics 256 c + 4 l .. + 3 of chunk c: a row of b is read
 // with 16-byte loads, 1 KB per instruction), K a multiple of 4 and at most 256 CH.  The document's gamma, a and the
-// sums over its nonzeros stay in registers over all iterations; two nonzeros are in flight at a time.
+// sums over its nonzeros stay in registers over all iterations; two nonzeros are in flight at a time (up to 256
+// topics: four, and the next four behind them).
 template <int CH>
 __global__ __launch_bounds__(256) void vb_estep_kernel(const int32_t* __restrict__ colptr, const int32_t* __restrict__ rowidx,
                                                        const float* __restrict__ val, int32_t D, int K,
@@ -115,6 +116,70 @@ __global__ __launch_bounds__(256) void vb_estep_kernel(const int32_t* __restrict
             a[c].w = in ? (float)exp(digamma_d(g[c][3]) - ps) : 0.f;
             acc[c][0] = 0.0; acc[c][1] = 0.0; acc[c][2] = 0.0; acc[c][3] = 0.0;
         }
+        if constexpr (CH == 1) {
+            // Up to 256 topics: kR nonzeros per round, and the rows of the next round are loaded while this round is
+            // worked off (their word ids were loaded a round earlier still).  Every round issues the same loads,
+            // past the document's end with the index of its last nonzero and a count of zero, so that the number of
+            // loads in flight behind the ones a round waits for is fixed and the wait lets them fly.
+            constexpr int kR = 2;                                  // nonzeros per round (even; four cost 171 registers and half the waves)
+            const int k = 4 * lane;
+            const bool in = k < K;
+            const int64_t last = hi - 1;
+            auto ids = [&](int64_t i0, int32_t (&wv)[kR], float (&cv)[kR]) {
+#pragma unroll
+                for (int j = 0; j < kR; ++j) {
+                    const int64_t i = i0 + j;
+                    const int64_t ic = i < hi ? i : last;
+                    wv[j] = rowidx[ic];
+                    cv[j] = i < hi ? val[ic] : 0.f;
+                }
+            };
+            auto rows = [&](const int32_t (&wv)[kR], float4 (&bv)[kR]) {
+#pragma unroll
+                for (int j = 0; j < kR; ++j)
+                    bv[j] = in ? *reinterpret_cast<const float4*>(b + (size_t)wv[j] * K + k) : make_float4(0.f, 0.f, 0.f, 0.f);
+            };
+            if (lo < hi) {
+                int32_t w[kR], nw[kR];
+                float cnt[kR], ncnt[kR];
+                float4 bv[kR], nbv[kR];
+                ids(lo, w, cnt);
+                ids(lo + kR, nw, ncnt);
+                rows(w, bv);
+                for (int64_t i = lo; i < hi; i += kR) {
+                    int32_t nnw[kR];
+                    float nncnt[kR];
+                    rows(nw, nbv);
+                    ids(i + 2 * kR, nnw, nncnt);
+                    __builtin_amdgcn_sched_barrier(0);             // the next round's loads first, then this round's work
+                    float m[kR];
+                    double r[kR];
+#pragma unroll
+                    for (int j = 0; j < kR; ++j) {
+                        float sj = 0.f;
+                        sj = __builtin_fmaf(a[0].x, bv[j].x, sj); sj = __builtin_fmaf(a[0].y, bv[j].y, sj);
+                        sj = __builtin_fmaf(a[0].z, bv[j].z, sj); sj = __builtin_fmaf(a[0].w, bv[j].w, sj);
+                        m[j] = wave_sum(sj);
+                        r[j] = cnt[j] > 0.f ? (double)cnt[j] / (double)m[j] : 0.0;
+                    }
+#pragma unroll
+                    for (int j = 0; j < kR; j += 2) {               // pairs of nonzeros, as in the loop for more topics
+                        acc[0][0] = __builtin_fma(r[j], (double)bv[j].x, __builtin_fma(r[j + 1], (double)bv[j + 1].x, acc[0][0]));
+                        acc[0][1] = __builtin_fma(r[j], (double)bv[j].y, __builtin_fma(r[j + 1], (double)bv[j + 1].y, acc[0][1]));
+                        acc[0][2] = __builtin_fma(r[j], (double)bv[j].z, __builtin_fma(r[j + 1], (double)bv[j + 1].z, acc[0][2]));
+                        acc[0][3] = __builtin_fma(r[j], (double)bv[j].w, __builtin_fma(r[j + 1], (double)bv[j + 1].w, acc[0][3]));
+                    }
+                    if (log_mu_out != nullptr && it == iters - 1 && lane == 0) {
+#pragma unroll
+                        for (int j = 0; j < kR; ++j)
+                            if (i + j < hi) log_mu_out[i + j] = logf(m[j]) + (shift ? shift[w[j]] : 0.f);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int j = 0; j < kR; ++j) { bv[j] = nbv[j]; w[j] = nw[j]; cnt[j] = ncnt[j]; nw[j] = nnw[j]; ncnt[j] = nncnt[j]; }
+                }
+            }
+        } else
         for (int64_t i = lo; i < hi; i += 2) {
             const bool two = i + 1 < hi;
             const int32_t w0 = rowidx[i], w1 = two ? rowidx[i + 1] : w0;
