@@ -1059,7 +1059,10 @@ int same_lda_sddmm(same_lda_t* h, float* mu_out, int32_t out_on_device)
         else { HIP_TRY(h, hipEventCreate(&ev.first)); HIP_TRY(h, hipEventCreate(&ev.second)); }
         HIP_TRY(h, hipEventRecord(ev.first, h->stream));
     }
-    if (h->K % 4 == 0)
+    if (h->K % 4 == 0 && h->K <= 256)
+        hipLaunchKernelGGL(same::sddmm_small_kernel, dim3((unsigned)blocks), dim3(64 * waves_per_block), 0, h->stream,
+                           M.nz_doc, M.rowidx, M.nnz, h->K, M.theta, h->phi, dst);
+    else if (h->K % 4 == 0)
         hipLaunchKernelGGL(same::sddmm_kernel<true>, dim3((unsigned)blocks), dim3(64 * waves_per_block), 0, h->stream,
                            M.nz_doc, M.rowidx, M.nnz, h->K, M.theta, h->phi, dst);
     else

@@ -234,4 +234,62 @@ __global__ __launch_bounds__(256) void sddmm_kernel(const int32_t* __restrict__ 
     }
 }
 
+// K a multiple of 4 and at most 256: a row is one 16-byte load per lane.  The wave reads the ids of its
+// kSddmmChunk nonzeros with one load (lane l those of nonzero l), then goes through them four at a time with
+// the eight row loads of the next four in flight; every round issues the same loads (past the end of the matrix
+// those of its last nonzero), so that the wait before a round's sums has a fixed number of younger loads behind it.
+__global__ __launch_bounds__(256) void sddmm_small_kernel(const int32_t* __restrict__ nz_doc,
+                                                          const int32_t* __restrict__ rowidx, int64_t nnz, int K,
+                                                          const float* __restrict__ theta, const float* __restrict__ phi,
+                                                          float* __restrict__ mu)
+{
+    static_assert(kSddmmChunk <= 64 && kSddmmChunk % 4 == 0, "one id per lane, rounds of four");
+    const int lane = threadIdx.x & 63;
+    const int64_t wave = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    const int64_t i0 = wave * kSddmmChunk;
+    if (i0 >= nnz) return;                                         // the whole wave
+    const int64_t mine = i0 + lane < nnz ? i0 + lane : nnz - 1;
+    const int32_t my_d = nz_doc[mine], my_w = rowidx[mine];
+    const int k = 4 * lane;
+    const bool in = k < K;
+    auto rows = [&](int r, float4 (&t)[4], float4 (&p)[4]) {      // the rows of round r (nonzeros 4r .. 4r+3 of the chunk)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int src = (4 * r + j) & (kSddmmChunk - 1);
+            const int32_t dd = __builtin_amdgcn_readlane(my_d, src), ww = __builtin_amdgcn_readlane(my_w, src);
+            t[j] = in ? *reinterpret_cast<const float4*>(theta + (size_t)dd * K + k) : make_float4(0.f, 0.f, 0.f, 0.f);
+            p[j] = in ? *reinterpret_cast<const float4*>(phi + (size_t)ww * K + k) : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+    };
+    auto sums = [&](int r, const float4 (&t)[4], const float4 (&p)[4]) {
+        float total[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            float acc = 0.f;
+            acc = __builtin_fmaf(t[j].x, p[j].x, acc);
+            acc = __builtin_fmaf(t[j].y, p[j].y, acc);
+            acc = __builtin_fmaf(t[j].z, p[j].z, acc);
+            acc = __builtin_fmaf(t[j].w, p[j].w, acc);
+            total[j] = wave_sum(acc);
+        }
+        const int64_t i = i0 + 4 * r + lane;                       // lanes 0..3 write the round's four values
+        const float v = lane == 0 ? total[0] : lane == 1 ? total[1] : lane == 2 ? total[2] : total[3];
+        if (lane < 4 && i < nnz) mu[i] = v;
+    };
+    float4 ta[4], pa[4], tb[4], pb[4];
+    rows(0, ta, pa);
+    static_assert((kSddmmChunk / 4) % 2 == 0, "rounds in pairs");
+#pragma unroll 1
+    for (int r = 0; r < kSddmmChunk / 4; r += 2) {
+        rows(r + 1, tb, pb);
+        __builtin_amdgcn_sched_barrier(0);
+        sums(r, ta, pa);
+        __builtin_amdgcn_sched_barrier(0);
+        rows(r + 2, ta, pa);                                       // the last one wraps to round 0: loaded, not used
+        __builtin_amdgcn_sched_barrier(0);
+        sums(r + 1, tb, pb);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
 }  // namespace same
