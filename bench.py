@@ -263,7 +263,7 @@ def sddmm_bench(args):
         "config": {"workload": f"{args.workload} (LDA-generated, scale {args.scale})", "D": st["D"], "V": st["V"], "K": K,
                    "nnz": st["nnz"]},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel": "sddmm_kernel",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel": "sddmm_small_kernel" if (K % 4 == 0 and K <= 256) else "sddmm_kernel",
                      "kernel_ms": kernel_ms / launches, "bytes_per_launch": bytes_per_launch}}))
 
 
