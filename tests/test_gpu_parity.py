@@ -607,6 +607,24 @@ def test_sddmm_against_double_oracle(K):
     g.close()
 
 
+@pytest.mark.parametrize("nnz", [1, 5, 31, 32, 33, 64, 97])
+def test_sddmm_few_nonzeros(nnz):
+    """Fewer nonzeros than a wave's chunk of 32, exactly one and two chunks, and ragged ends (the kernel for up to 256
+    topics loads the ids of a chunk with one instruction and the rows of every round of four unconditionally)."""
+    rng = np.random.default_rng(nnz)
+    D, V, K = 4, 200, 64
+    per = np.full(D, nnz // D); per[: nnz % D] += 1
+    colptr = np.concatenate([[0], np.cumsum(per)]).astype(np.int32)
+    rowidx = np.concatenate([np.sort(rng.choice(V, size=int(n), replace=False)) for n in per]).astype(np.int32)
+    val = rng.integers(1, 4, size=nnz).astype(np.float32)
+    X = oracle.CSC(D, V, colptr, rowidx, val)
+    o = oracle.OracleLDA(X, K, 0.3, 0.02, seed=3, m0=4, G=8)
+    g = make_gpu(X, K, 0.3, 0.02, 3, 4, 8)
+    o.sweep(5); g.sweep(5)
+    np.testing.assert_allclose(g.sddmm(), oracle.sddmm(X, o.theta, o.phi), rtol=1e-5, atol=0)
+    g.close()
+
+
 def test_sddmm_empty_matrix():
     X = oracle.CSC(3, 10, np.zeros(4, np.int32), np.zeros(0, np.int32), np.zeros(0, np.float32))
     g = make_gpu(X, 4, 0.1, 0.01, 1, 5, 8)
