@@ -222,8 +222,9 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(TB <= 2 ?
             };
             if (VEC && TB > 0) {
                 // Where every block is whole (K = 32 T: 256 at T = 8) the loads need no bounds.  Blocks of one batch
-                // (ONE) go through the pipeline at the top of run(); blocks of several batches load the next batch
-                // into a second set of registers before the current one is summed.
+                // (ONE) and of two batches of four loads go through the pipeline in run(); blocks of other shapes load
+                // the next batch into a second set of registers before the current one is summed (the load there sits
+                // under a condition, and the compiler's wait then covers it too: no overlap, rare shapes).
                 struct Item { int src, b; bool last, valid; };
                 auto advance = [&](Item& it) {                     // the next (pair of tasks, batch) of this refill
                     if (it.valid && !it.last) { it.b += 1; it.last = it.b == nb - 1; return; }
