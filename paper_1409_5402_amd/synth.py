@@ -169,6 +169,9 @@ PRESETS = {
     "news_k1024": dict(gen=dict(D=300_000, V=100_000, K=256, alpha=50.0 / 256, beta=0.01, seed=2,
                                 length="lognormal", mean_len=330.0, sigma=0.6, zipf_s=1.1),
                        K=1024, m=100, sweeps=50, alpha=50.0 / 1024, beta=0.01),
+    "news_k512": dict(gen=dict(D=300_000, V=100_000, K=256, alpha=50.0 / 256, beta=0.01, seed=2,
+                               length="lognormal", mean_len=330.0, sigma=0.6, zipf_s=1.1),
+                      K=512, m=100, sweeps=50, alpha=50.0 / 512, beta=0.01),
     # abstract-collection shape, one resident minibatch of 100k documents
     "abstracts_batch": dict(gen=dict(D=100_000, V=140_000, K=256, alpha=0.1, beta=0.01, seed=4,
                                      length="poisson", mean_len=90.0, zipf_s=1.05),
