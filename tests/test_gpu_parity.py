@@ -607,6 +607,27 @@ def test_sddmm_against_double_oracle(K):
     g.close()
 
 
+@pytest.mark.parametrize("K", [16, 64, 256, 512, 1024])
+def test_short_documents_every_scan_shape(K):
+    """Documents of one to three words, some empty: a refill's new tasks then change document every lane or two, so the
+    scan's runs inside one document are one or two lanes long, with single lanes left over (the pipeline's prologue,
+    tail and lone-lane cases, for blocks of one batch, of two, and for the scan in contiguous pieces)."""
+    rng = np.random.default_rng(K)
+    D, V = 700, 60
+    per = rng.integers(0, 4, size=D)
+    colptr = np.concatenate([[0], np.cumsum(per)]).astype(np.int32)
+    rowidx = np.concatenate([np.sort(rng.choice(V, size=int(n), replace=False)) for n in per] + [np.zeros(0, np.int64)]).astype(np.int32)
+    val = rng.integers(1, 6, size=int(per.sum())).astype(np.float32)
+    X = oracle.CSC(D, V, colptr, rowidx, val)
+    o = oracle.OracleLDA(X, K, 0.2, 0.05, seed=11, m0=3, G=8)
+    g = make_gpu(X, K, 0.2, 0.05, 11, 3, 8)
+    assert_state_equal(g, o, "after init")
+    for t, m in enumerate([1, 7, 40]):
+        o.sweep(m); g.sweep(m)
+        assert_state_equal(g, o, f"sweep {t} (m={m})")
+    g.close()
+
+
 @pytest.mark.parametrize("nnz", [1, 5, 31, 32, 33, 64, 97])
 def test_sddmm_few_nonzeros(nnz):
     """Fewer nonzeros than a wave's chunk of 32, exactly one and two chunks, and ragged ends (the kernel for up to 256
