@@ -185,7 +185,8 @@ __global__ void hot_fold_kernel(uint32_t* __restrict__ nwk, const int32_t* __res
 // quad picked by its index: tasks of one word have their large counts at the same topics in the same places
 // of their slots, and aligned walks would meet at one address.
 constexpr int kReduceChunk = 2048;
-constexpr int kSlotMinTasks = 32;
+constexpr int kSlotMinTasks = 2;         // (32 measured 1.5 % slower on the resident matrix and 5 % on a minibatch: the direct
+                                        // updates of rare words are atomics on lines that have long left the cache)
 constexpr int kReduceThreads = 1024;    // two slots per thread: the kernel waits on its loads, many waves hide that
 
 __global__ __launch_bounds__(kReduceThreads) void word_reduce_kernel(const uint32_t* __restrict__ pairs,
