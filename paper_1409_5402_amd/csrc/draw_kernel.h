@@ -200,7 +200,19 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(TB <= 2 ?
                 const int free_row = used0 == 0 ? 0 : ((n_rows > 1 && used1 == 0) ? 1 : -1);
                 int dn = (take && myrow < 0) ? d : 0x7FFFFFFF;         // the lowest new document without a row
                 for (int o = 32; o > 0; o >>= 1) dn = min(dn, __shfl_xor(dn, o));
-                if (free_row < 0 || dn == 0x7FFFFFFF) break;
+                if (dn == 0x7FFFFFFF) break;
+                if (free_row < 0) {
+                    // one row (n_rows == 1) in use: it goes to the new document if that one now has more lanes than
+                    // the row's document has left; the lanes that stay behind add to the matrix directly from here on
+                    if (n_rows != 1) break;
+                    const int n_new = (int)__popcll((unsigned long long)__ballot(take && myrow < 0 && d == dn));
+                    if (n_new <= (int)__popcll((unsigned long long)used0)) break;
+                    flush_row(0, tag0);
+                    if (myrow == 0) myrow = -1;
+                    tag0 = dn;
+                    if (take && d == dn) myrow = 0;
+                    break;
+                }
                 const int old = free_row == 0 ? tag0 : tag1;
                 if (old >= 0) flush_row(free_row, old);
                 if (free_row == 0) tag0 = dn; else tag1 = dn;
